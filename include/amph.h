@@ -1,0 +1,187 @@
+/*
+ * amph.h -- C ABI of libamph: the hot path of one Amphista speculate-and-verify decode step
+ * (arXiv 2406.13170) on one MI355X (gfx950).
+ *
+ * Conventions
+ *   - Every function returns amph_status (0 = OK).  Argument checks run on the host and are
+ *     synchronous; all device work is enqueued on the context's stream and returns at once.  No call
+ *     synchronises the stream or reads device memory on the host unless its comment says so.
+ *   - Unless marked "host", every pointer is a DEVICE pointer owned by the caller; the library never
+ *     frees or reallocates caller memory.  The library owns amph_ctx (a few KB of device counters)
+ *     and amph_tree (host tables plus device copies), released by their _destroy calls.
+ *   - Layouts are dense row-major in the order written, last index fastest.  "T" below is the
+ *     configuration's storage type: float for AMPH_F32, bfloat16 (16-bit patterns) for AMPH_BF16.
+ *     Weights are [out_features, in_features].  Accumulation is always float32.
+ *   - Quantities that only the device knows (kv_len, sal_len) are range-checked inside the kernels:
+ *     a violation sets a sticky device flag, the offending call writes no output for that batch
+ *     element, and amph_device_status() reports it.
+ *   - Paper references: Sec. 3.1 Eq. 1 (staged adaptation layers), Sec. 3.2 Eq. 2-6 (auto-embedding
+ *     block, LM head, top-k), Sec. 2 "Tree Attention" and Appendix "Draft Tree" (tree, mask,
+ *     verification), Sec. 2 "Speculative Decoding" and Table 1 (greedy acceptance).
+ */
+#ifndef AMPH_H
+#define AMPH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AMPH_OK = 0,
+  AMPH_EINVAL = 1,  /* null pointer, negative size, unsupported value           */
+  AMPH_ESHAPE = 2,  /* dimensions inconsistent or beyond a documented limit      */
+  AMPH_ETREE = 3,   /* malformed topology (missing parent, duplicate, too deep)  */
+  AMPH_EHIP = 4     /* HIP runtime error; text via amph_last_error               */
+} amph_status;
+
+enum { AMPH_F32 = 0, AMPH_BF16 = 1 };
+
+enum { AMPH_MAX_TREE = 128, AMPH_MAX_TOPK = 16, AMPH_MAX_HEADS_K = 8 };
+
+/* bits of the device status word (amph_device_status) */
+enum { AMPH_DEV_SAL_OVERFLOW = 1, AMPH_DEV_KV_OVERFLOW = 2, AMPH_DEV_BAD_TOKEN = 4 };
+
+typedef struct amph_config {
+  int32_t d_model, n_heads, head_dim; /* d_model = n_heads * head_dim; head_dim is 64 or 128        */
+  int32_t d_ffn, vocab;
+  int32_t K;                 /* drafting heads, 1..AMPH_MAX_HEADS_K                                */
+  int32_t topk;              /* per-head candidates, 1..AMPH_MAX_TOPK                              */
+  int32_t max_tree;          /* largest tree (nodes incl. root) used with this context, <= 128     */
+  int32_t max_kv;            /* rows of every KV cache; multiple of 32                             */
+  int32_t batch;             /* independent sequences per call                                     */
+  int32_t dtype;             /* AMPH_F32 | AMPH_BF16                                               */
+  float rms_eps;             /* RMSNorm epsilon                                                    */
+  float rope_theta;          /* RoPE base; pairs are (i, i + head_dim/2)                           */
+} amph_config;
+
+/* One Llama-style decoder layer (pre-RMSNorm, RoPE, SwiGLU, no biases); all T. */
+typedef struct amph_layer_w {
+  const void *rms1;                 /* [d]     */
+  const void *wq, *wk, *wv, *wo;    /* [d, d]  */
+  const void *rms2;                 /* [d]     */
+  const void *w_gate, *w_up;        /* [f, d]  */
+  const void *w_down;               /* [d, f]  */
+} amph_layer_w;
+
+/* Weights of the draft module (host struct of device pointers; all T). */
+typedef struct amph_draft_w {
+  const void *embed;        /* [V, d]  target's embedding table: e_{t+1} (Sec. 3.1)                */
+  const void *fc[2];        /* [d, 2d] fc^1, fc^2 of Eq. 1; columns [0,d) act on h, [d,2d) on e     */
+  amph_layer_w sal[2];      /* SAL^1, SAL^2 of Eq. 1                                                */
+  const void *mlp;          /* [K, d, d] MLP_k of Eq. 2, used as h + SiLU(W_k h)                    */
+  const void *pe;           /* [K, d]  positional embedding of Eq. 4                                */
+  const void *aeb_wq, *aeb_wk, *aeb_wv, *aeb_wo; /* [d, d] self-attention of Eq. 5                  */
+  const void *lm_head;      /* [V, d]  LM head of Eq. 6, shared by the K positions                  */
+} amph_draft_w;
+
+typedef struct amph_ctx amph_ctx;
+typedef struct amph_tree amph_tree;
+
+/* ---- context --------------------------------------------------------------------------------- */
+/* Validates cfg (host pointer), allocates the context's device counters.  *out is NULL on failure. */
+amph_status amph_create(const amph_config *cfg, amph_ctx **out);
+void amph_destroy(amph_ctx *ctx);
+/* hip_stream is a hipStream_t (NULL = the default stream).  The caller keeps it alive. */
+amph_status amph_set_stream(amph_ctx *ctx, void *hip_stream);
+/* Bytes of caller-provided scratch every call below needs (256-byte aligned). */
+size_t amph_workspace_bytes(const amph_ctx *ctx);
+/* Host string describing the last failure on this context (never NULL). */
+const char *amph_last_error(const amph_ctx *ctx);
+/* SYNCHRONISES the stream, copies the sticky device status word to *host_bits and clears it. */
+amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits);
+
+/* ---- A1-A5: draft (Sec. 3.1 Eq. 1, Sec. 3.2 Eq. 2-6) ------------------------------------------
+ * For each batch element b: e = embed[tok_new[b]]; x1 = fc1 [h_new[b]; e]; h1 = SAL1(x1);
+ * x2 = fc2 [h1; e]; h2 = SAL2(x2); H_p[k] = MLP_k(h1 or h2) + PE[k] (heads 1..floor(K/2) read h1);
+ * attn_o = bi-directional multi-head self-attention over the K rows; logits[k] = lm_head attn_o[k];
+ * top-k per row, sorted by descending logit, ties to the lower token id.
+ *   h_new    [B, n_new, d] float32     tok_new [B, n_new] int32     n_new must be 1
+ *   sal_kv   [2 stages, B, 2 (K then V), n_heads, max_kv, head_dim] T; row sal_len[b] of both stages
+ *            is written (keys after RoPE at position sal_len[b]) and attended together with rows below it
+ *   sal_len  [B] int32, read on the device and advanced by n_new when the call completes
+ *   topk_idx [B, K, topk] int32        topk_val [B, K, topk] float32
+ *   logits   [B, K, V] float32 or NULL (then the logits live only in the workspace)
+ * Device-side errors: sal_len[b] + 1 > max_kv (AMPH_DEV_SAL_OVERFLOW), token id outside [0, V). */
+amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w /* host */, const float *h_new,
+                       const int32_t *tok_new, int n_new, void *sal_kv, int32_t *sal_len,
+                       int32_t *topk_idx, float *topk_val, float *logits, void *workspace);
+
+/* ---- draft tree (Appendix "Draft Tree") -------------------------------------------------------
+ * paths: host array [n, K] of top-k ranks, -1 padded; one row per non-root node, any order; the
+ * root (the token the target just sampled) is implicit.  Nodes are numbered root first, then by
+ * (depth, rank path).  Fails with AMPH_ETREE on a missing parent, a duplicate or a path longer
+ * than K, AMPH_ESHAPE if n + 1 > AMPH_MAX_TREE or a rank >= AMPH_MAX_TOPK. */
+amph_status amph_tree_create(const int32_t *paths /* host */, int n, int K, amph_tree **out);
+void amph_tree_destroy(amph_tree *tree);
+/* Host views valid until amph_tree_destroy; any output pointer may be NULL.
+ *   parent, depth, rank [T] (root: -1, 0, -1);  mask_bits [T, 2]: bit j of row i set iff node j is
+ *   node i or one of its ancestors;  retrieve [n_leaves, K+1] node ids root..leaf, -1 padded. */
+amph_status amph_tree_info(const amph_tree *tree, int *T, int *n_leaves, const int32_t **parent,
+                           const int32_t **depth, const int32_t **rank, const uint64_t **mask_bits,
+                           const int32_t **retrieve);
+
+/* ---- A6: candidate-tree construction -----------------------------------------------------------
+ * tree_tok[b, i] = root_tok[b] for the root, else topk_idx[b, depth_i - 1, rank_i];
+ * tree_pos[b, i] = kv_len[b] + depth_i.
+ *   root_tok [B] int32   topk_idx [B, K, topk] int32   kv_len [B] int32   tree_tok, tree_pos [B, T] */
+amph_status amph_tree_build(amph_ctx *ctx, const amph_tree *tree, const int32_t *root_tok,
+                            const int32_t *topk_idx, const int32_t *kv_len, int32_t *tree_tok,
+                            int32_t *tree_pos);
+
+/* ---- A8: tree-masked verification attention (Sec. 2 "Tree Attention") ---------------------------
+ * out[b, i, h] = sum_j softmax_j(q[b,i,h] . k_j / sqrt(head_dim)) v_j over all committed rows
+ * j < kv_len[b] and the tree rows kv_len[b] + j' with j' = i or an ancestor of i.
+ *   q, out  [B, T, n_heads, head_dim] T
+ *   k_cache [B, n_heads, max_kv, head_dim] T   keys (already rotated); tree keys at rows
+ *           [kv_len[b], kv_len[b] + T) in node order
+ *   v_cache [B, n_heads, head_dim, max_kv] T   values stored dimension-major (transposed) so that a
+ *           16-byte load yields consecutive rows of one dimension; same row numbering as k_cache
+ * Device-side error: kv_len[b] + T > max_kv (AMPH_DEV_KV_OVERFLOW). */
+amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache,
+                             const void *v_cache, const int32_t *kv_len, void *out, void *workspace);
+
+/* ---- A10: greedy longest-accepted-prefix (Sec. 2 "Speculative Decoding"; Table 1, Temperature 0)
+ * ok[root] = 1; ok[i] = ok[parent_i] and tree_tok[i] == tgt[parent_i]; best = deepest ok node
+ * (lowest node id among equals); accept_len = depth(best); next_tok = tgt[best];
+ * accept_path = node ids root..best, -1 padded.
+ * Exactly one of tgt_argmax [B, T] int32 and tgt_logits [B, T, V] float32 is non-NULL; with logits
+ * the per-node argmax (ties to the lowest id) is taken inside.
+ *   accept_len, next_tok, best_node [B] int32     accept_path [B, K+1] int32 */
+amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok,
+                        const int32_t *tgt_argmax, const float *tgt_logits, int32_t *accept_len,
+                        int32_t *accept_path, int32_t *next_tok, int32_t *best_node, void *workspace);
+
+/* ---- A7 + A8 + A9: the target's forward pass over the tree tokens -------------------------------
+ * x = embed[tree_tok]; for every layer: RMSNorm, Q/K/V projections, RoPE at tree_pos, K/V written to
+ * cache rows [kv_len, kv_len + T), tree attention (as amph_verify_attn), output projection and
+ * residual, RMSNorm, SwiGLU FFN and residual; then the final RMSNorm, the LM head and the per-node
+ * argmax (ties to the lowest id).
+ *   layers     host array [n_layers] of device-pointer structs
+ *   k_caches   [n_layers, B, n_heads, max_kv, head_dim] T
+ *   v_caches   [n_layers, B, n_heads, head_dim, max_kv] T (dimension-major, see amph_verify_attn)
+ *   hidden_out [B, T, d] float32 (final-normed hidden states) or NULL
+ *   logits_out [B, T, V] float32 or NULL
+ *   tgt_argmax [B, T] int32 */
+amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers /* host */,
+                                int n_layers, const void *embed, const void *final_norm,
+                                const void *lm_head, const int32_t *tree_tok, const int32_t *tree_pos,
+                                void *k_caches, void *v_caches, const int32_t *kv_len, float *hidden_out,
+                                float *logits_out, int32_t *tgt_argmax, void *workspace);
+
+/* ---- single linear layers, exported for per-kernel parity tests and micro-benchmarks ------------
+ * amph_gemv: y[m, n] = sum_k x[m, k] W[n, k] for m < M <= 8 (weight-streaming vector kernel).
+ *   x [M, Kd] float32, W [N, Kd] T, y [M, N] float32.  Kd must be a multiple of 8.
+ * amph_gemm: same contraction on the matrix cores for any M; x [M, Kd] T, y [M, N] float32.
+ *   A row of x must be a multiple of 64 bytes (Kd % 32 == 0 in bf16, % 16 in float32).
+ *   split_k in {0 (automatic), 1, 2, 4, 8}. */
+amph_status amph_gemv(amph_ctx *ctx, const float *x, const void *W, float *y, int M, int N, int Kd);
+amph_status amph_gemm(amph_ctx *ctx, const void *x, const void *W, float *y, int M, int N, int Kd,
+                      int split_k, void *workspace);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMPH_H */

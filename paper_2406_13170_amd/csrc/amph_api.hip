@@ -1,0 +1,520 @@
+// C-ABI layer of libamph: argument checks, the host side of the draft tree, workspace layout, and the
+// launch sequences of amph_draft / amph_target_forward.  All arithmetic lives in the kernels.
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace amph;
+
+namespace {
+
+constexpr size_t N_COUNTERS = 16384;
+constexpr size_t CNT_SAL = 9000, CNT_VERIFY = 10000;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct WsLayout {   // byte offsets into the caller's workspace
+  size_t x, q, att, y, act, h[2], Hp, Qa, Ka, Va, ctxa, attn_o, logits, sal_part;        // draft
+  size_t xres, xn, qb, attb, actb, gemm_part, amax_val, amax_idx, ver_part, tgt_tmp;     // target
+  size_t gemm_part_floats, ver_part_floats;
+  size_t total;
+};
+
+}  // namespace
+
+struct amph_ctx {
+  amph_config cfg;
+  hipStream_t stream = nullptr;
+  unsigned int *counters = nullptr;   // device, zero between launches
+  uint32_t *dev_status = nullptr;     // device, sticky
+  std::string err = "";
+  WsLayout ws;
+  int esz = 2;
+};
+
+struct amph_tree {
+  int T = 0, K = 0, n_leaves = 0;
+  std::vector<int32_t> parent, depth, rank, retrieve;
+  std::vector<uint64_t> mask;
+  int32_t *d_parent = nullptr, *d_depth = nullptr, *d_rank = nullptr;
+  uint64_t *d_mask = nullptr;
+  bool on_device = false;
+};
+
+namespace {
+
+amph_status fail(amph_ctx *ctx, amph_status st, const std::string &msg) {
+  if (ctx) ctx->err = msg;
+  return st;
+}
+amph_status hip_fail(amph_ctx *ctx, hipError_t e, const char *where) {
+  return fail(ctx, AMPH_EHIP, std::string(where) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(ctx, expr)                                  \
+  do {                                                      \
+    hipError_t e__ = (expr);                                \
+    if (e__ != hipSuccess) return hip_fail(ctx, e__, #expr); \
+  } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+WsLayout make_layout(const amph_config &c) {
+  WsLayout w{};
+  const size_t esz = (c.dtype == AMPH_BF16) ? 2 : 4;
+  const size_t B = c.batch, d = c.d_model, f = c.d_ffn, V = c.vocab, K = c.K, BK = B * K;
+  const size_t M = B * (size_t)c.max_tree;
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
+  w.x = take(B * d * 4); w.q = take(B * d * 4); w.att = take(B * d * 4); w.y = take(B * d * 4);
+  w.act = take(B * f * 4); w.h[0] = take(B * d * 4); w.h[1] = take(B * d * 4);
+  w.Hp = take(BK * d * 4); w.Qa = take(BK * d * 4); w.Ka = take(BK * d * 4); w.Va = take(BK * d * 4);
+  w.ctxa = take(BK * d * 4); w.attn_o = take(BK * d * 4); w.logits = take(BK * V * 4);
+  w.sal_part = take(sal_attn_ws_floats(c.n_heads, c.batch, c.head_dim, c.max_kv) * 4);
+  w.xres = take(M * d * 4); w.xn = take(M * d * esz); w.qb = take(M * d * esz); w.attb = take(M * d * esz);
+  w.actb = take(M * f * esz);
+  // largest split-K partial buffer over the GEMMs of a layer and the LM head
+  const size_t mblocks = (M + 63) / 64;
+  size_t part = 0;
+  auto consider = [&](int epi, int n_seg, int rows, int Kd) {
+    const int tiles = gemm_tiles_n(epi, n_seg, rows, c.head_dim);
+    const int s = gemm_auto_split(tiles * (int)mblocks, Kd, (int)esz);
+    if (s > 1) part = std::max(part, (size_t)tiles * mblocks * s * 64 * 64 * 4);
+  };
+  consider(EPI_QKV_ROPE, 3, c.d_model, c.d_model);
+  consider(EPI_RESIDUAL, 1, c.d_model, c.d_model);
+  consider(EPI_SWIGLU, 2, c.d_ffn, c.d_model);
+  consider(EPI_RESIDUAL, 1, c.d_model, c.d_ffn);
+  consider(EPI_ARGMAX, 1, c.vocab, c.d_model);
+  part = std::max(part, (size_t)2048 * 64 * 64 * 4);       // amph_gemm: up to 2048 (tile, split) pairs
+  w.gemm_part = take(part);
+  w.gemm_part_floats = part / 4;
+  const size_t tilesV = (V + 63) / 64;
+  w.amax_val = take(tilesV * M * 4); w.amax_idx = take(tilesV * M * 4);
+  size_t vfl = 0;                                           // any tree size up to max_tree may be used
+  for (int t = 1; t <= c.max_tree; ++t) vfl = std::max(vfl, verify_ws_floats(c.batch, t, c.n_heads, c.head_dim, c.max_kv, (int)esz));
+  w.ver_part = take(vfl * 4);
+  w.ver_part_floats = vfl;
+  w.tgt_tmp = take(M * 4);
+  w.total = at;
+  return w;
+}
+
+amph_status tree_upload(amph_ctx *ctx, amph_tree *t) {
+  if (t->on_device) return AMPH_OK;
+  const size_t n = t->T;
+  HIP_TRY(ctx, hipMalloc(&t->d_parent, n * 4));
+  HIP_TRY(ctx, hipMalloc(&t->d_depth, n * 4));
+  HIP_TRY(ctx, hipMalloc(&t->d_rank, n * 4));
+  HIP_TRY(ctx, hipMalloc(&t->d_mask, n * 16));
+  HIP_TRY(ctx, hipMemcpy(t->d_parent, t->parent.data(), n * 4, hipMemcpyHostToDevice));
+  HIP_TRY(ctx, hipMemcpy(t->d_depth, t->depth.data(), n * 4, hipMemcpyHostToDevice));
+  HIP_TRY(ctx, hipMemcpy(t->d_rank, t->rank.data(), n * 4, hipMemcpyHostToDevice));
+  HIP_TRY(ctx, hipMemcpy(t->d_mask, t->mask.data(), n * 16, hipMemcpyHostToDevice));
+  t->on_device = true;
+  return AMPH_OK;
+}
+
+template <typename T>
+amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new, const int32_t *tok_new, void *sal_kv,
+                       int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits, void *workspace) {
+  const amph_config &c = ctx->cfg;
+  const int B = c.batch, d = c.d_model, f = c.d_ffn, V = c.vocab, K = c.K, n_h = c.n_heads, d_h = c.head_dim;
+  hipStream_t st = ctx->stream;
+  char *ws = (char *)workspace;
+  auto F = [&](size_t off) { return (float *)(ws + off); };
+  float *x = F(ctx->ws.x), *q = F(ctx->ws.q), *att = F(ctx->ws.att), *y = F(ctx->ws.y), *act = F(ctx->ws.act);
+  float *h[2] = {F(ctx->ws.h[0]), F(ctx->ws.h[1])};
+  const size_t stage_stride = (size_t)B * 2 * n_h * c.max_kv * d_h;      // elements of T
+  for (int s = 0; s < 2; ++s) {
+    const float *u = (s == 0) ? h_new : h[0];
+    void *kv_stage = (T *)sal_kv + s * stage_stride;
+    HIP_TRY(ctx, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, B, x, ctx->dev_status));
+    HIP_TRY(ctx, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, B, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
+                                   q, ctx->dev_status));
+    HIP_TRY(ctx, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, F(ctx->ws.sal_part),
+                                    ctx->counters + CNT_SAL, att));
+    HIP_TRY(ctx, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, B, x, y, nullptr, nullptr, d));
+    HIP_TRY(ctx, launch_gate_up<T>(st, w->sal[s], y, d, f, B, c.rms_eps, act));
+    HIP_TRY(ctx, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, B, y, h[s], nullptr, nullptr, d));
+  }
+  float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);
+  float *attn_o = F(ctx->ws.attn_o);
+  float *lg = logits ? logits : F(ctx->ws.logits);
+  HIP_TRY(ctx, launch_head_mlp<T>(st, w->mlp, w->pe, h[0], h[1], d, K, B, Hp));
+  const int BK = B * K;
+  for (int r0 = 0; r0 < BK; r0 += 8) {
+    const int m = std::min(8, BK - r0);
+    const size_t o = (size_t)r0 * d;
+    HIP_TRY(ctx, launch_linear<T>(st, w->aeb_wq, w->aeb_wk, w->aeb_wv, 3, d, d, Hp + o, d, m, nullptr, Qa + o, Ka + o,
+                                  Va + o, d));
+  }
+  HIP_TRY(ctx, launch_aeb_attn(st, Qa, Ka, Va, B, K, n_h, d_h, ctxa));
+  for (int r0 = 0; r0 < BK; r0 += 8) {
+    const int m = std::min(8, BK - r0);
+    const size_t o = (size_t)r0 * d;
+    HIP_TRY(ctx, launch_linear<T>(st, w->aeb_wo, nullptr, nullptr, 1, d, d, ctxa + o, d, m, nullptr, attn_o + o, nullptr,
+                                  nullptr, d));
+  }
+  for (int r0 = 0; r0 < BK; r0 += 8) {
+    const int m = std::min(8, BK - r0);
+    HIP_TRY(ctx, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
+                                  lg + (size_t)r0 * V, nullptr, nullptr, V));
+  }
+  HIP_TRY(ctx, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1));
+  return AMPH_OK;
+}
+
+template <typename T>
+amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache, const void *v_cache,
+                        const int32_t *kv_len, void *out, void *workspace) {
+  const amph_config &c = ctx->cfg;
+  VerifyArgs a{};
+  a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out; a.kv_len = kv_len; a.mask_bits = tree->d_mask;
+  a.B = c.batch; a.T = tree->T; a.n_heads = c.n_heads; a.d_h = c.head_dim; a.max_kv = c.max_kv;
+  a.partials = (float *)((char *)workspace + ctx->ws.ver_part);
+  a.partials_cap = ctx->ws.ver_part_floats;
+  a.counters = ctx->counters + CNT_VERIFY;
+  a.dev_status = ctx->dev_status;
+  HIP_TRY(ctx, launch_verify_attn<T>(ctx->stream, a));
+  return AMPH_OK;
+}
+
+template <typename T>
+amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers, int n_layers, const void *embed,
+                        const void *final_norm, const void *lm_head, const int32_t *tree_tok, const int32_t *tree_pos,
+                        void *k_caches, void *v_caches, const int32_t *kv_len, float *hidden_out, float *logits_out,
+                        int32_t *tgt_argmax, void *workspace) {
+  const amph_config &c = ctx->cfg;
+  const int B = c.batch, d = c.d_model, f = c.d_ffn, V = c.vocab, n_h = c.n_heads, d_h = c.head_dim, Tn = tree->T;
+  const int M = B * Tn;
+  const int mblocks = (M + 63) / 64;
+  hipStream_t st = ctx->stream;
+  char *ws = (char *)workspace;
+  float *xres = (float *)(ws + ctx->ws.xres);
+  void *xn = ws + ctx->ws.xn, *qb = ws + ctx->ws.qb, *attb = ws + ctx->ws.attb, *actb = ws + ctx->ws.actb;
+  const size_t cache_layer = (size_t)B * n_h * c.max_kv * d_h;     // elements of T per layer
+  GemmArgs g{};
+  g.partials = (float *)(ws + ctx->ws.gemm_part);
+  g.partials_cap = ctx->ws.gemm_part_floats;
+  g.counters = ctx->counters;
+  g.dev_status = ctx->dev_status;
+  g.M = M; g.T_nodes = Tn; g.n_heads = n_h; g.d_h = d_h; g.max_kv = c.max_kv; g.theta = c.rope_theta;
+  g.tree_pos = tree_pos; g.kv_len = kv_len;
+  auto split_for = [&](int epi, int n_seg, int rows, int Kd) {
+    return gemm_auto_split(gemm_tiles_n(epi, n_seg, rows, d_h) * mblocks, Kd, (int)sizeof(T));
+  };
+  for (int li = 0; li < n_layers; ++li) {
+    const amph_layer_w &lw = layers[li];
+    void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
+    HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, lw.rms1, M, d, c.rms_eps, xn,
+                                        nullptr, ctx->dev_status));
+    GemmArgs a = g;
+    a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
+    a.split_k = split_for(EPI_QKV_ROPE, 3, d, d);
+    a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
+    HIP_TRY(ctx, launch_gemm<T>(st, EPI_QKV_ROPE, a));
+    if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
+    a = g;
+    a.w0 = lw.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = xres;
+    a.split_k = split_for(EPI_RESIDUAL, 1, d, d);
+    HIP_TRY(ctx, launch_gemm<T>(st, EPI_RESIDUAL, a));
+    HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, nullptr, nullptr, V, lw.rms2, M, d, c.rms_eps, xn, nullptr,
+                                        ctx->dev_status));
+    a = g;
+    a.w0 = lw.w_gate; a.w1 = lw.w_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
+    a.split_k = split_for(EPI_SWIGLU, 2, f, d);
+    HIP_TRY(ctx, launch_gemm<T>(st, EPI_SWIGLU, a));
+    a = g;
+    a.w0 = lw.w_down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = xres;
+    a.split_k = split_for(EPI_RESIDUAL, 1, d, f);
+    HIP_TRY(ctx, launch_gemm<T>(st, EPI_RESIDUAL, a));
+  }
+  HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, final_norm, M, d, c.rms_eps,
+                                      xn, hidden_out, ctx->dev_status));
+  GemmArgs a = g;
+  a.w0 = lm_head; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
+  a.split_k = split_for(EPI_ARGMAX, 1, V, d);
+  a.logits = logits_out; a.tgt = tgt_argmax;
+  a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
+  HIP_TRY(ctx, launch_gemm<T>(st, EPI_ARGMAX, a));
+  return AMPH_OK;
+}
+
+}  // namespace
+
+// =====================================================================================================
+extern "C" {
+
+amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
+  if (out) *out = nullptr;
+  if (!cfg || !out) return AMPH_EINVAL;
+  const amph_config &c = *cfg;
+  if (c.dtype != AMPH_F32 && c.dtype != AMPH_BF16) return AMPH_EINVAL;
+  if (c.d_model <= 0 || c.n_heads <= 0 || c.head_dim <= 0 || c.d_ffn <= 0 || c.vocab <= 0 || c.batch <= 0 || c.K <= 0 ||
+      c.topk <= 0 || c.max_tree <= 0 || c.max_kv <= 0)
+    return AMPH_EINVAL;
+  if (!(c.rms_eps >= 0.f) || !(c.rope_theta > 1.f)) return AMPH_EINVAL;
+  if (c.head_dim != 64 && c.head_dim != 128) return AMPH_ESHAPE;
+  if (c.d_model != c.n_heads * c.head_dim) return AMPH_ESHAPE;
+  if (c.d_model % 64 || c.d_ffn % 16 || (c.dtype == AMPH_BF16 && c.d_ffn % 32)) return AMPH_ESHAPE;
+  if (c.K > AMPH_MAX_HEADS_K || c.topk > AMPH_MAX_TOPK || c.topk > c.vocab || c.max_tree > AMPH_MAX_TREE) return AMPH_ESHAPE;
+  if (c.max_kv % 32 || c.max_kv < c.max_tree) return AMPH_ESHAPE;
+  if (c.vocab > 65536 || c.batch > 64 || (long long)c.batch * c.n_heads > 1000) return AMPH_ESHAPE;
+  amph_ctx *ctx = new (std::nothrow) amph_ctx();
+  if (!ctx) return AMPH_EINVAL;
+  ctx->cfg = c;
+  ctx->esz = (c.dtype == AMPH_BF16) ? 2 : 4;
+  ctx->ws = make_layout(c);
+  hipError_t e = hipMalloc(&ctx->counters, N_COUNTERS * sizeof(unsigned int) + 256);
+  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, N_COUNTERS * sizeof(unsigned int) + 256);
+  if (e != hipSuccess) {
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    delete ctx;
+    return AMPH_EHIP;
+  }
+  ctx->dev_status = reinterpret_cast<uint32_t *>(ctx->counters + N_COUNTERS);
+  *out = ctx;
+  return AMPH_OK;
+}
+
+void amph_destroy(amph_ctx *ctx) {
+  if (!ctx) return;
+  if (ctx->counters) (void)hipFree(ctx->counters);
+  delete ctx;
+}
+
+amph_status amph_set_stream(amph_ctx *ctx, void *hip_stream) {
+  if (!ctx) return AMPH_EINVAL;
+  ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+  return AMPH_OK;
+}
+
+size_t amph_workspace_bytes(const amph_ctx *ctx) { return ctx ? ctx->ws.total : 0; }
+
+const char *amph_last_error(const amph_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits) {
+  if (!ctx || !host_bits) return AMPH_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  HIP_TRY(ctx, hipMemcpy(host_bits, ctx->dev_status, 4, hipMemcpyDeviceToHost));
+  HIP_TRY(ctx, hipMemset(ctx->dev_status, 0, 4));
+  return AMPH_OK;
+}
+
+amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new, const int32_t *tok_new, int n_new,
+                       void *sal_kv, int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits, void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!w || !h_new || !tok_new || !sal_kv || !sal_len || !topk_idx || !topk_val || !workspace)
+    return fail(ctx, AMPH_EINVAL, "amph_draft: null argument");
+  if (n_new != 1) return fail(ctx, AMPH_ESHAPE, "amph_draft: n_new must be 1");
+  const void *ptrs[] = {w->embed, w->fc[0], w->fc[1], w->mlp, w->pe, w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, w->lm_head,
+                        h_new, sal_kv, workspace};
+  for (const void *p : ptrs)
+    if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_draft: null or misaligned (16 B) pointer");
+  for (int s = 0; s < 2; ++s) {
+    const amph_layer_w &l = w->sal[s];
+    const void *lp[] = {l.rms1, l.wq, l.wk, l.wv, l.wo, l.rms2, l.w_gate, l.w_up, l.w_down};
+    for (const void *p : lp)
+      if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_draft: null or misaligned SAL weight");
+  }
+  if (ctx->cfg.batch > 8) return fail(ctx, AMPH_ESHAPE, "amph_draft: batch > 8 is not supported");
+  if (ctx->cfg.dtype == AMPH_BF16)
+    return draft_impl<bf16_t>(ctx, w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
+  return draft_impl<float>(ctx, w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
+}
+
+amph_status amph_tree_create(const int32_t *paths, int n, int K, amph_tree **out) {
+  if (out) *out = nullptr;
+  if (!out || n < 0 || K < 1 || (n > 0 && !paths)) return AMPH_EINVAL;
+  if (n + 1 > AMPH_MAX_TREE || K > AMPH_MAX_HEADS_K) return AMPH_ESHAPE;
+  std::vector<std::vector<int32_t>> nodes;
+  nodes.emplace_back();                                     // root
+  for (int i = 0; i < n; ++i) {
+    std::vector<int32_t> p;
+    bool ended = false;
+    for (int j = 0; j < K; ++j) {
+      const int32_t r = paths[(size_t)i * K + j];
+      if (r < 0) { ended = true; continue; }
+      if (ended) return AMPH_ETREE;                         // a rank after the padding began
+      if (r >= AMPH_MAX_TOPK) return AMPH_ESHAPE;
+      p.push_back(r);
+    }
+    if (p.empty()) return AMPH_ETREE;                       // the root is implicit
+    nodes.push_back(p);
+  }
+  std::sort(nodes.begin() + 1, nodes.end(), [](const std::vector<int32_t> &a, const std::vector<int32_t> &b) {
+    if (a.size() != b.size()) return a.size() < b.size();
+    return a < b;
+  });
+  std::map<std::vector<int32_t>, int> index;
+  for (size_t i = 0; i < nodes.size(); ++i) {
+    if (!index.emplace(nodes[i], (int)i).second) return AMPH_ETREE;   // duplicate
+  }
+  amph_tree *t = new (std::nothrow) amph_tree();
+  if (!t) return AMPH_EINVAL;
+  const int T = (int)nodes.size();
+  t->T = T; t->K = K;
+  t->parent.assign(T, -1); t->depth.assign(T, 0); t->rank.assign(T, -1); t->mask.assign((size_t)T * 2, 0);
+  for (int i = 1; i < T; ++i) {
+    std::vector<int32_t> par(nodes[i].begin(), nodes[i].end() - 1);
+    auto it = index.find(par);
+    if (it == index.end()) { delete t; return AMPH_ETREE; }          // missing parent
+    t->parent[i] = it->second;
+    t->depth[i] = (int32_t)nodes[i].size();
+    t->rank[i] = nodes[i].back();
+  }
+  std::vector<char> has_child(T, 0);
+  for (int i = 0; i < T; ++i) {
+    for (int j = i; j >= 0; j = t->parent[j]) t->mask[(size_t)i * 2 + (j >> 6)] |= (uint64_t)1 << (j & 63);
+    if (t->parent[i] >= 0) has_child[t->parent[i]] = 1;
+  }
+  for (int i = 0; i < T; ++i) {
+    if (has_child[i]) continue;
+    std::vector<int32_t> chain;
+    for (int j = i; j >= 0; j = t->parent[j]) chain.push_back(j);
+    std::reverse(chain.begin(), chain.end());
+    chain.resize(K + 1, -1);
+    t->retrieve.insert(t->retrieve.end(), chain.begin(), chain.end());
+    t->n_leaves++;
+  }
+  *out = t;
+  return AMPH_OK;
+}
+
+void amph_tree_destroy(amph_tree *t) {
+  if (!t) return;
+  if (t->d_parent) (void)hipFree(t->d_parent);
+  if (t->d_depth) (void)hipFree(t->d_depth);
+  if (t->d_rank) (void)hipFree(t->d_rank);
+  if (t->d_mask) (void)hipFree(t->d_mask);
+  delete t;
+}
+
+amph_status amph_tree_info(const amph_tree *t, int *T, int *n_leaves, const int32_t **parent, const int32_t **depth,
+                           const int32_t **rank, const uint64_t **mask_bits, const int32_t **retrieve) {
+  if (!t) return AMPH_EINVAL;
+  if (T) *T = t->T;
+  if (n_leaves) *n_leaves = t->n_leaves;
+  if (parent) *parent = t->parent.data();
+  if (depth) *depth = t->depth.data();
+  if (rank) *rank = t->rank.data();
+  if (mask_bits) *mask_bits = t->mask.data();
+  if (retrieve) *retrieve = t->retrieve.data();
+  return AMPH_OK;
+}
+
+static amph_status check_tree(amph_ctx *ctx, const amph_tree *tree, const char *who) {
+  if (!tree) return fail(ctx, AMPH_EINVAL, std::string(who) + ": null tree");
+  if (tree->T > ctx->cfg.max_tree) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": tree larger than cfg.max_tree");
+  if (tree->K != ctx->cfg.K) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": tree depth K differs from cfg.K");
+  for (int i = 1; i < tree->T; ++i)
+    if (tree->rank[i] >= ctx->cfg.topk) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": tree uses a rank >= cfg.topk");
+  return tree_upload(ctx, const_cast<amph_tree *>(tree));
+}
+
+amph_status amph_tree_build(amph_ctx *ctx, const amph_tree *tree, const int32_t *root_tok, const int32_t *topk_idx,
+                            const int32_t *kv_len, int32_t *tree_tok, int32_t *tree_pos) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!root_tok || !topk_idx || !kv_len || !tree_tok || !tree_pos) return fail(ctx, AMPH_EINVAL, "amph_tree_build: null argument");
+  if (amph_status s = check_tree(ctx, tree, "amph_tree_build")) return s;
+  HIP_TRY(ctx, launch_tree_build(ctx->stream, tree->d_depth, tree->d_rank, tree->T, ctx->cfg.batch, ctx->cfg.K,
+                                 ctx->cfg.topk, root_tok, topk_idx, kv_len, tree_tok, tree_pos));
+  return AMPH_OK;
+}
+
+amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache, const void *v_cache,
+                             const int32_t *kv_len, void *out, void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!q || !k_cache || !v_cache || !kv_len || !out || !workspace) return fail(ctx, AMPH_EINVAL, "amph_verify_attn: null argument");
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out) || !aligned16(workspace))
+    return fail(ctx, AMPH_EINVAL, "amph_verify_attn: pointers must be 16-byte aligned");
+  if (q == out) return fail(ctx, AMPH_EINVAL, "amph_verify_attn: out must not alias q");
+  if (amph_status s = check_tree(ctx, tree, "amph_verify_attn")) return s;
+  if (ctx->cfg.dtype == AMPH_BF16) return verify_impl<bf16_t>(ctx, tree, q, k_cache, v_cache, kv_len, out, workspace);
+  return verify_impl<float>(ctx, tree, q, k_cache, v_cache, kv_len, out, workspace);
+}
+
+amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok, const int32_t *tgt_argmax,
+                        const float *tgt_logits, int32_t *accept_len, int32_t *accept_path, int32_t *next_tok,
+                        int32_t *best_node, void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!tree_tok || !accept_len || !accept_path || !next_tok || !best_node) return fail(ctx, AMPH_EINVAL, "amph_accept: null argument");
+  if ((tgt_argmax == nullptr) == (tgt_logits == nullptr))
+    return fail(ctx, AMPH_EINVAL, "amph_accept: exactly one of tgt_argmax and tgt_logits must be given");
+  if (amph_status s = check_tree(ctx, tree, "amph_accept")) return s;
+  const int32_t *tgt = tgt_argmax;
+  if (tgt_logits) {
+    if (!workspace) return fail(ctx, AMPH_EINVAL, "amph_accept: workspace needed with tgt_logits");
+    int32_t *tmp = (int32_t *)((char *)workspace + ctx->ws.tgt_tmp);
+    HIP_TRY(ctx, launch_row_argmax(ctx->stream, tgt_logits, ctx->cfg.batch * tree->T, ctx->cfg.vocab, tmp));
+    tgt = tmp;
+  }
+  HIP_TRY(ctx, launch_accept(ctx->stream, tree->d_parent, tree->d_depth, tree->T, ctx->cfg.batch, ctx->cfg.K, tree_tok, tgt,
+                             accept_len, accept_path, next_tok, best_node));
+  return AMPH_OK;
+}
+
+amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers, int n_layers,
+                                const void *embed, const void *final_norm, const void *lm_head, const int32_t *tree_tok,
+                                const int32_t *tree_pos, void *k_caches, void *v_caches, const int32_t *kv_len,
+                                float *hidden_out, float *logits_out, int32_t *tgt_argmax, void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (n_layers < 0 || (n_layers > 0 && !layers)) return fail(ctx, AMPH_EINVAL, "amph_target_forward: bad layers");
+  if (!embed || !final_norm || !lm_head || !tree_tok || !tree_pos || !kv_len || !tgt_argmax || !workspace ||
+      (n_layers > 0 && (!k_caches || !v_caches)))
+    return fail(ctx, AMPH_EINVAL, "amph_target_forward: null argument");
+  for (int i = 0; i < n_layers; ++i) {
+    const amph_layer_w &l = layers[i];
+    const void *lp[] = {l.rms1, l.wq, l.wk, l.wv, l.wo, l.rms2, l.w_gate, l.w_up, l.w_down};
+    for (const void *p : lp)
+      if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_target_forward: null or misaligned layer weight");
+  }
+  if (!aligned16(embed) || !aligned16(lm_head) || !aligned16(workspace) || (k_caches && !aligned16(k_caches)) ||
+      (v_caches && !aligned16(v_caches)))
+    return fail(ctx, AMPH_EINVAL, "amph_target_forward: pointers must be 16-byte aligned");
+  if (amph_status s = check_tree(ctx, tree, "amph_target_forward")) return s;
+  if (ctx->cfg.dtype == AMPH_BF16)
+    return target_impl<bf16_t>(ctx, tree, layers, n_layers, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches,
+                               v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+  return target_impl<float>(ctx, tree, layers, n_layers, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches, v_caches,
+                            kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+}
+
+amph_status amph_gemv(amph_ctx *ctx, const float *x, const void *W, float *y, int M, int N, int Kd) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!x || !W || !y || !aligned16(W)) return fail(ctx, AMPH_EINVAL, "amph_gemv: null or misaligned argument");
+  if (M < 1 || M > 8 || N < 1 || Kd < 8 || Kd % 8) return fail(ctx, AMPH_ESHAPE, "amph_gemv: need 1 <= M <= 8, Kd % 8 == 0");
+  if (ctx->cfg.dtype == AMPH_BF16)
+    HIP_TRY(ctx, launch_linear<bf16_t>(ctx->stream, W, nullptr, nullptr, 1, N, Kd, x, Kd, M, nullptr, y, nullptr, nullptr, N));
+  else
+    HIP_TRY(ctx, launch_linear<float>(ctx->stream, W, nullptr, nullptr, 1, N, Kd, x, Kd, M, nullptr, y, nullptr, nullptr, N));
+  return AMPH_OK;
+}
+
+amph_status amph_gemm(amph_ctx *ctx, const void *x, const void *W, float *y, int M, int N, int Kd, int split_k,
+                      void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!x || !W || !y || !workspace || !aligned16(x) || !aligned16(W) || !aligned16(workspace))
+    return fail(ctx, AMPH_EINVAL, "amph_gemm: null or misaligned argument");
+  if (M < 1 || N < 1 || Kd < 1 || (Kd * ctx->esz) % 64) return fail(ctx, AMPH_ESHAPE, "amph_gemm: a row of x must be a multiple of 64 bytes");
+  const int tiles = (N + 63) / 64, mblocks = (M + 63) / 64;
+  if (split_k == 0) split_k = gemm_auto_split(tiles * mblocks, Kd, ctx->esz);
+  if (split_k != 1 && split_k != 2 && split_k != 4 && split_k != 8) return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k");
+  if ((size_t)tiles * mblocks * split_k > 2048) return fail(ctx, AMPH_ESHAPE, "amph_gemm: more than 2048 (tile, split) pairs");
+  GemmArgs a{};
+  a.w0 = W; a.n_seg = 1; a.seg_rows = N; a.Kd = Kd; a.x = x; a.M = M; a.split_k = split_k;
+  a.partials = (float *)((char *)workspace + ctx->ws.gemm_part);
+  a.partials_cap = ctx->ws.gemm_part_floats;
+  a.counters = ctx->counters; a.out = y; a.dev_status = ctx->dev_status;
+  if (ctx->cfg.dtype == AMPH_BF16) HIP_TRY(ctx, launch_gemm<bf16_t>(ctx->stream, EPI_STORE, a));
+  else HIP_TRY(ctx, launch_gemm<float>(ctx->stream, EPI_STORE, a));
+  return AMPH_OK;
+}
+
+}  // extern "C"

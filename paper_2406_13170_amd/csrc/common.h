@@ -1,0 +1,115 @@
+// Shared device helpers for the gfx950 kernels: 16-byte fragments of float / bfloat16, wave
+// reductions and the "last workgroup to arrive finishes the job" counter protocol.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace amph {
+
+typedef __bf16 bf16_t;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int WAVE = 64;
+constexpr float NEG_BIG = -1.0e30f;   // finite stand-in for -inf in running maxima
+
+// ---- element traits: PER = elements in one 16-byte fragment ------------------------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int PER = 4;
+  static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ float to_f32(float v) { return v; }
+  static __device__ __forceinline__ float from_f32(float v) { return v; }
+};
+template <> struct Elem<bf16_t> {
+  static constexpr int PER = 8;
+  static __device__ __forceinline__ void unpack(const uint4 &v, float *f) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+  static __device__ __forceinline__ bf16_t from_f32(float v) { return (bf16_t)v; }   // RNE
+};
+
+// pack PER floats into one 16-byte fragment of T (RNE for bf16)
+template <typename T> __device__ __forceinline__ uint4 pack16(const float *f);
+template <> __device__ __forceinline__ uint4 pack16<float>(const float *f) {
+  return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+}
+template <> __device__ __forceinline__ uint4 pack16<bf16_t>(const float *f) {
+  union { bf16x8 v; uint4 u; } c;
+  #pragma unroll
+  for (int i = 0; i < 8; ++i) c.v[i] = (bf16_t)f[i];
+  return c.u;
+}
+
+__device__ __forceinline__ uint4 ldg16(const void *p) { return *reinterpret_cast<const uint4 *>(p); }
+__device__ __forceinline__ void stg16(void *p, const uint4 &v) { *reinterpret_cast<uint4 *>(p) = v; }
+
+// ---- matrix-core step on 16-byte fragments --------------------------------------------------------
+// D[16 x 16] += A[16 x KS] * B[KS x 16] with KS = 4 * PER.  Lane l holds for A: row l%16, contraction
+// slots (l/16)*PER .. +PER; for B: column l%16, the same slots; for D: column l%16, rows (l/16)*4..+4.
+// bf16: one 16x16x32 instruction.  float: four 16x16x4 instructions, the j-th using element j of
+// every lane's fragment (any one-to-one slot assignment is valid as long as A and B agree).
+template <typename T> __device__ __forceinline__ f32x4 mma16(const uint4 &a, const uint4 &b, f32x4 acc);
+template <> __device__ __forceinline__ f32x4 mma16<bf16_t>(const uint4 &a, const uint4 &b, f32x4 acc) {
+  union { uint4 u; bf16x8 v; } ca, cb;
+  ca.u = a; cb.u = b;
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(ca.v, cb.v, acc, 0, 0, 0);
+}
+template <> __device__ __forceinline__ f32x4 mma16<float>(const uint4 &a, const uint4 &b, f32x4 acc) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  return acc;
+}
+
+// ---- wave-level reductions ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
+  return v;
+}
+
+// sum over a whole 256-thread block; every thread gets the result.  red must hold 4 floats.
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
+
+// ---- last-arriver protocol -----------------------------------------------------------------------------
+// Each of `expected` workgroups calls this after writing its partial results to global memory.  The
+// one that arrives last gets true and may read all partials; it also resets the counter so the next
+// launch finds it at zero.  No workgroup ever waits for another, so the kernel cannot hang.
+__device__ __forceinline__ bool arrive_and_is_last(unsigned int *counter, unsigned int expected, int *s_flag) {
+  __threadfence();                      // release: this thread's partials are visible device-wide
+  __syncthreads();                      // ... for every thread of the block
+  if (threadIdx.x == 0) {
+    unsigned int old = atomicAdd(counter, 1u);
+    int last = (old == expected - 1u);
+    if (last) *counter = 0u;            // nobody else touches it any more in this launch
+    *s_flag = last;
+  }
+  __syncthreads();
+  const bool last = (*s_flag != 0);
+  if (last) __threadfence();            // acquire: see the other workgroups' partials
+  return last;
+}
+
+}  // namespace amph

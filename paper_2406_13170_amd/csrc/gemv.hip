@@ -1,0 +1,499 @@
+// Weight-streaming GEMV family for the draft path (Sec. 3.1 Eq. 1, Sec. 3.2 Eq. 2-6): M <= 8
+// activation rows against a [N, Kd] weight matrix that is read exactly once from HBM.
+//
+// Shape of every kernel here: a 256-thread workgroup first parks the M activation rows in LDS as
+// float32 (after the prologue: concat with the token embedding, or RMSNorm scaling), then each of
+// its 4 waves walks over groups of R = 4 weight rows.  For a group the 64 lanes stride over the
+// reduction axis in 16-byte fragments, keeping R x U fragments in flight, and multiply them with the
+// LDS copy of x; a wave-wide butterfly sum finishes the R x M dot products and the epilogue (RoPE and
+// cache write, residual add, SwiGLU, head MLP) is applied to them directly.  No matrix cores: with
+// M <= 8 the contraction is a stream of dot products bound by HBM.
+#include "kernels.h"
+
+namespace amph {
+
+constexpr int GV_THREADS = 256;
+constexpr int GV_R = 4;        // weight rows per wave step
+constexpr int GV_U = 4;        // 16-byte fragments in flight per row
+
+// LDS layout of x: for wave-chunk c (64 lanes x PER elements), quad q (4 floats), lane l:
+//   xs[((m * nC + c) * NQ + q) * 256 + l * 4 + j]  holds x[m][c * CH + l * PER + q * 4 + j]
+// so that a lane's float4 reads are contiguous across the wave.
+template <typename T> struct XLayout {
+  static constexpr int PER = Elem<T>::PER;
+  static constexpr int NQ = PER / 4;
+  static constexpr int CH = WAVE * PER;
+  static __device__ __forceinline__ int index(int m, int nC, int k) {
+    const int c = k / CH, r = k % CH, l = r / PER, e = r % PER;
+    return ((m * nC + c) * NQ + e / 4) * 256 + l * 4 + (e % 4);
+  }
+};
+
+// Accumulate acc[r][m] += sum_k W_r[k] * x[m][k] over the whole reduction axis for this lane's slots.
+template <typename T, int M>
+__device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const float *xs, int Kd, int nC,
+                                          float (&acc)[GV_R][M]) {
+  constexpr int PER = Elem<T>::PER, NQ = PER / 4, CH = WAVE * PER;
+  const int lane = threadIdx.x & 63;
+  const float4 *xs4 = reinterpret_cast<const float4 *>(xs);
+  for (int c0 = 0; c0 < nC; c0 += GV_U) {
+    uint4 w[GV_U][GV_R];
+    #pragma unroll
+    for (int u = 0; u < GV_U; ++u) {
+      const int k = (c0 + u) * CH + lane * PER;
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        if (k < Kd) w[u][r] = ldg16(rows[r] + k);
+        else w[u][r] = make_uint4(0u, 0u, 0u, 0u);
+      }
+    }
+    #pragma unroll
+    for (int u = 0; u < GV_U; ++u) {
+      if (c0 + u < nC) {
+        float wf[GV_R][PER];
+        #pragma unroll
+        for (int r = 0; r < GV_R; ++r) Elem<T>::unpack(w[u][r], wf[r]);
+        #pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          #pragma unroll
+          for (int m = 0; m < M; ++m) {
+            const float4 xv = xs4[((m * nC + c0 + u) * NQ + q) * 64 + lane];
+            #pragma unroll
+            for (int r = 0; r < GV_R; ++r) {
+              acc[r][m] = fmaf(wf[r][q * 4 + 0], xv.x, acc[r][m]);
+              acc[r][m] = fmaf(wf[r][q * 4 + 1], xv.y, acc[r][m]);
+              acc[r][m] = fmaf(wf[r][q * 4 + 2], xv.z, acc[r][m]);
+              acc[r][m] = fmaf(wf[r][q * 4 + 3], xv.w, acc[r][m]);
+            }
+          }
+        }
+      }
+    }
+  }
+  #pragma unroll
+  for (int r = 0; r < GV_R; ++r)
+    #pragma unroll
+    for (int m = 0; m < M; ++m) acc[r][m] = wave_sum(acc[r][m]);
+}
+
+template <int M> __device__ __forceinline__ void zero_acc(float (&acc)[GV_R][M]) {
+  #pragma unroll
+  for (int r = 0; r < GV_R; ++r)
+    #pragma unroll
+    for (int m = 0; m < M; ++m) acc[r][m] = 0.f;
+}
+
+// ---- prologues: fill xs (and zero its padding), return per-row inverse RMS where asked ---------------
+// plain float32 rows x[m][k], leading dimension ldx; rows m >= m_valid are zero.
+template <typename T, int M>
+__device__ __forceinline__ void load_x_plain(float *xs, const float *x, int ldx, int m_valid, int Kd, int nC) {
+  constexpr int CH = XLayout<T>::CH;
+  const int Kp = nC * CH;
+  for (int i = threadIdx.x; i < M * Kp; i += GV_THREADS) {
+    const int m = i / Kp, k = i % Kp;
+    float v = 0.f;
+    if (m < m_valid && k < Kd) v = x[(size_t)m * ldx + k];
+    xs[XLayout<T>::index(m, nC, k)] = v;
+  }
+}
+
+// x[m][k] * g[k] with the row's 1/rms returned in rs[m] (applied by the caller to the dot products).
+template <typename T, int M>
+__device__ __forceinline__ void load_x_rmsnorm(float *xs, float *red, const float *x, int ldx, const T *g,
+                                               int m_valid, int Kd, int nC, float eps, float (&rs)[M]) {
+  constexpr int CH = XLayout<T>::CH;
+  const int Kp = nC * CH;
+  float ss[M];
+  #pragma unroll
+  for (int m = 0; m < M; ++m) ss[m] = 0.f;
+  for (int k = threadIdx.x; k < Kp; k += GV_THREADS) {
+    const float gk = (k < Kd) ? Elem<T>::to_f32(g[k]) : 0.f;
+    #pragma unroll
+    for (int m = 0; m < M; ++m) {
+      float v = 0.f;
+      if (m < m_valid && k < Kd) v = x[(size_t)m * ldx + k];
+      ss[m] = fmaf(v, v, ss[m]);
+      xs[XLayout<T>::index(m, nC, k)] = v * gk;
+    }
+  }
+  #pragma unroll
+  for (int m = 0; m < M; ++m) {
+    const float tot = block_sum_256(ss[m], red);
+    rs[m] = rsqrtf(tot / (float)Kd + eps);
+  }
+}
+
+// =====================================================================================================
+// K1: x^s = fc^s([u ; e]) of Eq. 1, e = embed[tok] gathered on the fly.  out [M, d] float32.
+// =====================================================================================================
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const float *u, const T *embed,
+                                                          const int32_t *tok, int vocab, int d, int m_valid,
+                                                          float *out, uint32_t *dev_status) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int Kd = 2 * d, nC = (Kd + CH - 1) / CH, Kp = nC * CH;
+  float *xs = smem;
+  for (int i = threadIdx.x; i < M * Kp; i += GV_THREADS) {
+    const int m = i / Kp, k = i % Kp;
+    float v = 0.f;
+    if (m < m_valid && k < Kd) {
+      if (k < d) v = u[(size_t)m * d + k];
+      else {
+        const int t = tok[m];
+        if (t >= 0 && t < vocab) v = Elem<T>::to_f32(embed[(size_t)t * d + (k - d)]);
+        else if (blockIdx.x == 0 && k == d) atomicOr(dev_status, 4u);
+      }
+    }
+    xs[XLayout<T>::index(m, nC, k)] = v;
+  }
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int G = (d + GV_R - 1) / GV_R;
+  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+    const T *rows[GV_R];
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = W + (size_t)min(g * GV_R + r, d - 1) * Kd;
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        const int n = g * GV_R + r;
+        if (n < d) {
+          #pragma unroll
+          for (int m = 0; m < M; ++m) if (m < m_valid) out[(size_t)m * d + n] = acc[r][m];
+        }
+      }
+    }
+  }
+}
+
+// =====================================================================================================
+// K2: SAL q/k/v projections on RMSNorm(x) with RoPE at position sal_len[b]; k and v go straight into
+// row sal_len[b] of the stage's cache, q (float32) to qbuf [M, d].  Row m is batch element m.
+// A wave step handles the two RoPE pairs (i, i + half), (i + 1, i + 1 + half) of one head.
+// kv_stage points at [B, 2, n_heads, max_kv, d_h] of this stage.
+// =====================================================================================================
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk, const T *wv, const T *norm_w,
+                                                        const float *x, int d, int n_heads, int d_h, int m_valid,
+                                                        float eps, float theta, const int32_t *sal_len, int max_kv,
+                                                        T *kv_stage, float *qbuf, uint32_t *dev_status) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int Kd = d, nC = (Kd + CH - 1) / CH;
+  float *xs = smem + 4;
+  float rs[M];
+  load_x_rmsnorm<T, M>(xs, smem, x, d, norm_w, m_valid, Kd, nC, eps, rs);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int half = d_h / 2;
+  const int Gseg = d / GV_R;                 // groups per matrix (d is a multiple of 4)
+  const int G = 3 * Gseg;
+  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+    const int seg = g / Gseg, gl = g % Gseg;
+    const T *Wm = (seg == 0) ? wq : (seg == 1) ? wk : wv;
+    int n[GV_R];
+    int head = 0, i0 = 0;
+    if (seg < 2) {
+      const int gph = half / 2;              // groups per head
+      head = gl / gph; i0 = (gl % gph) * 2;
+      n[0] = head * d_h + i0; n[1] = n[0] + 1; n[2] = n[0] + half; n[3] = n[2] + 1;
+    } else {
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) n[r] = gl * GV_R + r;
+    }
+    const T *rows[GV_R];
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)n[r] * Kd;
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int m = 0; m < M; ++m) {
+        if (m >= m_valid) continue;
+        const int pos = sal_len[m];
+        if (pos < 0 || pos + 1 > max_kv) {
+          if (g == 0) atomicOr(dev_status, 1u);
+          continue;
+        }
+        float y[GV_R];
+        #pragma unroll
+        for (int r = 0; r < GV_R; ++r) y[r] = acc[r][m] * rs[m];
+        if (seg < 2) {
+          #pragma unroll
+          for (int p = 0; p < 2; ++p) {
+            const float inv_freq = exp2f(-2.0f * (float)(i0 + p) / (float)d_h * log2f(theta));
+            float sn, cs;
+            sincosf((float)pos * inv_freq, &sn, &cs);
+            const float a = y[p], b = y[2 + p];
+            y[p] = a * cs - b * sn;
+            y[2 + p] = b * cs + a * sn;
+          }
+        }
+        if (seg == 0) {
+          #pragma unroll
+          for (int r = 0; r < GV_R; ++r) qbuf[(size_t)m * d + n[r]] = y[r];
+        } else {
+          // [B, 2, n_heads, max_kv, d_h]
+          #pragma unroll
+          for (int r = 0; r < GV_R; ++r) {
+            const int hh = n[r] / d_h, e = n[r] % d_h;
+            T *dst = kv_stage + ((((size_t)m * 2 + (seg - 1)) * n_heads + hh) * max_kv + pos) * d_h + e;
+            *dst = Elem<T>::from_f32(y[r]);
+          }
+        }
+      }
+    }
+  }
+}
+
+// =====================================================================================================
+// K3: generic linear with up to three stacked matrices of `seg_rows` rows each (AEB q/k/v, Wo, W_down,
+// LM head).  out_s[m][n] = (res ? res[m][n] : 0) + sum_k x[m][k] W_s[n][k].  x float32 [M, Kd].
+// =====================================================================================================
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1, const T *w2, int n_seg, int seg_rows,
+                                                       int Kd, const float *x, int ldx, int m_valid, const float *res,
+                                                       float *o0, float *o1, float *o2, int ldo) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int nC = (Kd + CH - 1) / CH;
+  float *xs = smem;
+  load_x_plain<T, M>(xs, x, ldx, m_valid, Kd, nC);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int Gseg = (seg_rows + GV_R - 1) / GV_R;
+  const int G = n_seg * Gseg;
+  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+    const int seg = g / Gseg, gl = g % Gseg;
+    const T *Wm = (seg == 0) ? w0 : (seg == 1) ? w1 : w2;
+    float *om = (seg == 0) ? o0 : (seg == 1) ? o1 : o2;
+    const T *rows[GV_R];
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * Kd;
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        const int n = gl * GV_R + r;
+        if (n < seg_rows) {
+          #pragma unroll
+          for (int m = 0; m < M; ++m) {
+            if (m < m_valid) {
+              float v = acc[r][m];
+              if (res) v += res[(size_t)m * ldo + n];
+              om[(size_t)m * ldo + n] = v;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+// =====================================================================================================
+// K4: SwiGLU front half: act[m][j] = SiLU(W_gate[j] . n) * (W_up[j] . n), n = RMSNorm(x).
+// A wave step handles gate rows j, j+1 and up rows j, j+1.
+// =====================================================================================================
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T *w_up, const T *norm_w, const float *x,
+                                                        int d, int f, int m_valid, float eps, float *act) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int Kd = d, nC = (Kd + CH - 1) / CH;
+  float *xs = smem + 4;
+  float rs[M];
+  load_x_rmsnorm<T, M>(xs, smem, x, d, norm_w, m_valid, Kd, nC, eps, rs);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int G = (f + 1) / 2;
+  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+    const int j0 = g * 2, j1 = min(j0 + 1, f - 1);
+    const T *rows[GV_R] = {w_gate + (size_t)j0 * Kd, w_gate + (size_t)j1 * Kd, w_up + (size_t)j0 * Kd,
+                           w_up + (size_t)j1 * Kd};
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int m = 0; m < M; ++m) {
+        if (m >= m_valid) continue;
+        act[(size_t)m * f + j0] = silu_f(acc[0][m] * rs[m]) * (acc[2][m] * rs[m]);
+        if (j0 + 1 < f) act[(size_t)m * f + j0 + 1] = silu_f(acc[1][m] * rs[m]) * (acc[3][m] * rs[m]);
+      }
+    }
+  }
+}
+
+// =====================================================================================================
+// K5: head MLPs of Eq. 2-4.  For head k (0-based) the source is h1 when k < floor(K/2), else h2;
+// Hp[b, k, n] = src[b][n] + SiLU(W_k[n] . src[b]) + PE[k][n].  Rows m are batch elements.
+// Both sources sit in LDS; a workgroup handles groups of one head at a time.
+// =====================================================================================================
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T *pe, const float *h1, const float *h2,
+                                                         int d, int K, int m_valid, float *Hp) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int Kd = d, nC = (Kd + CH - 1) / CH;
+  float *xs1 = smem;
+  float *xs2 = smem + (size_t)M * nC * CH;
+  load_x_plain<T, M>(xs1, h1, d, m_valid, Kd, nC);
+  load_x_plain<T, M>(xs2, h2, d, m_valid, Kd, nC);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int Gseg = (d + GV_R - 1) / GV_R;
+  const int G = K * Gseg;
+  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+    const int k = g / Gseg, gl = g % Gseg;
+    const bool first = (k < K / 2);
+    const float *xs = first ? xs1 : xs2;
+    const float *src = first ? h1 : h2;
+    const T *Wm = w_mlp + (size_t)k * d * d;
+    const T *rows[GV_R];
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)min(gl * GV_R + r, d - 1) * Kd;
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        const int n = gl * GV_R + r;
+        if (n < d) {
+          const float pek = Elem<T>::to_f32(pe[(size_t)k * d + n]);
+          #pragma unroll
+          for (int m = 0; m < M; ++m)
+            if (m < m_valid) Hp[((size_t)m * K + k) * d + n] = src[(size_t)m * d + n] + silu_f(acc[r][m]) + pek;
+        }
+      }
+    }
+  }
+}
+
+// ---- host launchers ---------------------------------------------------------------------------------
+static inline int gv_grid(int groups, int cap = 1024) {
+  int g = (groups + 3) / 4;
+  return g < 1 ? 1 : (g > cap ? cap : g);
+}
+template <typename T> static inline size_t gv_xs_bytes(int M, int Kd) {
+  constexpr int CH = XLayout<T>::CH;
+  return (size_t)M * ((Kd + CH - 1) / CH) * CH * sizeof(float);
+}
+
+#define GV_DISPATCH_M(Mv, BODY)                                   \
+  switch (Mv) {                                                    \
+    case 1: { constexpr int MM = 1; BODY; } break;                 \
+    case 2: { constexpr int MM = 2; BODY; } break;                 \
+    case 3: case 4: { constexpr int MM = 4; BODY; } break;         \
+    case 5: { constexpr int MM = 5; BODY; } break;                 \
+    default: { constexpr int MM = 8; BODY; } break;                \
+  }
+
+template <typename T, typename Kern> static hipError_t gv_set_smem(Kern kern, size_t bytes) {
+  if (bytes > 48 * 1024) return hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  return hipSuccess;
+}
+
+template <typename T>
+hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const void *embed, const int32_t *tok,
+                            int vocab, int d, int M, float *out, uint32_t *dev_status) {
+  if (M < 1 || M > 8) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  GV_DISPATCH_M(M, {
+    const size_t sm = gv_xs_bytes<T>(MM, 2 * d);
+    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
+    e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W, u,
+                       (const T *)embed, tok, vocab, d, M, out, dev_status);
+  });
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int n_heads, int d_h, int M,
+                          float eps, float theta, const int32_t *sal_len, int max_kv, void *kv_stage, float *qbuf,
+                          uint32_t *dev_status) {
+  if (M < 1 || M > 8 || d % 4 || d_h % 4) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  GV_DISPATCH_M(M, {
+    const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
+    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
+    e = gv_set_smem<T>(k_sal_qkv<T, MM>, sm);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_sal_qkv<T, MM>), dim3(gv_grid(3 * d / 4)), dim3(GV_THREADS), sm, st, (const T *)lw.wq,
+                       (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1, x, d, n_heads, d_h, M, eps, theta, sal_len,
+                       max_kv, (T *)kv_stage, qbuf, dev_status);
+  });
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const void *w2, int n_seg, int seg_rows, int Kd,
+                         const float *x, int ldx, int M, const float *res, float *o0, float *o1, float *o2, int ldo) {
+  if (M < 1 || M > 8 || Kd % 8) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  GV_DISPATCH_M(M, {
+    const size_t sm = gv_xs_bytes<T>(MM, Kd);
+    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
+    e = gv_set_smem<T>(k_linear<T, MM>, sm);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_linear<T, MM>), dim3(gv_grid(n_seg * ((seg_rows + 3) / 4))), dim3(GV_THREADS), sm, st,
+                       (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows, Kd, x, ldx, M, res, o0, o1, o2, ldo);
+  });
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_gate_up(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int f, int M, float eps,
+                          float *act) {
+  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  GV_DISPATCH_M(M, {
+    const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
+    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
+    e = gv_set_smem<T>(k_gate_up<T, MM>, sm);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_gate_up<T, MM>), dim3(gv_grid((f + 1) / 2)), dim3(GV_THREADS), sm, st, (const T *)lw.w_gate,
+                       (const T *)lw.w_up, (const T *)lw.rms2, x, d, f, M, eps, act);
+  });
+  return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, const float *h1, const float *h2, int d,
+                           int K, int M, float *Hp) {
+  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  hipError_t e = hipSuccess;
+  GV_DISPATCH_M(M, {
+    const size_t sm = 2 * gv_xs_bytes<T>(MM, d);
+    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
+    e = gv_set_smem<T>(k_head_mlp<T, MM>, sm);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((k_head_mlp<T, MM>), dim3(gv_grid(K * ((d + 3) / 4))), dim3(GV_THREADS), sm, st, (const T *)w_mlp,
+                       (const T *)pe, h1, h2, d, K, M, Hp);
+  });
+  return hipGetLastError();
+}
+
+#define INSTANTIATE(T)                                                                                                   \
+  template hipError_t launch_fc_concat<T>(hipStream_t, const void *, const float *, const void *, const int32_t *, int, \
+                                          int, int, float *, uint32_t *);                                               \
+  template hipError_t launch_sal_qkv<T>(hipStream_t, const amph_layer_w &, const float *, int, int, int, int, float,    \
+                                        float, const int32_t *, int, void *, float *, uint32_t *);                      \
+  template hipError_t launch_linear<T>(hipStream_t, const void *, const void *, const void *, int, int, int,            \
+                                       const float *, int, int, const float *, float *, float *, float *, int);         \
+  template hipError_t launch_gate_up<T>(hipStream_t, const amph_layer_w &, const float *, int, int, int, float, float *); \
+  template hipError_t launch_head_mlp<T>(hipStream_t, const void *, const void *, const float *, const float *, int,    \
+                                         int, int, float *);
+INSTANTIATE(float)
+INSTANTIATE(bf16_t)
+
+}  // namespace amph

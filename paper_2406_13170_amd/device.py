@@ -1,0 +1,45 @@
+"""Host->device marshalling of synthetic tensors (data movement and layout only, no arithmetic)."""
+from __future__ import annotations
+
+from typing import Dict
+
+import numpy as np
+import torch
+
+from .binding import AMPH_BF16, AMPH_F32
+
+
+def dtype_code(name: str) -> int:
+    return AMPH_BF16 if name == "bf16" else AMPH_F32
+
+
+def torch_dtype(name: str):
+    return torch.bfloat16 if name == "bf16" else torch.float32
+
+
+def to_device(t, device="cuda:0") -> torch.Tensor:
+    """synth_inputs.Tensor -> device tensor holding exactly the same values (bf16 patterns or float32)."""
+    if t.dtype == "bf16":
+        return torch.from_numpy(t.dev.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(t.dev)).to(device)
+
+
+def layer_to_device(lw: Dict[str, object], device="cuda:0") -> Dict[str, torch.Tensor]:
+    return {k: to_device(v, device) for k, v in lw.items()}
+
+
+def draft_to_device(dw: Dict[str, object], device="cuda:0") -> Dict[str, object]:
+    out = {}
+    for k, v in dw.items():
+        if k == "sal":
+            out[k] = [layer_to_device(l, device) for l in v]
+        elif k == "fc":
+            out[k] = [to_device(x, device) for x in v]
+        else:
+            out[k] = to_device(v, device)
+    return out
+
+
+def values_to_dim_major(v_rows: torch.Tensor) -> torch.Tensor:
+    """[..., rows, head_dim] -> [..., head_dim, rows] contiguous: the value-cache layout of amph_verify_attn."""
+    return v_rows.transpose(-1, -2).contiguous()

@@ -1,0 +1,108 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, validates configurations, and its host-side tree tables equal the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import amphista_oracle as orc
+from paper_2406_13170_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "amph.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(amph_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = header_functions()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in amph.h but not exported"
+    assert sorted(B.EXPORTS) == names, "binding and header disagree on the set of entry points"
+
+
+def base_cfg(**kw):
+    c = dict(d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024, K=4, topk=4, max_tree=16, max_kv=160, batch=1,
+             dtype=B.AMPH_F32, rms_eps=1e-6, rope_theta=10000.0)
+    c.update(kw)
+    return B.amph_config(*[c[k] for k in ("d_model", "n_heads", "head_dim", "d_ffn", "vocab", "K", "topk", "max_tree",
+                                          "max_kv", "batch", "dtype", "rms_eps", "rope_theta")])
+
+
+@pytest.mark.parametrize("kw,expect", [
+    (dict(dtype=7), B.AMPH_EINVAL),
+    (dict(d_model=0), B.AMPH_EINVAL),
+    (dict(head_dim=96, n_heads=4, d_model=384), B.AMPH_ESHAPE),
+    (dict(d_model=320), B.AMPH_ESHAPE),              # != n_heads * head_dim
+    (dict(topk=17), B.AMPH_ESHAPE),
+    (dict(K=9), B.AMPH_ESHAPE),
+    (dict(max_tree=129), B.AMPH_ESHAPE),
+    (dict(max_kv=100), B.AMPH_ESHAPE),               # not a multiple of 32
+    (dict(rope_theta=0.5), B.AMPH_EINVAL),
+])
+def test_create_rejects_bad_configs_before_touching_the_device(kw, expect):
+    h = C.c_void_p()
+    cfg = base_cfg(**kw)
+    assert B.lib().amph_create(C.byref(cfg), C.byref(h)) == expect
+    assert not h.value
+
+
+def test_create_null_arguments():
+    h = C.c_void_p()
+    assert B.lib().amph_create(None, C.byref(h)) == B.AMPH_EINVAL
+
+
+@pytest.mark.parametrize("T,caps", [(16, (4, 2, 2, 2)), (64, (10,) * 4), (96, (10,) * 5), (22, (10,) * 4), (2, (1,))])
+def test_tree_tables_equal_the_oracle(T, caps):
+    K = len(caps)
+    paths = si.tree_paths(T, caps)
+    rng = np.random.default_rng(0)
+    shuffled = [paths[i] for i in rng.permutation(len(paths))]      # any order is accepted
+    t = B.Tree(shuffled, K)
+    o = orc.tree_from_paths(paths, K)
+    assert t.T == o.T and t.n_leaves == len(o.leaves)
+    np.testing.assert_array_equal(t.parent, o.parent)
+    np.testing.assert_array_equal(t.depth, o.depth)
+    np.testing.assert_array_equal(t.rank, o.rank)
+    np.testing.assert_array_equal(t.mask_bool(), o.mask)
+    np.testing.assert_array_equal(t.retrieve, o.retrieve)
+    t.close()
+
+
+def test_tree_caption_example():
+    t = B.Tree(si.dense_tree_paths((2, 3)), 2)
+    assert (t.T, t.n_leaves) == (9, 6)
+
+
+def test_tree_root_only():
+    t = B.Tree([], 4)
+    assert (t.T, t.n_leaves) == (1, 1)
+    assert list(t.retrieve[0]) == [0, -1, -1, -1, -1]
+
+
+@pytest.mark.parametrize("paths,K,expect", [
+    ([(0,), (1, 0)], 4, B.AMPH_ETREE),                       # parent (1,) missing
+    ([(0,), (0,)], 4, B.AMPH_ETREE),                         # duplicate
+    ([(0,), (16,)], 4, B.AMPH_ESHAPE),                       # rank beyond AMPH_MAX_TOPK
+    ([(i,) for i in range(16)] * 8, 4, B.AMPH_ESHAPE),       # more than 128 nodes
+])
+def test_tree_create_rejects(paths, K, expect):
+    with pytest.raises(B.AmphError) as e:
+        B.Tree(paths, K)
+    assert e.value.status == expect
+
+
+def test_tree_rejects_rank_after_padding():
+    arr = np.array([[0, -1, 0, -1]], dtype=np.int32)
+    h = C.c_void_p()
+    assert B.lib().amph_tree_create(arr.ctypes.data_as(C.c_void_p), 1, 4, C.byref(h)) == B.AMPH_ETREE
+    arr = np.array([[-1, -1, -1, -1]], dtype=np.int32)
+    assert B.lib().amph_tree_create(arr.ctypes.data_as(C.c_void_p), 1, 4, C.byref(h)) == B.AMPH_ETREE

@@ -1,0 +1,203 @@
+"""GPU parity of the single kernels behind the C ABI against the CPU oracle, element by element, on
+seeded inputs: the weight-streaming GEMV, the matrix-core skinny GEMM, tree-masked verification
+attention, candidate-tree construction and greedy acceptance."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+from oracle import amphista_oracle as orc
+from paper_2406_13170_amd import binding as B
+from paper_2406_13170_amd import device as D
+
+from gpu_common import (DEV, TOL, act_to_dev, assert_rows_close, cfg_tensor_to_dev, f32_to_dev, i32_to_dev, make_ctx,
+                        np_of, say)
+
+pytestmark = pytest.mark.gpu
+
+
+# ---------------------------------------------------------------------------- GEMV (A1-A5 building block)
+@pytest.mark.parametrize("cfg,M,N,Kd", [
+    (si.TINY, 1, 256, 512), (si.TINY, 4, 1024, 256), (si.TINY, 1, 256, 688), (si.TINY, 5, 77, 264),
+    (si.MINI, 1, 512, 1024), (si.MINI, 4, 2048, 512), (si.MINI, 1, 512, 1376), (si.MINI, 8, 203, 520), (si.MINI, 3, 64, 8),
+    (si.V7B, 1, 4096, 4096), (si.V7B, 1, 4096, 11008), (si.V7B, 4, 32000, 4096),
+])
+def test_gemv_matches_oracle(cfg, M, N, Kd):
+    say(f"gemv {cfg.name} M={M} N={N} Kd={Kd}")
+    ctx = make_ctx(cfg)
+    W = si.normal(cfg, 11, f"gemv.W.{N}.{Kd}", (N, Kd), si.W_STD)
+    x = si.as_f32_exact(cfg, 11, f"gemv.x.{M}.{Kd}", (M, Kd), 1.0)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    ctx.amph_gemv(f32_to_dev(x), cfg_tensor_to_dev(W), y, M, N, Kd)
+    torch.cuda.synchronize()
+    ref = orc.linear(W.f32, x)
+    assert_rows_close(np_of(y), ref, 1e-4, "gemv")          # exact products, float32 accumulation in both dtypes
+
+
+# ---------------------------------------------------------------------------- skinny GEMM (A7/A9 building block)
+@pytest.mark.parametrize("cfg,M,N,Kd,split", [
+    (si.TINY, 16, 256, 256, 1), (si.TINY, 16, 256, 688 // 16 * 16, 2), (si.TINY, 37, 100, 256, 0),
+    (si.MINI, 64, 512, 512, 1), (si.MINI, 64, 512, 1376, 4), (si.MINI, 130, 203, 512, 2), (si.MINI, 7, 64, 32, 1),
+    (si.MINI, 64, 2048, 512, 8),
+    (si.V7B, 64, 4096, 4096, 0), (si.V7B, 64, 4096, 11008, 0), (si.V7B, 64, 1024, 4096, 8),
+])
+def test_gemm_matches_oracle(cfg, M, N, Kd, split):
+    say(f"gemm {cfg.name} M={M} N={N} Kd={Kd} split={split}")
+    ctx = make_ctx(cfg)
+    W = si.normal(cfg, 12, f"gemm.W.{N}.{Kd}", (N, Kd), si.W_STD)
+    x = si.normal(cfg, 12, f"gemm.x.{M}.{Kd}", (M, Kd), 1.0)
+    y = torch.full((M, N), float("nan"), dtype=torch.float32, device=DEV)
+    ctx.amph_gemm(cfg_tensor_to_dev(x), cfg_tensor_to_dev(W), y, M, N, Kd, split)
+    torch.cuda.synchronize()
+    ref = orc.linear(W.f32, x.f32)
+    assert_rows_close(np_of(y), ref, 1e-4, "gemm")
+    # split-K partials are folded in a fixed order: a second run is bit-identical
+    y2 = torch.empty_like(y)
+    ctx.amph_gemm(cfg_tensor_to_dev(x), cfg_tensor_to_dev(W), y2, M, N, Kd, split)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+
+
+# ---------------------------------------------------------------------------- A8 tree-masked attention
+def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None):
+    K = len(caps)
+    cfgx = si.with_(cfg, batch=B_, K=K, topk=min(16, max(caps)))
+    max_kv = (L + T + 31) // 32 * 32 + 32
+    ctx = make_ctx(cfgx, T=T, batch=B_, max_kv=max_kv)
+    paths = si.tree_paths(T, caps)
+    tree = B.Tree(paths, K)
+    otree = orc.tree_from_paths(paths, K)
+    n_h, d_h = cfg.n_heads, cfg.head_dim
+    q = si.normal(cfgx, seed, "va.q", (B_, T, n_h, d_h), 1.0)
+    k = si.normal(cfgx, seed, "va.k", (B_, n_h, L + T, d_h), 1.0)
+    v = si.normal(cfgx, seed, "va.v", (B_, n_h, L + T, d_h), 1.0)
+    tdt = D.torch_dtype(cfg.dtype)
+    # caches start as NaN everywhere outside the valid rows: nothing beyond L + T may leak in
+    kc = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
+    vc = torch.full((B_, n_h, d_h, max_kv), float("nan"), dtype=tdt, device=DEV)
+    kc[:, :, :L + T] = cfg_tensor_to_dev(k)
+    vc[:, :, :, :L + T] = D.values_to_dim_major(cfg_tensor_to_dev(v))
+    out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
+    kv_len = i32_to_dev(np.full(B_, L))
+    ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), kc, vc, kv_len, out)
+    torch.cuda.synchronize()
+    assert ctx.device_status() == 0
+    got = np_of(out)
+    hs = range(n_h) if heads is None else heads
+    worst = 0.0
+    for b in range(B_):
+        for h in hs:
+            ref = orc.tree_attention(q.f32[b][:, h:h + 1], k.f32[b][h:h + 1], v.f32[b][h:h + 1], L, otree.mask)
+            worst = max(worst, assert_rows_close(got[b][:, h], ref[:, 0], TOL[cfg.dtype], f"verify_attn b={b} h={h}"))
+    return worst
+
+
+@pytest.mark.parametrize("cfg,T,caps,L", [
+    (si.TINY, 16, (4, 2, 2, 2), 128),
+    (si.TINY, 16, (4, 2, 2, 2), 0),             # empty cache: only root/ancestors/self
+    (si.TINY, 22, (10,) * 4, 37),               # ragged: 22 queries in 2 blocks, L not a multiple of the key step
+    (si.TINY, 5, (1, 1, 1, 1), 9),              # chain tree = causal attention
+    (si.MINI, 64, (10,) * 4, 200),
+    (si.MINI, 64, (10,) * 4, 1),
+    (si.MINI, 96, (10,) * 5, 333),              # two query groups of three 16-query blocks
+    (si.MINI, 35, (10,) * 4, 1000),
+])
+def test_verify_attn_matches_oracle(cfg, T, caps, L):
+    say(f"verify_attn {cfg.name} T={T} L={L}")
+    worst = verify_case(cfg, T, caps, L)
+    say(f"  worst row error {worst:.2e}")
+
+
+def test_verify_attn_batch_independent_lengths_share_a_launch():
+    say("verify_attn batch=3 (same L per element in this case; caches independent)")
+    verify_case(si.MINI, 64, (10,) * 4, 77, B_=3)
+
+
+def test_verify_attn_vicuna7b_shape():
+    """Full 7B layer shape (32 heads x 128, L = 1024, T = 64) in the launch configuration the bench uses;
+    every head checked against the oracle."""
+    say("verify_attn vicuna7b L=1024 T=64")
+    worst = verify_case(si.V7B, 64, (10,) * 4, 1024)
+    say(f"  worst row error {worst:.2e}")
+
+
+def test_verify_attn_flags_cache_overflow():
+    cfg = si.TINY
+    ctx = make_ctx(cfg, T=16, max_kv=64)
+    tree = B.Tree(si.tree_paths(16, (4, 2, 2, 2)), 4)
+    tdt = D.torch_dtype(cfg.dtype)
+    q = torch.zeros((1, 16, cfg.n_heads, cfg.head_dim), dtype=tdt, device=DEV)
+    kc = torch.zeros((1, cfg.n_heads, 64, cfg.head_dim), dtype=tdt, device=DEV)
+    vc = torch.zeros((1, cfg.n_heads, cfg.head_dim, 64), dtype=tdt, device=DEV)
+    out = torch.full_like(q, 7.0)
+    ctx.amph_verify_attn(tree, q, kc, vc, i32_to_dev([60]), out)       # 60 + 16 > 64
+    assert ctx.device_status() == B.AMPH_DEV_KV_OVERFLOW
+    assert torch.all(out == 7.0)                                        # nothing written
+    assert ctx.device_status() == 0                                     # the flag was cleared by the read
+
+
+# ---------------------------------------------------------------------------- A6 / A10 integer work
+@pytest.mark.parametrize("T,caps,B_", [(16, (4, 2, 2, 2), 1), (64, (10,) * 4, 1), (96, (10,) * 5, 4)])
+def test_tree_build_and_accept_are_bit_exact(T, caps, B_):
+    say(f"tree_build/accept T={T} B={B_}")
+    K = len(caps)
+    cfg = si.with_(si.MINI, K=K, batch=B_, topk=10 if caps[0] > 4 else 4)
+    ctx = make_ctx(cfg, T=T, batch=B_)
+    paths = si.tree_paths(T, caps)
+    tree = B.Tree(paths, K)
+    otree = orc.tree_from_paths(paths, K)
+    rng = np.random.default_rng(5)
+    for trial in range(8):
+        vocab = 13                      # tiny vocabulary so that many drafts hit the target's choice
+        topk = np.stack([[rng.permutation(vocab)[:cfg.topk] for _ in range(K)] for _ in range(B_)]).astype(np.int32)
+        root = rng.integers(0, vocab, size=B_).astype(np.int32)
+        kvl = rng.integers(0, 1000, size=B_).astype(np.int32)
+        tok = torch.empty((B_, T), dtype=torch.int32, device=DEV)
+        pos = torch.empty((B_, T), dtype=torch.int32, device=DEV)
+        ctx.amph_tree_build(tree, i32_to_dev(root), i32_to_dev(topk), i32_to_dev(kvl), tok, pos)
+        tgt = rng.integers(0, vocab, size=(B_, T)).astype(np.int32)
+        a_len = torch.empty(B_, dtype=torch.int32, device=DEV)
+        a_path = torch.empty((B_, K + 1), dtype=torch.int32, device=DEV)
+        nxt = torch.empty(B_, dtype=torch.int32, device=DEV)
+        best = torch.empty(B_, dtype=torch.int32, device=DEV)
+        ctx.amph_accept(tree, tok, i32_to_dev(tgt), None, a_len, a_path, nxt, best)
+        torch.cuda.synchronize()
+        for b in range(B_):
+            o_tok, o_pos = orc.tree_tokens(otree, int(root[b]), topk[b], int(kvl[b]))
+            np.testing.assert_array_equal(np_of(tok)[b], o_tok)
+            np.testing.assert_array_equal(np_of(pos)[b], o_pos)
+            oa, opath, onxt, obest = orc.accept_greedy(otree, o_tok, tgt[b])
+            assert int(a_len[b]) == oa and int(best[b]) == obest and int(nxt[b]) == onxt
+            np.testing.assert_array_equal(np_of(a_path)[b], opath)
+
+
+def test_accept_from_logits_takes_argmax_with_lowest_id_on_ties():
+    cfg = si.with_(si.TINY, vocab=1024)
+    T, K = 16, 4
+    ctx = make_ctx(cfg, T=T)
+    paths = si.tree_paths(T, (4, 2, 2, 2))
+    tree = B.Tree(paths, K)
+    otree = orc.tree_from_paths(paths, K)
+    rng = np.random.default_rng(6)
+    logits = rng.standard_normal((1, T, cfg.vocab)).astype(np.float32)
+    logits[0, :, 700] = logits[0].max(axis=1) + 1.0
+    logits[0, :, 300] = logits[0, :, 700]                 # exact tie: 300 must win
+    logits[0, 3, 5] = logits[0, 3, 300]                   # three-way tie at node 3: 5 wins
+    tgt = np.array([orc.row_argmax(r) for r in logits[0]], dtype=np.int32)
+    assert tgt[0] == 300 and tgt[3] == 5
+    tok = np.zeros(T, dtype=np.int32)
+    tok[1:] = rng.integers(0, cfg.vocab, size=T - 1)
+    # plant a full accepted path so that the logits-derived argmax decides every hop
+    path = [int(n) for n in otree.retrieve[np.argmax((otree.retrieve >= 0).sum(axis=1))] if n >= 0]
+    for par, ch in zip(path[:-1], path[1:]):
+        tok[ch] = tgt[par]
+    a_len = torch.empty(1, dtype=torch.int32, device=DEV)
+    a_path = torch.empty((1, K + 1), dtype=torch.int32, device=DEV)
+    nxt = torch.empty(1, dtype=torch.int32, device=DEV)
+    best = torch.empty(1, dtype=torch.int32, device=DEV)
+    ctx.amph_accept(tree, i32_to_dev(tok[None]), None, f32_to_dev(logits), a_len, a_path, nxt, best)
+    torch.cuda.synchronize()
+    oa, opath, onxt, obest = orc.accept_greedy(otree, tok, tgt)
+    assert oa == 4
+    assert (int(a_len[0]), int(best[0]), int(nxt[0])) == (oa, obest, onxt)
+    np.testing.assert_array_equal(np_of(a_path)[0], opath)
