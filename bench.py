@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the Amphista draft+verify step on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input, all through the C ABI:
+amph_draft (Eq. 1-6) -> amph_tree_build -> amph_target_forward (32 decoder layers with tree attention,
+final norm, LM head, argmax) -> amph_accept.  Workload at N = 1: Vicuna-7B shapes (configurations 2 + 3:
+hidden 4096, 32 x 128 heads, FFN 11008, vocab 32000, K = 4 heads, top-10, 64-node tree, KV length 1024,
+SAL cache 1024, batch 1, bf16 weights N(0, 0.02^2) generated on the device, seed 0).
+
+Prints one JSON line with steps/s, the roofline of the dominant kernel (timed live with HIP events
+around each of its launches inside the timed region) and the CPU oracle's rate on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algo_bytes(kind: str, c, M: int) -> float:
+    """Algorithmic bytes one launch of `kind` must move: every weight/cache byte once plus the
+    activations it reads and writes (bf16 = 2 B, float32 = 4 B)."""
+    e = 2 if c.dtype == "bf16" else 4
+    d, f, V, K, L, T, B = c.d_model, c.d_ffn, c.vocab, c.K, c.kv_len, c.T, c.batch
+    Ls = c.sal_len
+    return {
+        "fc": 2 * d * d * e + B * (3 * d) * 4,
+        "sal_qkv": 3 * d * d * e + B * d * 4 * 2 + 2 * B * d * e,
+        "sal_attn": 2 * B * (Ls + 1) * d * e + 2 * B * d * 4,
+        "sal_wo": d * d * e + 3 * B * d * 4,
+        "sal_gateup": 2 * f * d * e + B * (d + f) * 4,
+        "sal_down": d * f * e + B * (f + 2 * d) * 4,
+        "head_mlp": K * d * d * e + B * (2 * d + K * d) * 4,
+        "aeb_qkv": 3 * d * d * e + 4 * B * K * d * 4,
+        "aeb_attn": 4 * B * K * d * 4,
+        "aeb_wo": d * d * e + 2 * B * K * d * 4,
+        "lm_head": V * d * e + B * K * (d + V) * 4,
+        "topk": B * K * V * 4,
+        "t_rmsnorm": M * d * (4 + e),
+        "t_qkv": 3 * d * d * e + M * d * e + 3 * M * d * e,
+        "verify": 2 * B * (L + T) * d * e + 2 * M * d * e,
+        "t_wo": d * d * e + M * d * e + 2 * M * d * 4,
+        "t_gateup": 2 * f * d * e + M * d * e + M * f * e,
+        "t_down": d * f * e + M * f * e + 2 * M * d * 4,
+        "t_lmhead": V * d * e + M * d * e + M * 4,
+    }[kind]
+
+
+def step_bytes(c, M: int, n_layers: int) -> float:
+    per_layer = sum(algo_bytes(k, c, M) for k in ("t_qkv", "verify", "t_wo", "t_gateup", "t_down")) + 2 * algo_bytes("t_rmsnorm", c, M)
+    draft = 2 * sum(algo_bytes(k, c, M) for k in ("fc", "sal_qkv", "sal_attn", "sal_wo", "sal_gateup", "sal_down")) + \
+        sum(algo_bytes(k, c, M) for k in ("head_mlp", "aeb_qkv", "aeb_attn", "aeb_wo", "lm_head", "topk"))
+    return draft + n_layers * per_layer + algo_bytes("t_rmsnorm", c, M) + algo_bytes("t_lmhead", c, M)
+
+
+def cpu_baseline(cfg, n_layers: int):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload: the
+    whole draft, ONE of the n_layers target layers over the 64 tree tokens, and the final norm + LM head;
+    the step time is t_draft + n_layers * t_layer + t_head."""
+    import numpy as np
+    import synth_inputs as si
+    from oracle import amphista_oracle as orc
+    f32l = lambda lw: {k: v.f32 for k, v in lw.items()}
+    t0 = time.time()
+    dw = si.draft_weights(cfg, 0)
+    dwo = dict(embed=dw["embed"].f32, fc=[x.f32 for x in dw["fc"]], sal=[f32l(l) for l in dw["sal"]], mlp=dw["mlp"].f32,
+               pe=dw["pe"].f32, aeb_wq=dw["aeb_wq"].f32, aeb_wk=dw["aeb_wk"].f32, aeb_wv=dw["aeb_wv"].f32,
+               aeb_wo=dw["aeb_wo"].f32, lm_head=dw["lm_head"].f32)
+    n_h, d_h, d, L, Ls, T = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.kv_len, cfg.sal_len, cfg.T
+    h = si.as_f32_exact(cfg, 0, "bench.h", (d,), 1.0)
+    tok = int(si.tokens(cfg, 0, "bench.tok", (1,))[0])
+    sal_k = [si.normal(cfg, 0, f"sal{s}.k", (n_h, Ls, d_h), 1.0).f32 for s in range(2)]
+    sal_v = [si.normal(cfg, 0, f"sal{s}.v", (n_h, Ls, d_h), 1.0).f32 for s in range(2)]
+    log(f"[cpu_baseline] inputs for the draft generated in {time.time() - t0:.1f}s")
+    t1 = time.time()
+    dr = orc.draft(dwo, h, tok, sal_k, sal_v, n_h, cfg.topk, cfg.rms_eps, cfg.rope_theta)
+    t_draft = time.time() - t1
+    tree = orc.tree_from_paths(si.tree_paths(T, cfg.tree_caps), cfg.K)
+    tree_tok, tree_pos = orc.tree_tokens(tree, tok, dr["topk_idx"], L)
+    lw = f32l(si.decoder_layer(cfg, 0, "target.layer0"))
+    kc = si.normal(cfg, 0, "tkv0.k", (n_h, L, d_h), 1.0).f32
+    vc = si.normal(cfg, 0, "tkv0.v", (n_h, L, d_h), 1.0).f32
+    x = dwo["embed"][tree_tok]
+    t2 = time.time()
+    x1, _, _, _, _ = orc.decoder_layer_rows(x, lw, kc, vc, list(tree_pos), tree.mask, n_h, cfg.rms_eps, cfg.rope_theta)
+    t_layer = time.time() - t2
+    lm = si.normal(cfg, 0, "target.lm_head", (cfg.vocab, d), si.W_STD).f32
+    t3 = time.time()
+    hidden = orc.rmsnorm(x1, np.ones(d), cfg.rms_eps)
+    logits = orc.linear(lm, hidden)
+    tgt = np.array([orc.row_argmax(r) for r in logits], dtype=np.int32)
+    orc.accept_greedy(tree, tree_tok, tgt)
+    t_head = time.time() - t3
+    total = t_draft + n_layers * t_layer + t_head
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    log(f"[cpu_baseline] draft {t_draft:.2f}s, one layer {t_layer:.2f}s, head {t_head:.2f}s -> step {total:.1f}s")
+    return {"value": 1.0 / total, "unit": "steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"whole draft + 1 of {n_layers} target layers (T={T}, L={L}) + final norm/LM head/accept, "
+                      f"scaled: t_draft + {n_layers} * t_layer + t_head = {total:.1f} s per step"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="vicuna7b", choices=["vicuna7b", "vicuna13b", "tiny", "mini_bf16"])
+    ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
+    ap.add_argument("--profile-kind", default=None, help="kernel kind to time live (default: the one with the largest share)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    from paper_2406_13170_amd import binding as B
+    from paper_2406_13170_amd import device as D
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    cfg = si.CONFIGS[args.workload]
+    n_layers = cfg.n_layers if args.layers is None else args.layers
+    n_h, d_h, d, f, V, K, T, L, Ls, Bsz = (cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.d_ffn, cfg.vocab, cfg.K, cfg.T,
+                                           cfg.kv_len, cfg.sal_len, cfg.batch)
+    max_kv = cfg.max_kv
+    tdt = D.torch_dtype(cfg.dtype)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+
+    def randn(shape, std):
+        t = torch.randn(shape, generator=gen, device=dev, dtype=torch.float32)
+        return (t * std).to(tdt) if std != 1.0 else t.to(tdt)
+
+    def layer():
+        return dict(rms1=torch.ones(d, dtype=tdt, device=dev), rms2=torch.ones(d, dtype=tdt, device=dev),
+                    wq=randn((d, d), 0.02), wk=randn((d, d), 0.02), wv=randn((d, d), 0.02), wo=randn((d, d), 0.02),
+                    w_gate=randn((f, d), 0.02), w_up=randn((f, d), 0.02), w_down=randn((d, f), 0.02))
+
+    t0 = time.time()
+    dw = dict(embed=randn((V, d), 0.02), fc=[randn((d, 2 * d), 0.02) for _ in range(2)], sal=[layer() for _ in range(2)],
+              mlp=randn((K, d, d), 0.02), pe=randn((K, d), 0.02), aeb_wq=randn((d, d), 0.02), aeb_wk=randn((d, d), 0.02),
+              aeb_wv=randn((d, d), 0.02), aeb_wo=randn((d, d), 0.02), lm_head=randn((V, d), 0.02))
+    layers = [layer() for _ in range(n_layers)]
+    final_norm = torch.ones(d, dtype=tdt, device=dev)
+    t_lm_head = randn((V, d), 0.02)
+    k_caches = torch.zeros((max(n_layers, 1), Bsz, n_h, max_kv, d_h), dtype=tdt, device=dev)
+    v_caches = torch.zeros((max(n_layers, 1), Bsz, n_h, d_h, max_kv), dtype=tdt, device=dev)
+    for li in range(n_layers):
+        k_caches[li, :, :, :L] = randn((Bsz, n_h, L, d_h), 1.0)
+        v_caches[li, :, :, :, :L] = randn((Bsz, n_h, d_h, L), 1.0)
+    sal_kv = torch.zeros((2, Bsz, 2, n_h, max_kv, d_h), dtype=tdt, device=dev)
+    sal_kv[:, :, :, :, :Ls] = randn((2, Bsz, 2, n_h, Ls, d_h), 1.0)
+    h = torch.randn((Bsz, d), generator=gen, device=dev, dtype=torch.float32).to(tdt).float()
+    tok = torch.randint(0, V, (Bsz,), generator=gen, device=dev, dtype=torch.int32)
+    torch.cuda.synchronize()
+    log(f"[bench] {args.workload}: {n_layers} layers, weights on device in {time.time() - t0:.1f}s")
+
+    ctx = B.Context(d_model=d, n_heads=n_h, head_dim=d_h, d_ffn=f, vocab=V, K=K, topk=cfg.topk, max_tree=T, max_kv=max_kv,
+                    batch=Bsz, dtype=D.dtype_code(cfg.dtype), rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, device=dev)
+    tree = B.Tree(si.tree_paths(T, cfg.tree_caps), K)
+    dstruct = B.Context.draft_struct(dw)
+    structs = [B.Context.layer_struct(l) for l in layers]
+    i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=dev)
+    topk_idx, topk_val = i32(Bsz, K, cfg.topk), torch.zeros((Bsz, K, cfg.topk), dtype=torch.float32, device=dev)
+    tree_tok, tree_pos, tgt = i32(Bsz, T), i32(Bsz, T), i32(Bsz, T)
+    a_len, a_path, nxt, best = i32(Bsz), i32(Bsz, K + 1), i32(Bsz), i32(Bsz)
+    kv_len = torch.full((Bsz,), L, dtype=torch.int32, device=dev)
+    sal_len0 = torch.full((Bsz,), Ls, dtype=torch.int32, device=dev)
+    sal_len = sal_len0.clone()
+
+    def step():
+        sal_len.copy_(sal_len0)          # every step repeats the same work: the SAL cache does not grow across steps
+        ctx.amph_draft(dstruct, h, tok, sal_kv, sal_len, topk_idx, topk_val, None)
+        ctx.amph_tree_build(tree, tok, topk_idx, kv_len, tree_tok, tree_pos)
+        ctx.amph_target_forward(tree, structs, dw["embed"], final_norm, t_lm_head, tree_tok, tree_pos, k_caches, v_caches,
+                                kv_len, None, None, tgt)
+        ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    assert ctx.device_status() == 0, "device-side range check failed"
+
+    M = Bsz * T
+    kinds = B.KERNEL_KINDS
+    per_kind = {}
+    if args.breakdown or args.profile_kind is None:
+        for ki, name in enumerate(kinds):
+            ctx.amph_profile_kind(ki, 4096)
+            step()
+            ms, n = ctx.amph_profile_read()
+            per_kind[name] = (ms, n)
+        ctx.amph_profile_kind(-1, 0)
+        tot = sum(v[0] for v in per_kind.values())
+        log("[bench] per-kind kernel time in one step (HIP events around each launch):")
+        for name, (ms, n) in sorted(per_kind.items(), key=lambda kv: -kv[1][0]):
+            if n:
+                gbs = algo_bytes(name, cfg, M) * n / (ms * 1e-3) / 1e9
+                log(f"    {name:11s} {n:4d} launches {ms * 1e3:9.1f} us total {ms * 1e3 / n:8.2f} us avg {gbs:8.0f} GB/s "
+                    f"({gbs / HBM_PEAK_GBS * 100:5.1f}% of HBM peak)")
+        log(f"    sum of kernel time {tot * 1e3:.1f} us")
+    dominant = args.profile_kind or max(per_kind, key=lambda k: per_kind[k][0])
+    dom_id = kinds.index(dominant)
+
+    ctx.amph_profile_kind(dom_id, min(65536, 64 * args.steps + 64))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    dom_ms, dom_n = ctx.amph_profile_read()
+    ctx.amph_profile_kind(-1, 0)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    steps_per_s = 1e3 / ms_per_step
+    dom_avg_s = dom_ms * 1e-3 / max(dom_n, 1)
+    dom_bytes = algo_bytes(dominant, cfg, M)
+    achieved = dom_bytes / dom_avg_s / 1e9
+    sb = step_bytes(cfg, M, n_layers)
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{dominant}_{args.workload}.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("hbm_bytes_per_launch"):
+                traffic = float(line.split()[1])
+
+    out = {
+        "metric": "draft+verify steps/sec at Vicuna-7B shapes, 1 MI355X" if args.workload == "vicuna7b"
+                  else f"draft+verify steps/sec, {args.workload}",
+        "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload} full step: draft (K={K}, top-{cfg.topk}, SAL cache {Ls}) + {n_layers}-layer "
+                               f"tree verification (T={T}, L={L}) + greedy accept, batch {Bsz}",
+                   "layers": n_layers, "tree_nodes": T, "kv_len": L, "batch": Bsz},
+        "step_algorithmic_GB": sb / 1e9,
+        "step_hbm_frac": sb * steps_per_s / 1e9 / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "launches_timed": dom_n,
+                     "avg_launch_us": dom_avg_s * 1e6, "algorithmic_bytes_per_launch": dom_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, n_layers)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

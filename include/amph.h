@@ -171,6 +171,21 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
                                 void *k_caches, void *v_caches, const int32_t *kv_len, float *hidden_out,
                                 float *logits_out, int32_t *tgt_argmax, void *workspace);
 
+/* ---- per-kernel timing, for measurement ------------------------------------------------------------
+ * Every kernel launch inside amph_draft / amph_target_forward / amph_verify_attn belongs to one kind.
+ * amph_profile_kind selects one kind (or -1 for none): from then on each launch of that kind is
+ * bracketed by a pair of HIP events on the context's stream, up to max_launches launches.
+ * amph_profile_read SYNCHRONISES the stream, returns the summed elapsed time and the number of launches
+ * recorded since the last read, and resets the count.  Not for use under stream capture. */
+typedef enum {
+  AMPH_K_FC = 0, AMPH_K_SAL_QKV, AMPH_K_SAL_ATTN, AMPH_K_SAL_WO, AMPH_K_SAL_GATEUP, AMPH_K_SAL_DOWN, AMPH_K_HEAD_MLP,
+  AMPH_K_AEB_QKV, AMPH_K_AEB_ATTN, AMPH_K_AEB_WO, AMPH_K_LM_HEAD, AMPH_K_TOPK,
+  AMPH_K_T_RMSNORM, AMPH_K_T_QKV, AMPH_K_VERIFY, AMPH_K_T_WO, AMPH_K_T_GATEUP, AMPH_K_T_DOWN, AMPH_K_T_LMHEAD,
+  AMPH_K_COUNT
+} amph_kernel_kind;
+amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches);
+amph_status amph_profile_read(amph_ctx *ctx, double *total_ms /* host */, int *launches /* host */);
+
 /* ---- single linear layers, exported for per-kernel parity tests and micro-benchmarks ------------
  * amph_gemv: y[m, n] = sum_k x[m, k] W[n, k] for m < M <= 8 (weight-streaming vector kernel).
  *   x [M, Kd] float32, W [N, Kd] T, y [M, N] float32.  Kd must be a multiple of 8.

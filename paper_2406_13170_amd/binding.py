@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(HERE, "libamph.so")
 AMPH_OK, AMPH_EINVAL, AMPH_ESHAPE, AMPH_ETREE, AMPH_EHIP = 0, 1, 2, 3, 4
 AMPH_F32, AMPH_BF16 = 0, 1
 AMPH_DEV_SAL_OVERFLOW, AMPH_DEV_KV_OVERFLOW, AMPH_DEV_BAD_TOKEN = 1, 2, 4
+KERNEL_KINDS = ["fc", "sal_qkv", "sal_attn", "sal_wo", "sal_gateup", "sal_down", "head_mlp", "aeb_qkv", "aeb_attn", "aeb_wo",
+                "lm_head", "topk", "t_rmsnorm", "t_qkv", "verify", "t_wo", "t_gateup", "t_down", "t_lmhead"]
 STATUS_NAMES = {0: "AMPH_OK", 1: "AMPH_EINVAL", 2: "AMPH_ESHAPE", 3: "AMPH_ETREE", 4: "AMPH_EHIP"}
 
 
@@ -52,6 +54,8 @@ EXPORTS = {
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
     "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.c_int] + [C.c_void_p] * 12),
+    "amph_profile_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
+    "amph_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     "amph_gemv": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "amph_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
 }
@@ -228,6 +232,14 @@ class Context:
                                               _ptr(tree_tok), _ptr(tree_pos), _ptr(k_caches), _ptr(v_caches), _ptr(kv_len),
                                               _ptr(hidden_out), _ptr(logits_out), _ptr(tgt_argmax), _ptr(self.workspace)),
                     "amph_target_forward")
+
+    def amph_profile_kind(self, kind: int, max_launches: int = 4096):
+        self._check(lib().amph_profile_kind(self.handle, kind, max_launches), "amph_profile_kind")
+
+    def amph_profile_read(self):
+        ms, n = C.c_double(), C.c_int()
+        self._check(lib().amph_profile_read(self.handle, C.byref(ms), C.byref(n)), "amph_profile_read")
+        return ms.value, n.value
 
     def amph_gemv(self, x, W, y, M, N, Kd):
         self._check(lib().amph_gemv(self.handle, _ptr(x), _ptr(W), _ptr(y), M, N, Kd), "amph_gemv")

@@ -36,6 +36,9 @@ struct amph_ctx {
   std::string err = "";
   WsLayout ws;
   int esz = 2;
+  int prof_kind = -1;                 // amph_kernel_kind being timed, -1 = none
+  std::vector<hipEvent_t> prof_ev;    // start/stop pairs
+  size_t prof_used = 0;
 };
 
 struct amph_tree {
@@ -60,6 +63,18 @@ amph_status hip_fail(amph_ctx *ctx, hipError_t e, const char *where) {
   do {                                                      \
     hipError_t e__ = (expr);                                \
     if (e__ != hipSuccess) return hip_fail(ctx, e__, #expr); \
+  } while (0)
+
+// Launch `expr`; when its kind is the one being profiled, bracket it with a pair of events on the stream.
+#define PROF_TRY(ctx, kind, expr)                                                              \
+  do {                                                                                         \
+    const bool p__ = ((ctx)->prof_kind == (kind)) && ((ctx)->prof_used < (ctx)->prof_ev.size() / 2); \
+    if (p__) HIP_TRY(ctx, hipEventRecord((ctx)->prof_ev[2 * (ctx)->prof_used], (ctx)->stream));       \
+    HIP_TRY(ctx, expr);                                                                        \
+    if (p__) {                                                                                 \
+      HIP_TRY(ctx, hipEventRecord((ctx)->prof_ev[2 * (ctx)->prof_used + 1], (ctx)->stream));   \
+      (ctx)->prof_used++;                                                                      \
+    }                                                                                          \
   } while (0)
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -134,39 +149,39 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   for (int s = 0; s < 2; ++s) {
     const float *u = (s == 0) ? h_new : h[0];
     void *kv_stage = (T *)sal_kv + s * stage_stride;
-    HIP_TRY(ctx, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, B, x, ctx->dev_status));
-    HIP_TRY(ctx, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, B, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
+    PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, B, x, ctx->dev_status));
+    PROF_TRY(ctx, AMPH_K_SAL_QKV, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, B, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
                                    q, ctx->dev_status));
-    HIP_TRY(ctx, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, F(ctx->ws.sal_part),
+    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, F(ctx->ws.sal_part),
                                     ctx->counters + CNT_SAL, att));
-    HIP_TRY(ctx, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, B, x, y, nullptr, nullptr, d));
-    HIP_TRY(ctx, launch_gate_up<T>(st, w->sal[s], y, d, f, B, c.rms_eps, act));
-    HIP_TRY(ctx, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, B, y, h[s], nullptr, nullptr, d));
+    PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, B, x, y, nullptr, nullptr, d));
+    PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, B, c.rms_eps, act));
+    PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, B, y, h[s], nullptr, nullptr, d));
   }
   float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);
   float *attn_o = F(ctx->ws.attn_o);
   float *lg = logits ? logits : F(ctx->ws.logits);
-  HIP_TRY(ctx, launch_head_mlp<T>(st, w->mlp, w->pe, h[0], h[1], d, K, B, Hp));
+  PROF_TRY(ctx, AMPH_K_HEAD_MLP, launch_head_mlp<T>(st, w->mlp, w->pe, h[0], h[1], d, K, B, Hp));
   const int BK = B * K;
   for (int r0 = 0; r0 < BK; r0 += 8) {
     const int m = std::min(8, BK - r0);
     const size_t o = (size_t)r0 * d;
-    HIP_TRY(ctx, launch_linear<T>(st, w->aeb_wq, w->aeb_wk, w->aeb_wv, 3, d, d, Hp + o, d, m, nullptr, Qa + o, Ka + o,
+    PROF_TRY(ctx, AMPH_K_AEB_QKV, launch_linear<T>(st, w->aeb_wq, w->aeb_wk, w->aeb_wv, 3, d, d, Hp + o, d, m, nullptr, Qa + o, Ka + o,
                                   Va + o, d));
   }
-  HIP_TRY(ctx, launch_aeb_attn(st, Qa, Ka, Va, B, K, n_h, d_h, ctxa));
+  PROF_TRY(ctx, AMPH_K_AEB_ATTN, launch_aeb_attn(st, Qa, Ka, Va, B, K, n_h, d_h, ctxa));
   for (int r0 = 0; r0 < BK; r0 += 8) {
     const int m = std::min(8, BK - r0);
     const size_t o = (size_t)r0 * d;
-    HIP_TRY(ctx, launch_linear<T>(st, w->aeb_wo, nullptr, nullptr, 1, d, d, ctxa + o, d, m, nullptr, attn_o + o, nullptr,
+    PROF_TRY(ctx, AMPH_K_AEB_WO, launch_linear<T>(st, w->aeb_wo, nullptr, nullptr, 1, d, d, ctxa + o, d, m, nullptr, attn_o + o, nullptr,
                                   nullptr, d));
   }
   for (int r0 = 0; r0 < BK; r0 += 8) {
     const int m = std::min(8, BK - r0);
-    HIP_TRY(ctx, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
+    PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
                                   lg + (size_t)r0 * V, nullptr, nullptr, V));
   }
-  HIP_TRY(ctx, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1));
+  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1));
   return AMPH_OK;
 }
 
@@ -181,7 +196,7 @@ amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, con
   a.partials_cap = ctx->ws.ver_part_floats;
   a.counters = ctx->counters + CNT_VERIFY;
   a.dev_status = ctx->dev_status;
-  HIP_TRY(ctx, launch_verify_attn<T>(ctx->stream, a));
+  PROF_TRY(ctx, AMPH_K_VERIFY, launch_verify_attn<T>(ctx->stream, a));
   return AMPH_OK;
 }
 
@@ -212,37 +227,37 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   for (int li = 0; li < n_layers; ++li) {
     const amph_layer_w &lw = layers[li];
     void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
-    HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, lw.rms1, M, d, c.rms_eps, xn,
+    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, lw.rms1, M, d, c.rms_eps, xn,
                                         nullptr, ctx->dev_status));
     GemmArgs a = g;
     a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
     a.split_k = split_for(EPI_QKV_ROPE, 3, d, d);
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
-    HIP_TRY(ctx, launch_gemm<T>(st, EPI_QKV_ROPE, a));
+    PROF_TRY(ctx, AMPH_K_T_QKV, launch_gemm<T>(st, EPI_QKV_ROPE, a));
     if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
     a = g;
     a.w0 = lw.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = xres;
     a.split_k = split_for(EPI_RESIDUAL, 1, d, d);
-    HIP_TRY(ctx, launch_gemm<T>(st, EPI_RESIDUAL, a));
-    HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, nullptr, nullptr, V, lw.rms2, M, d, c.rms_eps, xn, nullptr,
+    PROF_TRY(ctx, AMPH_K_T_WO, launch_gemm<T>(st, EPI_RESIDUAL, a));
+    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, nullptr, nullptr, V, lw.rms2, M, d, c.rms_eps, xn, nullptr,
                                         ctx->dev_status));
     a = g;
     a.w0 = lw.w_gate; a.w1 = lw.w_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
     a.split_k = split_for(EPI_SWIGLU, 2, f, d);
-    HIP_TRY(ctx, launch_gemm<T>(st, EPI_SWIGLU, a));
+    PROF_TRY(ctx, AMPH_K_T_GATEUP, launch_gemm<T>(st, EPI_SWIGLU, a));
     a = g;
     a.w0 = lw.w_down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = xres;
     a.split_k = split_for(EPI_RESIDUAL, 1, d, f);
-    HIP_TRY(ctx, launch_gemm<T>(st, EPI_RESIDUAL, a));
+    PROF_TRY(ctx, AMPH_K_T_DOWN, launch_gemm<T>(st, EPI_RESIDUAL, a));
   }
-  HIP_TRY(ctx, launch_rmsnorm_rows<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, final_norm, M, d, c.rms_eps,
+  PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, final_norm, M, d, c.rms_eps,
                                       xn, hidden_out, ctx->dev_status));
   GemmArgs a = g;
   a.w0 = lm_head; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
   a.split_k = split_for(EPI_ARGMAX, 1, V, d);
   a.logits = logits_out; a.tgt = tgt_argmax;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
-  HIP_TRY(ctx, launch_gemm<T>(st, EPI_ARGMAX, a));
+  PROF_TRY(ctx, AMPH_K_T_LMHEAD, launch_gemm<T>(st, EPI_ARGMAX, a));
   return AMPH_OK;
 }
 
@@ -285,6 +300,7 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
 
 void amph_destroy(amph_ctx *ctx) {
   if (!ctx) return;
+  for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
   if (ctx->counters) (void)hipFree(ctx->counters);
   delete ctx;
 }
@@ -484,6 +500,35 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
                                v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
   return target_impl<float>(ctx, tree, layers, n_layers, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches, v_caches,
                             kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+}
+
+amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches) {
+  if (!ctx) return AMPH_EINVAL;
+  if (kind < -1 || kind >= AMPH_K_COUNT || max_launches < 0 || max_launches > 65536)
+    return fail(ctx, AMPH_EINVAL, "amph_profile_kind: bad kind or max_launches");
+  while (ctx->prof_ev.size() < (size_t)2 * max_launches) {
+    hipEvent_t e;
+    HIP_TRY(ctx, hipEventCreate(&e));
+    ctx->prof_ev.push_back(e);
+  }
+  ctx->prof_kind = kind;
+  ctx->prof_used = 0;
+  return AMPH_OK;
+}
+
+amph_status amph_profile_read(amph_ctx *ctx, double *total_ms, int *launches) {
+  if (!ctx || !total_ms || !launches) return AMPH_EINVAL;
+  HIP_TRY(ctx, hipStreamSynchronize(ctx->stream));
+  double tot = 0.0;
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0.f;
+    HIP_TRY(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = (int)ctx->prof_used;
+  ctx->prof_used = 0;
+  return AMPH_OK;
 }
 
 amph_status amph_gemv(amph_ctx *ctx, const float *x, const void *W, float *y, int M, int N, int Kd) {
