@@ -14,15 +14,14 @@ using namespace amph;
 
 namespace {
 
-constexpr size_t N_COUNTERS = 16384;
-constexpr size_t CNT_SAL = 9000, CNT_VERIFY = 10000;
+constexpr size_t N_COUNTERS = 64;      // device words owned by a context; word N_COUNTERS is the status word
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {   // byte offsets into the caller's workspace
-  size_t x, q, att, y, act, h[2], Hp, Qa, Ka, Va, ctxa, attn_o, logits, sal_part;        // draft
-  size_t xres, xn, qb, attb, actb, gemm_part, amax_val, amax_idx, ver_part, tgt_tmp;     // target
-  size_t gemm_part_floats, ver_part_floats;
+  size_t x, q, att, y, act, h[2], Hp, Qa, Ka, Va, ctxa, attn_o, logits, topk_ws;                 // draft
+  size_t xres, xn, qb, attb, actb, slabs, amax_val, amax_idx, ver_part, tgt_tmp, rope_cs;      // target
+  size_t slabs_floats, ver_part_floats;
   size_t total;
 };
 
@@ -90,25 +89,12 @@ WsLayout make_layout(const amph_config &c) {
   w.act = take(B * f * 4); w.h[0] = take(B * d * 4); w.h[1] = take(B * d * 4);
   w.Hp = take(BK * d * 4); w.Qa = take(BK * d * 4); w.Ka = take(BK * d * 4); w.Va = take(BK * d * 4);
   w.ctxa = take(BK * d * 4); w.attn_o = take(BK * d * 4); w.logits = take(BK * V * 4);
-  w.sal_part = take(sal_attn_ws_floats(c.n_heads, c.batch, c.head_dim, c.max_kv) * 4);
+  w.topk_ws = take(std::max(topk_ws_floats((int)BK, c.vocab, c.topk), topk_ws_floats((int)M, c.vocab, 1)) * 4);
   w.xres = take(M * d * 4); w.xn = take(M * d * esz); w.qb = take(M * d * esz); w.attb = take(M * d * esz);
   w.actb = take(M * f * esz);
-  // largest split-K partial buffer over the GEMMs of a layer and the LM head
-  const size_t mblocks = (M + 63) / 64;
-  size_t part = 0;
-  auto consider = [&](int epi, int n_seg, int rows, int Kd) {
-    const int tiles = gemm_tiles_n(epi, n_seg, rows, c.head_dim);
-    const int s = gemm_auto_split(tiles * (int)mblocks, Kd, (int)esz);
-    if (s > 1) part = std::max(part, (size_t)tiles * mblocks * s * 64 * 64 * 4);
-  };
-  consider(EPI_QKV_ROPE, 3, c.d_model, c.d_model);
-  consider(EPI_RESIDUAL, 1, c.d_model, c.d_model);
-  consider(EPI_SWIGLU, 2, c.d_ffn, c.d_model);
-  consider(EPI_RESIDUAL, 1, c.d_model, c.d_ffn);
-  consider(EPI_ARGMAX, 1, c.vocab, c.d_model);
-  part = std::max(part, (size_t)2048 * 64 * 64 * 4);       // amph_gemm: up to 2048 (tile, split) pairs
-  w.gemm_part = take(part);
-  w.gemm_part_floats = part / 4;
+  // partial slabs of the split-K GEMMs (Wo, W_down: up to 8 slabs of [M, d]); amph_gemm may use the same area
+  w.slabs_floats = std::max((size_t)8 * M * d, (size_t)8 * 1024 * 1024);
+  w.slabs = take(w.slabs_floats * 4);
   const size_t tilesV = (V + 63) / 64;
   w.amax_val = take(tilesV * M * 4); w.amax_idx = take(tilesV * M * 4);
   size_t vfl = 0;                                           // any tree size up to max_tree may be used
@@ -116,6 +102,7 @@ WsLayout make_layout(const amph_config &c) {
   w.ver_part = take(vfl * 4);
   w.ver_part_floats = vfl;
   w.tgt_tmp = take(M * 4);
+  w.rope_cs = take(M * (size_t)(c.head_dim / 2) * 8);
   w.total = at;
   return w;
 }
@@ -152,8 +139,7 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, B, x, ctx->dev_status));
     PROF_TRY(ctx, AMPH_K_SAL_QKV, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, B, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
                                    q, ctx->dev_status));
-    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, F(ctx->ws.sal_part),
-                                    ctx->counters + CNT_SAL, att));
+    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, att));
     PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, B, x, y, nullptr, nullptr, d));
     PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, B, c.rms_eps, act));
     PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, B, y, h[s], nullptr, nullptr, d));
@@ -181,7 +167,7 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
                                   lg + (size_t)r0 * V, nullptr, nullptr, V));
   }
-  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1));
+  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1, F(ctx->ws.topk_ws)));
   return AMPH_OK;
 }
 
@@ -194,7 +180,6 @@ amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, con
   a.B = c.batch; a.T = tree->T; a.n_heads = c.n_heads; a.d_h = c.head_dim; a.max_kv = c.max_kv;
   a.partials = (float *)((char *)workspace + ctx->ws.ver_part);
   a.partials_cap = ctx->ws.ver_part_floats;
-  a.counters = ctx->counters + CNT_VERIFY;
   a.dev_status = ctx->dev_status;
   PROF_TRY(ctx, AMPH_K_VERIFY, launch_verify_attn<T>(ctx->stream, a));
   return AMPH_OK;
@@ -212,52 +197,54 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   hipStream_t st = ctx->stream;
   char *ws = (char *)workspace;
   float *xres = (float *)(ws + ctx->ws.xres);
+  float *slabs = (float *)(ws + ctx->ws.slabs);
+  float2 *rope_cs = (float2 *)(ws + ctx->ws.rope_cs);
   void *xn = ws + ctx->ws.xn, *qb = ws + ctx->ws.qb, *attb = ws + ctx->ws.attb, *actb = ws + ctx->ws.actb;
   const size_t cache_layer = (size_t)B * n_h * c.max_kv * d_h;     // elements of T per layer
+  const size_t slab = (size_t)M * d;
   GemmArgs g{};
-  g.partials = (float *)(ws + ctx->ws.gemm_part);
-  g.partials_cap = ctx->ws.gemm_part_floats;
-  g.counters = ctx->counters;
   g.dev_status = ctx->dev_status;
-  g.M = M; g.T_nodes = Tn; g.n_heads = n_h; g.d_h = d_h; g.max_kv = c.max_kv; g.theta = c.rope_theta;
-  g.tree_pos = tree_pos; g.kv_len = kv_len;
-  auto split_for = [&](int epi, int n_seg, int rows, int Kd) {
-    return gemm_auto_split(gemm_tiles_n(epi, n_seg, rows, d_h) * mblocks, Kd, (int)sizeof(T));
+  g.M = M; g.T_nodes = Tn; g.n_heads = n_h; g.d_h = d_h; g.max_kv = c.max_kv;
+  g.rope_cs = rope_cs; g.kv_len = kv_len; g.split_k = 1;
+  auto split_for = [&](int rows, int Kd) {
+    int s = gemm_auto_split(gemm_tiles_n(EPI_STORE, 1, rows, d_h) * mblocks, Kd, (int)sizeof(T));
+    while (s > 1 && (size_t)s * slab > ctx->ws.slabs_floats) s /= 2;
+    return s;
   };
+  const int s_wo = split_for(d, d), s_down = split_for(d, f);
+  if (n_layers > 0) HIP_TRY(ctx, launch_rope_table(st, tree_pos, M, d_h, c.rope_theta, rope_cs));
+  int pending = 0;                        // slabs of the previous GEMM still to be added to the residual stream
   for (int li = 0; li < n_layers; ++li) {
     const amph_layer_w &lw = layers[li];
     void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
-    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, lw.rms1, M, d, c.rms_eps, xn,
-                                        nullptr, ctx->dev_status));
+    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, slabs, pending,
+                                                        slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status));
     GemmArgs a = g;
     a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
-    a.split_k = split_for(EPI_QKV_ROPE, 3, d, d);
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
     PROF_TRY(ctx, AMPH_K_T_QKV, launch_gemm<T>(st, EPI_QKV_ROPE, a));
     if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
     a = g;
-    a.w0 = lw.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = xres;
-    a.split_k = split_for(EPI_RESIDUAL, 1, d, d);
-    PROF_TRY(ctx, AMPH_K_T_WO, launch_gemm<T>(st, EPI_RESIDUAL, a));
-    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, nullptr, nullptr, V, lw.rms2, M, d, c.rms_eps, xn, nullptr,
-                                        ctx->dev_status));
+    a.w0 = lw.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
+    PROF_TRY(ctx, AMPH_K_T_WO, launch_gemm<T>(st, EPI_STORE, a));
+    PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, nullptr, nullptr, V, slabs, s_wo, slab, lw.rms2, M, d,
+                                                        c.rms_eps, xn, nullptr, ctx->dev_status));
     a = g;
     a.w0 = lw.w_gate; a.w1 = lw.w_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
-    a.split_k = split_for(EPI_SWIGLU, 2, f, d);
     PROF_TRY(ctx, AMPH_K_T_GATEUP, launch_gemm<T>(st, EPI_SWIGLU, a));
     a = g;
-    a.w0 = lw.w_down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = xres;
-    a.split_k = split_for(EPI_RESIDUAL, 1, d, f);
-    PROF_TRY(ctx, AMPH_K_T_DOWN, launch_gemm<T>(st, EPI_RESIDUAL, a));
+    a.w0 = lw.w_down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = slabs; a.split_k = s_down;
+    PROF_TRY(ctx, AMPH_K_T_DOWN, launch_gemm<T>(st, EPI_STORE, a));
+    pending = s_down;
   }
-  PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_rmsnorm_rows<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, final_norm, M, d, c.rms_eps,
-                                      xn, hidden_out, ctx->dev_status));
+  PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, slabs, pending,
+                                                      slab, final_norm, M, d, c.rms_eps, xn, hidden_out, ctx->dev_status));
   GemmArgs a = g;
   a.w0 = lm_head; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
-  a.split_k = split_for(EPI_ARGMAX, 1, V, d);
-  a.logits = logits_out; a.tgt = tgt_argmax;
+  a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
   PROF_TRY(ctx, AMPH_K_T_LMHEAD, launch_gemm<T>(st, EPI_ARGMAX, a));
+  HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_tiles_n(EPI_ARGMAX, 1, V, d_h), M, tgt_argmax));
   return AMPH_OK;
 }
 
@@ -468,7 +455,8 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
   if (tgt_logits) {
     if (!workspace) return fail(ctx, AMPH_EINVAL, "amph_accept: workspace needed with tgt_logits");
     int32_t *tmp = (int32_t *)((char *)workspace + ctx->ws.tgt_tmp);
-    HIP_TRY(ctx, launch_row_argmax(ctx->stream, tgt_logits, ctx->cfg.batch * tree->T, ctx->cfg.vocab, tmp));
+    HIP_TRY(ctx, launch_row_argmax(ctx->stream, tgt_logits, ctx->cfg.batch * tree->T, ctx->cfg.vocab, tmp,
+                                   (float *)((char *)workspace + ctx->ws.topk_ws)));
     tgt = tmp;
   }
   HIP_TRY(ctx, launch_accept(ctx->stream, tree->d_parent, tree->d_depth, tree->T, ctx->cfg.batch, ctx->cfg.K, tree_tok, tgt,
@@ -551,14 +539,15 @@ amph_status amph_gemm(amph_ctx *ctx, const void *x, const void *W, float *y, int
   const int tiles = (N + 63) / 64, mblocks = (M + 63) / 64;
   if (split_k == 0) split_k = gemm_auto_split(tiles * mblocks, Kd, ctx->esz);
   if (split_k != 1 && split_k != 2 && split_k != 4 && split_k != 8) return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k");
-  if ((size_t)tiles * mblocks * split_k > 2048) return fail(ctx, AMPH_ESHAPE, "amph_gemm: more than 2048 (tile, split) pairs");
+  if (split_k > 1 && (size_t)split_k * M * N > ctx->ws.slabs_floats)
+    return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k * M * N exceeds the workspace's slab area");
+  float *slabs = (float *)((char *)workspace + ctx->ws.slabs);
   GemmArgs a{};
   a.w0 = W; a.n_seg = 1; a.seg_rows = N; a.Kd = Kd; a.x = x; a.M = M; a.split_k = split_k;
-  a.partials = (float *)((char *)workspace + ctx->ws.gemm_part);
-  a.partials_cap = ctx->ws.gemm_part_floats;
-  a.counters = ctx->counters; a.out = y; a.dev_status = ctx->dev_status;
+  a.out = (split_k > 1) ? slabs : y; a.dev_status = ctx->dev_status;
   if (ctx->cfg.dtype == AMPH_BF16) HIP_TRY(ctx, launch_gemm<bf16_t>(ctx->stream, EPI_STORE, a));
   else HIP_TRY(ctx, launch_gemm<float>(ctx->stream, EPI_STORE, a));
+  if (split_k > 1) HIP_TRY(ctx, launch_sum_slabs(ctx->stream, slabs, split_k, (size_t)M * N, y));
   return AMPH_OK;
 }
 

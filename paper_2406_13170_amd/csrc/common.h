@@ -1,5 +1,5 @@
-// Shared device helpers for the gfx950 kernels: 16-byte fragments of float / bfloat16, wave
-// reductions and the "last workgroup to arrive finishes the job" counter protocol.
+// Shared device helpers for the gfx950 kernels: 16-byte fragments of float / bfloat16, the matrix-core
+// step on such fragments, and wave / block reductions.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -92,24 +92,5 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
 }
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
-
-// ---- last-arriver protocol -----------------------------------------------------------------------------
-// Each of `expected` workgroups calls this after writing its partial results to global memory.  The
-// one that arrives last gets true and may read all partials; it also resets the counter so the next
-// launch finds it at zero.  No workgroup ever waits for another, so the kernel cannot hang.
-__device__ __forceinline__ bool arrive_and_is_last(unsigned int *counter, unsigned int expected, int *s_flag) {
-  __threadfence();                      // release: this thread's partials are visible device-wide
-  __syncthreads();                      // ... for every thread of the block
-  if (threadIdx.x == 0) {
-    unsigned int old = atomicAdd(counter, 1u);
-    int last = (old == expected - 1u);
-    if (last) *counter = 0u;            // nobody else touches it any more in this launch
-    *s_flag = last;
-  }
-  __syncthreads();
-  const bool last = (*s_flag != 0);
-  if (last) __threadfence();            // acquire: see the other workgroups' partials
-  return last;
-}
 
 }  // namespace amph

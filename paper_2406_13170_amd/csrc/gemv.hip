@@ -42,10 +42,10 @@ __device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const fl
     for (int u = 0; u < GV_U; ++u) {
       const int k = (c0 + u) * CH + lane * PER;
       #pragma unroll
-      for (int r = 0; r < GV_R; ++r) {
-        if (k < Kd) w[u][r] = ldg16(rows[r] + k);
-        else w[u][r] = make_uint4(0u, 0u, 0u, 0u);
-      }
+      // Unconditional loads (a predicated load with a zero alternative makes the compiler wait for every
+      // load at the merge).  Lanes past the end re-read the row's first fragment; x is zero-padded there
+      // and weights are finite, so they add nothing.
+      for (int r = 0; r < GV_R; ++r) w[u][r] = ldg16(rows[r] + (k < Kd ? k : 0));
     }
     #pragma unroll
     for (int u = 0; u < GV_U; ++u) {

@@ -26,68 +26,67 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
                            int K, int M, float *Hp);
 
 // ---- small.hip (attention of the draft path, top-k, tree, accept, norms) ----
-int sal_attn_splits(int n_heads, int batch, int max_kv);
-size_t sal_attn_ws_floats(int n_heads, int batch, int d_h, int max_kv);
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *partials, unsigned int *counters, float *out);
+                           int n_heads, int d_h, int max_kv, float *out);
 hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, const float *V, int B, int K, int n_heads,
                            int d_h, float *ctx);
+// ws: topk_ws_floats(rows, V, k) floats of scratch for the per-wave candidates
+size_t topk_ws_floats(int rows, int V, int k);
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by);
-hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out);
+                            int32_t *advance, int n_advance, int advance_by, float *ws);
+hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws);
 hipError_t launch_tree_build(hipStream_t st, const int32_t *depth, const int32_t *rank, int T, int B, int K, int topk,
                              const int32_t *root_tok, const int32_t *topk_idx, const int32_t *kv_len, int32_t *tree_tok,
                              int32_t *tree_pos);
 hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *depth, int T, int B, int K,
                          const int32_t *tree_tok, const int32_t *tgt, int32_t *accept_len, int32_t *accept_path,
                          int32_t *next_tok, int32_t *best_node);
-// xn[m] = RMSNorm(x[m]) * g as T; when tok != NULL, x[m] is first gathered from embed[tok[m]] and also
-// written to x (float32).  hidden_out (float32, optional) receives the same normalised rows.
+// x[m] (+)= sum_s slabs[s][m] (or x[m] = embed[tok[m]] when tok != NULL); xn[m] = RMSNorm(x[m]) * g as T;
+// hidden_out (float32, optional) receives the same normalised rows.
 template <typename T>
-hipError_t launch_rmsnorm_rows(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
-                               const void *g, int rows, int d, float eps, void *xn, float *hidden_out,
-                               uint32_t *dev_status);
+hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
+                            const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
+                            void *xn, float *hidden_out, uint32_t *dev_status);
 
 // ---- gemm_skinny.hip (target path, rows on the matrix cores) ----
-enum GemmEpi { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
+enum GemmEpi { EPI_STORE = 0, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
 struct GemmArgs {
   const void *w0, *w1, *w2;   // stacked matrices (q,k,v | gate,up | single)
   int n_seg, seg_rows;        // rows per matrix
   int Kd;
   const void *x;              // [M, Kd] T
   int M;
-  int split_k;                // 1, 2, 4, 8
-  float *partials;            // [tiles_n * m_blocks][split_k][64 * BN] float32 (split_k > 1)
-  size_t partials_cap;        // floats available at partials
-  unsigned int *counters;     // one per (tile, m_block) plus one global
+  int split_k;                // 1, 2, 4, 8 (fused epilogues: 1)
   // epilogue operands
-  float *out;                 // EPI_STORE / EPI_RESIDUAL: [M, seg_rows] float32 (RESIDUAL: in place add)
+  float *out;                 // EPI_STORE: [split_k][M, seg_rows] float32 partial slabs
   float *logits;              // EPI_ARGMAX: optional [M, seg_rows]
   void *act;                  // EPI_SWIGLU: [M, f] T
   // QKV
   void *q_out;                // [M, d] T
   void *k_cache, *v_cache;    // this layer: [B, n_h, max_kv, d_h] and [B, n_h, d_h, max_kv] T
-  const int32_t *tree_pos;    // [M]
+  const float2 *rope_cs;      // [M, d_h/2] (cos, sin) of each row's position
   const int32_t *kv_len;      // [B]
   int T_nodes, n_heads, d_h, max_kv;
-  float theta;
   // ARGMAX
-  float *amax_val;            // [tiles_n][M] partial maxima
+  float *amax_val;            // [tiles_n][M] per-tile maxima
   int32_t *amax_idx;          // [tiles_n][M]
-  int32_t *tgt;               // [M]
   uint32_t *dev_status;
 };
 int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h);
 int gemm_auto_split(int tiles, int Kd, int elem_bytes);
 template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a);
+hipError_t launch_rope_table(hipStream_t st, const int32_t *pos, int M, int d_h, float theta, float2 *cs);
+hipError_t launch_sum_slabs(hipStream_t st, const float *slabs, int S, size_t n, float *out);
+hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32_t *amax_idx, int tiles, int M,
+                              int32_t *tgt);
 
 // ---- verify_attn.hip ----
 struct VerifyArgs {
   const void *q; const void *k_cache; const void *v_cache; void *out;
   const int32_t *kv_len; const uint64_t *mask_bits;
   int B, T, n_heads, d_h, max_kv;
-  float *partials; size_t partials_cap; unsigned int *counters; uint32_t *dev_status;
+  float *partials; size_t partials_cap; uint32_t *dev_status;
 };
 int verify_splits(int B, int T, int n_heads, int max_kv, int elem_bytes);
 size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes);

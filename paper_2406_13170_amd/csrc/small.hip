@@ -1,37 +1,58 @@
 // The small kernels of the step: single-query attention of the adaptation layers over their caches
 // (Eq. 1), the K x K bi-directional attention of Eq. 5, per-row top-k / argmax (Eq. 6), candidate-tree
-// construction, greedy acceptance, and the row-wise RMSNorm of the target path.
+// construction, greedy acceptance, and the row-wise RMSNorm (+ partial-sum fold) of the target path.
 #include "kernels.h"
 
 namespace amph {
 
+// 4 consecutive elements of T <-> float[4]
+template <typename T> __device__ __forceinline__ void load4(const T *p, float *f);
+template <> __device__ __forceinline__ void load4<float>(const float *p, float *f) {
+  const float4 v = *reinterpret_cast<const float4 *>(p);
+  f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, float *f) {
+  const uint2 v = *reinterpret_cast<const uint2 *>(p);
+  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+}
+template <typename T> __device__ __forceinline__ void store4(T *p, const float *f);
+template <> __device__ __forceinline__ void store4<float>(float *p, const float *f) {
+  *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float *f) {
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 v;
+  #pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = (bf16_t)f[i];
+  *reinterpret_cast<bf16x4 *>(p) = v;
+}
+
 // =====================================================================================================
 // Single-query attention over a SAL cache: one new position per (batch, head) against rows
-// [0, sal_len] of the cache (the new row included).  grid = (splits, heads, batch).  Each 16-byte
-// fragment of a key/value row belongs to one lane; LPR lanes share a row, so a wave covers 64/LPR
-// rows per load.  Running (max, sum, weighted values) are merged lane group -> wave -> workgroup ->
-// key splits; the last workgroup of a (batch, head) to arrive folds the splits and writes the result.
-// kv_stage: [B, 2, n_heads, max_kv, DH] T.   partials: [B, n_heads, splits, DH + 2] float32.
+// [0, sal_len] of the cache (the new row included).  grid = (heads, batch), 1024 threads: the 16
+// waves of a workgroup stride over the rows.  Each 16-byte fragment of a key/value row belongs to one
+// lane; LPR lanes share a row, so a wave covers 64/LPR rows per load.  Running (max, sum, weighted
+// values) are merged lane group -> wave -> workgroup; no workgroup depends on another.
+// kv_stage: [B, 2, n_heads, max_kv, DH] T.   out: [B, d] float32.
 // =====================================================================================================
+constexpr int SA_WAVES = 16;
+
 template <typename T, int DH>
-__global__ __launch_bounds__(256) void k_sal_attn(const float *qbuf, const T *kv_stage, const int32_t *sal_len,
-                                                  int n_heads, int max_kv, float *partials, unsigned int *counters,
-                                                  float *out) {
+__global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, const T *kv_stage, const int32_t *sal_len,
+                                                            int n_heads, int max_kv, float *out) {
   constexpr int PER = Elem<T>::PER;
   constexpr int LPR = DH / PER;          // lanes per row
   constexpr int G = WAVE / LPR;          // rows per wave load
   constexpr int U = 4;
-  __shared__ float sm_m[4], sm_l[4];
-  __shared__ float sm_o[4][DH];
-  __shared__ int s_flag;
-  const int b = blockIdx.z, h = blockIdx.y, s = blockIdx.x, S = gridDim.x;
+  __shared__ float sm_m[SA_WAVES], sm_l[SA_WAVES];
+  __shared__ float sm_o[SA_WAVES][DH];
+  const int b = blockIdx.y, h = blockIdx.x;
   const int d = n_heads * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int grp = lane / LPR, li = lane % LPR;
-  int len = sal_len[b];
-  int n = (len < 0 || len + 1 > max_kv) ? 0 : len + 1;
-  const int per = (n + S - 1) / S;
-  const int k0 = s * per, k1 = min(n, k0 + per);
+  const int len = sal_len[b];
+  const int n = (len < 0 || len + 1 > max_kv) ? 0 : len + 1;
   const float scale = 1.4426950408889634f * rsqrtf((float)DH);
   float qv[PER];
   #pragma unroll
@@ -41,18 +62,13 @@ __global__ __launch_bounds__(256) void k_sal_attn(const float *qbuf, const T *kv
   float m = NEG_BIG, l = 0.f, o[PER];
   #pragma unroll
   for (int j = 0; j < PER; ++j) o[j] = 0.f;
-  for (int jb = k0 + wave * (U * G); jb < k1; jb += 4 * U * G) {
+  for (int jb = wave * (U * G); jb < n; jb += SA_WAVES * U * G) {
     uint4 kf[U], vf[U];
     #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int j = jb + u * G + grp;
-      if (j < k1) {
-        kf[u] = ldg16(kbase + (size_t)j * DH + li * PER);
-        vf[u] = ldg16(vbase + (size_t)j * DH + li * PER);
-      } else {
-        kf[u] = make_uint4(0u, 0u, 0u, 0u);
-        vf[u] = kf[u];
-      }
+      const int j = min(jb + u * G + grp, n - 1);     // unconditional loads; rows past the end are skipped below
+      kf[u] = ldg16(kbase + (size_t)j * DH + li * PER);
+      vf[u] = ldg16(vbase + (size_t)j * DH + li * PER);
     }
     #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -65,7 +81,7 @@ __global__ __launch_bounds__(256) void k_sal_attn(const float *qbuf, const T *kv
       for (int e = 0; e < PER; ++e) sc = fmaf(qv[e], kk[e], sc);
       #pragma unroll
       for (int off = 1; off < LPR; off <<= 1) sc += __shfl_xor(sc, off, WAVE);
-      if (j < k1) {
+      if (j < n) {
         const float mn = fmaxf(m, sc);
         const float corr = exp2f(m - mn), p = exp2f(sc - mn);
         l = l * corr + p;
@@ -96,81 +112,62 @@ __global__ __launch_bounds__(256) void k_sal_attn(const float *qbuf, const T *kv
   }
   __syncthreads();
   // waves -> workgroup
-  const float mw = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
-  float lw = 0.f;
-  #pragma unroll
-  for (int w = 0; w < 4; ++w) lw += sm_l[w] * exp2f(sm_m[w] - mw);
-  float ow = 0.f;
   if (threadIdx.x < DH) {
+    float mw = sm_m[0];
     #pragma unroll
-    for (int w = 0; w < 4; ++w) ow += sm_o[w][threadIdx.x] * exp2f(sm_m[w] - mw);
+    for (int w = 1; w < SA_WAVES; ++w) mw = fmaxf(mw, sm_m[w]);
+    float lw = 0.f, ow = 0.f;
+    #pragma unroll
+    for (int w = 0; w < SA_WAVES; ++w) {
+      const float f = exp2f(sm_m[w] - mw);
+      lw += sm_l[w] * f;
+      ow += sm_o[w][threadIdx.x] * f;
+    }
+    out[(size_t)b * d + h * DH + threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
   }
-  float *dst = out + (size_t)b * d + h * DH;
-  if (S == 1) {
-    if (threadIdx.x < DH) dst[threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
-    return;
-  }
-  float *part = partials + (((size_t)b * n_heads + h) * S + s) * (DH + 2);
-  if (threadIdx.x < DH) part[2 + threadIdx.x] = ow;
-  if (threadIdx.x == 0) { part[0] = mw; part[1] = lw; }
-  if (!arrive_and_is_last(counters + (size_t)b * n_heads + h, (unsigned)S, &s_flag)) return;
-  const float *p0 = partials + ((size_t)b * n_heads + h) * S * (DH + 2);
-  float mt = NEG_BIG;
-  for (int i = 0; i < S; ++i) mt = fmaxf(mt, p0[(size_t)i * (DH + 2)]);
-  float lt = 0.f, ot = 0.f;
-  for (int i = 0; i < S; ++i) {
-    const float wgt = exp2f(p0[(size_t)i * (DH + 2)] - mt);
-    lt += p0[(size_t)i * (DH + 2) + 1] * wgt;
-    if (threadIdx.x < DH) ot += p0[(size_t)i * (DH + 2) + 2 + threadIdx.x] * wgt;
-  }
-  if (threadIdx.x < DH) dst[threadIdx.x] = (lt > 0.f) ? ot / lt : 0.f;
-}
-
-int sal_attn_splits(int n_heads, int batch, int max_kv) {
-  int s = 256 / (n_heads * batch);
-  const int cap = (max_kv + 63) / 64;
-  if (s > cap) s = cap;
-  if (s > 16) s = 16;
-  return s < 1 ? 1 : s;
-}
-size_t sal_attn_ws_floats(int n_heads, int batch, int d_h, int max_kv) {
-  return (size_t)batch * n_heads * sal_attn_splits(n_heads, batch, max_kv) * (d_h + 2);
 }
 
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *partials, unsigned int *counters, float *out) {
-  const dim3 grid(sal_attn_splits(n_heads, B, max_kv), n_heads, B);
+                           int n_heads, int d_h, int max_kv, float *out) {
+  const dim3 grid(n_heads, B), block(SA_WAVES * 64);
   if (d_h == 64)
-    hipLaunchKernelGGL((k_sal_attn<T, 64>), grid, dim3(256), 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv,
-                       partials, counters, out);
+    hipLaunchKernelGGL((k_sal_attn<T, 64>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out);
   else if (d_h == 128)
-    hipLaunchKernelGGL((k_sal_attn<T, 128>), grid, dim3(256), 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv,
-                       partials, counters, out);
+    hipLaunchKernelGGL((k_sal_attn<T, 128>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 template hipError_t launch_sal_attn<float>(hipStream_t, const float *, const void *, const int32_t *, int, int, int, int,
-                                           float *, unsigned int *, float *);
+                                           float *);
 template hipError_t launch_sal_attn<bf16_t>(hipStream_t, const float *, const void *, const int32_t *, int, int, int,
-                                            int, float *, unsigned int *, float *);
+                                            int, float *);
 
 // =====================================================================================================
 // Eq. 5 core: for one (batch, head) the K x K score matrix of the K head positions, a row softmax
 // with no mask, and the weighted sum of the value rows.  Q, Kk, V, ctx: [B * K, d] float32.
+// The head's K rows of Q, K and V are first parked in LDS.
 // =====================================================================================================
 __global__ __launch_bounds__(128) void k_aeb_attn(const float *Q, const float *Kk, const float *V, int K, int n_heads,
                                                   int d_h, float *ctx) {
+  __shared__ float sq[AMPH_MAX_HEADS_K * 128], sk[AMPH_MAX_HEADS_K * 128], sv[AMPH_MAX_HEADS_K * 128];
   __shared__ float sc[AMPH_MAX_HEADS_K * AMPH_MAX_HEADS_K];
   const int h = blockIdx.x, b = blockIdx.y;
   const int d = n_heads * d_h;
   const size_t base = (size_t)b * K * d + (size_t)h * d_h;
   const int t = threadIdx.x;
+  for (int i = t; i < K * d_h; i += blockDim.x) {
+    const int r = i / d_h, e = i % d_h;
+    sq[i] = Q[base + (size_t)r * d + e];
+    sk[i] = Kk[base + (size_t)r * d + e];
+    sv[i] = V[base + (size_t)r * d + e];
+  }
+  __syncthreads();
   if (t < K * K) {
     const int i = t / K, j = t % K;
     float s = 0.f;
-    for (int e = 0; e < d_h; ++e) s = fmaf(Q[base + (size_t)i * d + e], Kk[base + (size_t)j * d + e], s);
+    for (int e = 0; e < d_h; ++e) s = fmaf(sq[i * d_h + e], sk[j * d_h + e], s);
     sc[t] = s * rsqrtf((float)d_h);
   }
   __syncthreads();
@@ -186,7 +183,7 @@ __global__ __launch_bounds__(128) void k_aeb_attn(const float *Q, const float *K
   for (int e = t; e < d_h; e += blockDim.x) {
     for (int i = 0; i < K; ++i) {
       float o = 0.f;
-      for (int j = 0; j < K; ++j) o = fmaf(sc[i * K + j], V[base + (size_t)j * d + e], o);
+      for (int j = 0; j < K; ++j) o = fmaf(sc[i * K + j], sv[j * d_h + e], o);
       ctx[base + (size_t)i * d + e] = o;
     }
   }
@@ -194,44 +191,36 @@ __global__ __launch_bounds__(128) void k_aeb_attn(const float *Q, const float *K
 
 hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, const float *V, int B, int K, int n_heads,
                            int d_h, float *ctx) {
-  if (K < 1 || K > AMPH_MAX_HEADS_K) return hipErrorInvalidValue;
+  if (K < 1 || K > AMPH_MAX_HEADS_K || d_h > 128) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_aeb_attn, dim3(n_heads, B), dim3(128), 0, st, Q, Kk, V, K, n_heads, d_h, ctx);
   return hipGetLastError();
 }
 
 // =====================================================================================================
-// Per-row top-k (Eq. 6) by repeated selection.  One 1024-thread workgroup per row; thread t owns
-// elements t, t + 1024, ... in registers.  Each round picks the best remaining element of the row:
-// thread-local best -> wave butterfly -> 16 wave winners in LDS, read by everybody.  "Better" means a
-// larger value, or the same value and a smaller index, so the result is sorted and ties are
-// deterministic.  Block 0 also advances the caller's length counters (used by the draft call).
+// Per-row top-k (Eq. 6) by repeated selection inside single waves (no workgroup barriers).
+// "Better" means a larger value, or the same value and a smaller index, so results are sorted and
+// ties deterministic.
+//   pass 1: every wave owns TK_CHUNK consecutive logits of one row (TK_NPT per lane) and emits its own
+//           top-k as (value, index) candidates;
+//   pass 2: one wave per row selects the top-k of all candidates of the row.
+// The top-k of a union is the top-k of the parts' top-k, so the result is exact.
 // =====================================================================================================
-struct Cand { float v; int i; };
+constexpr int TK_NPT = 8, TK_CHUNK = TK_NPT * WAVE;      // 512 logits per wave
+constexpr int TK_MAXC = 32;                              // pass 2: candidates per lane
+
 __device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
   return (v1 > v2) || (v1 == v2 && i1 < i2);
 }
 
+// Select k times from NPT per-lane (value, index) pairs spread over a wave.  Lane 0 writes the results.
 template <int NPT>
-__global__ __launch_bounds__(1024) void k_topk_rows(const float *logits, int V, int k, int32_t *idx, float *val,
-                                                    int32_t *advance, int n_advance, int advance_by) {
-  __shared__ float s_v[2][16];
-  __shared__ int s_i[2][16];
-  const int row = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const float *src = logits + (size_t)row * V;
+__device__ __forceinline__ void wave_select(float (&x)[NPT], int (&id)[NPT], int k, int none, float *out_v, int *out_i) {
   const float NEG_INF = -__builtin_huge_valf();
-  float x[NPT];
+  const int lane = threadIdx.x & 63;
+  float bv = NEG_INF; int bi = none, bj = -1;
   #pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const int e = t + j * 1024;
-    x[j] = (e < V) ? src[e] : NEG_INF;
-  }
-  // thread-local best; index V marks "nothing left"
-  float bv = NEG_INF; int bi = V;
-  #pragma unroll
-  for (int j = 0; j < NPT; ++j) {
-    const int e = t + j * 1024;
-    if (e < V && better(x[j], e, bv, bi)) { bv = x[j]; bi = e; }
-  }
+  for (int j = 0; j < NPT; ++j)
+    if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
   for (int r = 0; r < k; ++r) {
     float wv = bv; int wi = bi;
     #pragma unroll
@@ -240,49 +229,79 @@ __global__ __launch_bounds__(1024) void k_topk_rows(const float *logits, int V, 
       const int oi = __shfl_xor(wi, off, WAVE);
       if (better(ov, oi, wv, wi)) { wv = ov; wi = oi; }
     }
-    const int buf = r & 1;
-    if (lane == 0) { s_v[buf][wave] = wv; s_i[buf][wave] = wi; }
-    __syncthreads();
-    float gv = s_v[buf][0]; int gi = s_i[buf][0];
-    #pragma unroll
-    for (int w = 1; w < 16; ++w) {
-      const float ov = s_v[buf][w]; const int oi = s_i[buf][w];
-      if (better(ov, oi, gv, gi)) { gv = ov; gi = oi; }
-    }
-    if (t == 0) {
-      if (idx) idx[(size_t)row * k + r] = (gi < V) ? gi : -1;
-      if (val) val[(size_t)row * k + r] = gv;
-    }
-    if (gi < V && (gi & 1023) == t) {          // the owner retires the element and rescans its own
-      const int jj = gi >> 10;
-      bv = NEG_INF; bi = V;
+    if (lane == 0) { out_v[r] = wv; out_i[r] = (wi == none) ? -1 : wi; }
+    if (wi != none && wi == bi) {              // this lane owned the winner: retire it and rescan
+      bv = NEG_INF; bi = none;
+      const int gone = bj; bj = -1;
       #pragma unroll
       for (int j = 0; j < NPT; ++j) {
-        if (j == jj) x[j] = NEG_INF;
-        const int e = t + j * 1024;
-        if (e < V && j != jj && x[j] > NEG_INF && better(x[j], e, bv, bi)) { bv = x[j]; bi = e; }
+        if (j == gone) id[j] = none;
+        if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
       }
     }
   }
-  if (row == 0 && advance && t < n_advance) advance[t] += advance_by;
+}
+
+__global__ __launch_bounds__(256) void k_topk_pass1(const float *logits, int V, int k, int chunks_per_row, float *cand_v,
+                                                    int *cand_i) {
+  const int row = blockIdx.y, chunk = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (chunk >= chunks_per_row) return;                    // whole wave leaves together
+  const float *src = logits + (size_t)row * V;
+  float x[TK_NPT]; int id[TK_NPT];
+  #pragma unroll
+  for (int j = 0; j < TK_NPT; ++j) {
+    const int e = chunk * TK_CHUNK + j * WAVE + lane;
+    id[j] = (e < V) ? e : V;
+    x[j] = (e < V) ? src[e] : 0.f;
+  }
+  const size_t o = ((size_t)row * chunks_per_row + chunk) * k;
+  wave_select<TK_NPT>(x, id, k, V, cand_v + o, cand_i + o);
+}
+
+__global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const int *cand_i, int n_cand, int V, int k,
+                                                   int32_t *idx, float *val, int32_t *advance, int n_advance,
+                                                   int advance_by) {
+  const int row = blockIdx.x, lane = threadIdx.x;
+  float x[TK_MAXC]; int id[TK_MAXC];
+  #pragma unroll
+  for (int j = 0; j < TK_MAXC; ++j) {
+    const int c = j * WAVE + lane;
+    const int ci = (c < n_cand) ? cand_i[(size_t)row * n_cand + c] : -1;
+    id[j] = (ci >= 0) ? ci : V;
+    x[j] = (ci >= 0) ? cand_v[(size_t)row * n_cand + c] : 0.f;
+  }
+  __shared__ float sv[AMPH_MAX_TOPK];
+  __shared__ int si[AMPH_MAX_TOPK];
+  wave_select<TK_MAXC>(x, id, k, V, sv, si);
+  __syncthreads();
+  if (lane < k) {
+    if (idx) idx[(size_t)row * k + lane] = si[lane];
+    if (val) val[(size_t)row * k + lane] = sv[lane];
+  }
+  if (row == 0 && advance) for (int i = lane; i < n_advance; i += WAVE) advance[i] += advance_by;
+}
+
+size_t topk_ws_floats(int rows, int V, int k) {
+  const int chunks = (V + TK_CHUNK - 1) / TK_CHUNK;
+  return 2 * (size_t)rows * chunks * k;
 }
 
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by) {
-  if (rows < 1 || V < 1 || k < 1 || k > V || n_advance > 1024) return hipErrorInvalidValue;
-  if (V <= 32 * 1024)
-    hipLaunchKernelGGL((k_topk_rows<32>), dim3(rows), dim3(1024), 0, st, logits, V, k, idx, val, advance, n_advance,
-                       advance_by);
-  else if (V <= 64 * 1024)
-    hipLaunchKernelGGL((k_topk_rows<64>), dim3(rows), dim3(1024), 0, st, logits, V, k, idx, val, advance, n_advance,
-                       advance_by);
-  else
-    return hipErrorInvalidValue;
+                            int32_t *advance, int n_advance, int advance_by, float *ws) {
+  if (rows < 1 || V < 1 || k < 1 || k > V || k > AMPH_MAX_TOPK) return hipErrorInvalidValue;
+  const int chunks = (V + TK_CHUNK - 1) / TK_CHUNK;
+  const int n_cand = chunks * k;
+  if (n_cand > TK_MAXC * WAVE) return hipErrorInvalidValue;          // V <= 65536 with k <= 16
+  float *cand_v = ws;
+  int *cand_i = reinterpret_cast<int *>(ws + (size_t)rows * n_cand);
+  hipLaunchKernelGGL(k_topk_pass1, dim3((chunks + 3) / 4, rows), dim3(256), 0, st, logits, V, k, chunks, cand_v, cand_i);
+  hipLaunchKernelGGL(k_topk_pass2, dim3(rows), dim3(64), 0, st, cand_v, cand_i, n_cand, V, k, idx, val, advance, n_advance,
+                     advance_by);
   return hipGetLastError();
 }
 
-hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out) {
-  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0);
+hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws) {
+  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0, ws);
 }
 
 // =====================================================================================================
@@ -357,42 +376,71 @@ hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *d
 }
 
 // =====================================================================================================
-// Row-wise RMSNorm for the target path: xn = x / rms(x) * g, stored as T for the matrix cores.
-// With tok != NULL the row is first gathered from the embedding table (and kept in x as float32).
+// Row-wise RMSNorm for the target path, fused with the fold of the previous GEMM's partial slabs:
+//   x[m] (+)= sum_s slabs[s][m]   (or x[m] = embed[tok[m]] on entry to the first layer)
+//   xn[m] = x[m] / rms(x[m]) * g  stored as T for the matrix cores; hidden_out optionally in float32.
+// One workgroup per row; the row lives in registers (d <= 8192).
 // =====================================================================================================
+constexpr int NR_VEC = 8;
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_rmsnorm_rows(float *x, const T *embed, const int32_t *tok, int vocab, const T *g,
-                                                      int d, float eps, T *xn, float *hidden_out, uint32_t *dev_status) {
+__global__ __launch_bounds__(256) void k_norm_fold(float *x, const T *embed, const int32_t *tok, int vocab,
+                                                   const float *slabs, int S, size_t slab_stride, const T *g, int d,
+                                                   float eps, T *xn, float *hidden_out, uint32_t *dev_status) {
   __shared__ float red[4];
-  const int row = blockIdx.x;
+  const int row = blockIdx.x, tid = threadIdx.x;
   float *xr = x + (size_t)row * d;
+  float v[NR_VEC][4];
+  int t = 0;
   if (tok) {
-    int t = tok[row];
-    if (t < 0 || t >= vocab) { if (threadIdx.x == 0) atomicOr(dev_status, 4u); t = 0; }
-    const T *er = embed + (size_t)t * d;
-    for (int k = threadIdx.x; k < d; k += 256) xr[k] = Elem<T>::to_f32(er[k]);
+    t = tok[row];
+    if (t < 0 || t >= vocab) { if (tid == 0) atomicOr(dev_status, 4u); t = 0; }
   }
   float ss = 0.f;
-  for (int k = threadIdx.x; k < d; k += 256) { const float v = xr[k]; ss = fmaf(v, v, ss); }   // own writes: visible
+  #pragma unroll
+  for (int i = 0; i < NR_VEC; ++i) {
+    const int k = (tid + i * 256) * 4;
+    if (k < d) {
+      if (tok) load4<T>(embed + (size_t)t * d + k, v[i]);
+      else load4<float>(xr + k, v[i]);
+      for (int s = 0; s < S; ++s) {
+        float p[4];
+        load4<float>(slabs + (size_t)s * slab_stride + (size_t)row * d + k, p);
+        #pragma unroll
+        for (int j = 0; j < 4; ++j) v[i][j] += p[j];
+      }
+      if (tok || S > 0) store4<float>(xr + k, v[i]);
+      #pragma unroll
+      for (int j = 0; j < 4; ++j) ss = fmaf(v[i][j], v[i][j], ss);
+    }
+  }
   const float rs = rsqrtf(block_sum_256(ss, red) / (float)d + eps);
-  for (int k = threadIdx.x; k < d; k += 256) {
-    const float v = xr[k] * rs * Elem<T>::to_f32(g[k]);
-    xn[(size_t)row * d + k] = Elem<T>::from_f32(v);
-    if (hidden_out) hidden_out[(size_t)row * d + k] = v;
+  #pragma unroll
+  for (int i = 0; i < NR_VEC; ++i) {
+    const int k = (tid + i * 256) * 4;
+    if (k < d) {
+      float gk[4], o[4];
+      load4<T>(g + k, gk);
+      #pragma unroll
+      for (int j = 0; j < 4; ++j) o[j] = v[i][j] * rs * gk[j];
+      store4<T>(xn + (size_t)row * d + k, o);
+      if (hidden_out) store4<float>(hidden_out + (size_t)row * d + k, o);
+    }
   }
 }
 
 template <typename T>
-hipError_t launch_rmsnorm_rows(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
-                               const void *g, int rows, int d, float eps, void *xn, float *hidden_out,
-                               uint32_t *dev_status) {
-  hipLaunchKernelGGL((k_rmsnorm_rows<T>), dim3(rows), dim3(256), 0, st, x, (const T *)embed, tok, vocab, (const T *)g, d,
-                     eps, (T *)xn, hidden_out, dev_status);
+hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
+                            const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
+                            void *xn, float *hidden_out, uint32_t *dev_status) {
+  if (d % 4 || d > NR_VEC * 256 * 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_norm_fold<T>), dim3(rows), dim3(256), 0, st, x, (const T *)embed, tok, vocab, slabs, S, slab_stride,
+                     (const T *)g, d, eps, (T *)xn, hidden_out, dev_status);
   return hipGetLastError();
 }
-template hipError_t launch_rmsnorm_rows<float>(hipStream_t, float *, const void *, const int32_t *, int, const void *,
-                                               int, int, float, void *, float *, uint32_t *);
-template hipError_t launch_rmsnorm_rows<bf16_t>(hipStream_t, float *, const void *, const int32_t *, int, const void *,
-                                                int, int, float, void *, float *, uint32_t *);
+template hipError_t launch_norm_fold<float>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
+                                            size_t, const void *, int, int, float, void *, float *, uint32_t *);
+template hipError_t launch_norm_fold<bf16_t>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
+                                             size_t, const void *, int, int, float, void *, float *, uint32_t *);
 
 }  // namespace amph

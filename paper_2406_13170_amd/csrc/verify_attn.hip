@@ -10,7 +10,8 @@
 // its B operand, so P never leaves registers.  A wave owns whole key steps (32 keys in bf16, 16 in
 // float) for up to 64 queries; the four waves of a workgroup take different steps and merge their
 // running (max, sum, O) through LDS; workgroups that split the keys of one head merge through global
-// memory, the last one to arrive doing the fold in a fixed order.
+// memory: a second small kernel (k_verify_fold) folds them in a fixed order, so no workgroup ever
+// waits for or signals another.
 #include "kernels.h"
 
 namespace amph {
@@ -33,7 +34,6 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
   constexpr int PER = C::PER, KSTEP = C::KSTEP, NT = C::NT, DSTEPS = C::DSTEPS, DB = C::DB, NQ = C::NQ;
   __shared__ __align__(16) float sm_o[4][NQ][C::OPITCH];
   __shared__ float sm_m[4][NQ], sm_l[4][NQ];
-  __shared__ int s_flag;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
   const int S = gridDim.x, split = blockIdx.x, h = blockIdx.y;
@@ -62,9 +62,9 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
   for (int qb = 0; qb < NQB; ++qb) {
     const int qi = q_base + qb * 16 + r16;
     #pragma unroll
-    for (int ds = 0; ds < DSTEPS; ++ds) {
-      if (qi < Tn) Qf[qb][ds] = ldg16((const T *)a.q + (((size_t)b * Tn + qi) * n_h + h) * DH + ds * (4 * PER) + g * PER);
-      else Qf[qb][ds] = make_uint4(0u, 0u, 0u, 0u);
+    for (int ds = 0; ds < DSTEPS; ++ds) {      // padding queries re-read query 0; their rows are never stored
+      const int qs = (qi < Tn) ? qi : 0;
+      Qf[qb][ds] = ldg16((const T *)a.q + (((size_t)b * Tn + qs) * n_h + h) * DH + ds * (4 * PER) + g * PER);
     }
     mk_lo[qb] = (qi < Tn) ? a.mask_bits[(size_t)qi * 2] : 0ull;
     mk_hi[qb] = (qi < Tn) ? a.mask_bits[(size_t)qi * 2 + 1] : 0ull;
@@ -197,29 +197,38 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
       if (d4 == 0) { part[NQ * DH + q] = mw; part[NQ * DH + NQ + q] = l; }
     }
   }
-  if (S == 1) return;
+}
 
-  // ---- key splits -> result, by the last workgroup of this (batch, query group, head)
-  if (!arrive_and_is_last(a.counters + ((size_t)(b * n_qg + qg) * n_h + h), (unsigned)S, &s_flag)) return;
-  const float *p0 = a.partials + ((size_t)(b * n_qg + qg) * n_h + h) * S * C::PART;
+// Fold the S key-split partials of one (batch, query group, head): out = sum_s O_s 2^(m_s - m) / sum_s l_s 2^(m_s - m),
+// s ascending.  grid = (heads, B * query groups), 256 threads, 4 dims of one query per thread and iteration.
+template <typename T, int DH>
+__global__ __launch_bounds__(256) void k_verify_fold(const VerifyArgs a, int n_qg, int nqb, int S) {
+  const int NQ = nqb * 16, PART = NQ * DH + 2 * NQ;
+  const int h = blockIdx.x, b = blockIdx.y / n_qg, qg = blockIdx.y % n_qg, tid = threadIdx.x;
+  const int Tn = a.T, n_h = a.n_heads;
+  const int L = a.kv_len[b];
+  if (L < 0 || L + Tn > a.max_kv) return;               // the main kernel wrote nothing for this element
+  const float *p0 = a.partials + ((size_t)(b * n_qg + qg) * n_h + h) * S * PART;
+  T *outp = (T *)a.out;
   for (int idx = tid; idx < NQ * (DH / 4); idx += 256) {
     const int q = idx / (DH / 4), d4 = (idx % (DH / 4)) * 4;
-    const int qi = q_base + q;
+    const int qi = qg * NQ + q;
     if (qi >= Tn) continue;
     float mt = NEG_BIG;
-    for (int s = 0; s < S; ++s) mt = fmaxf(mt, p0[(size_t)s * C::PART + NQ * DH + q]);
+    for (int s = 0; s < S; ++s) mt = fmaxf(mt, p0[(size_t)s * PART + NQ * DH + q]);
     f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
     float l = 0.f;
     for (int s = 0; s < S; ++s) {
-      const float *ps = p0 + (size_t)s * C::PART;
+      const float *ps = p0 + (size_t)s * PART;
       const float f = exp2f(ps[NQ * DH + q] - mt);
       o += *reinterpret_cast<const f32x4 *>(ps + (size_t)q * DH + d4) * f;
       l += ps[NQ * DH + NQ + q] * f;
     }
     const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+    float r[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
     T *dst = outp + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
     #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(o[i] * inv);
+    for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(r[i]);
   }
 }
 
@@ -253,7 +262,8 @@ template <typename T, int DH>
 static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
   int nqb, n_qg;
   va_groups(a.T, &nqb, &n_qg);
-  const dim3 grid(verify_splits(a.B, a.T, a.n_heads, a.max_kv, (int)sizeof(T)), a.n_heads, a.B * n_qg), block(256);
+  const int S = verify_splits(a.B, a.T, a.n_heads, a.max_kv, (int)sizeof(T));
+  const dim3 grid(S, a.n_heads, a.B * n_qg), block(256);
   switch (nqb) {
     case 1: hipLaunchKernelGGL((k_verify_attn<T, DH, 1>), grid, block, 0, st, a, n_qg); break;
     case 2: hipLaunchKernelGGL((k_verify_attn<T, DH, 2>), grid, block, 0, st, a, n_qg); break;
@@ -261,6 +271,7 @@ static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
     case 4: hipLaunchKernelGGL((k_verify_attn<T, DH, 4>), grid, block, 0, st, a, n_qg); break;
     default: return hipErrorInvalidValue;
   }
+  if (S > 1) hipLaunchKernelGGL((k_verify_fold<T, DH>), dim3(a.n_heads, a.B * n_qg), block, 0, st, a, n_qg, nqb, S);
   return hipGetLastError();
 }
 
