@@ -8,7 +8,7 @@
 // The 16 keys fed to one S^T tile are chosen so that the accumulator a lane ends up with (4 keys of
 // its lane group per tile) is exactly the contraction-slot layout the second product expects from
 // its B operand, so P never leaves registers.  A wave owns whole key steps (32 keys in bf16, 16 in
-// float) for up to 64 queries; the four waves of a workgroup take different steps and merge their
+// float) for up to 32 queries; the four waves of a workgroup take different steps and merge their
 // running (max, sum, O) through LDS; workgroups that split the keys of one head merge through global
 // memory: a second small kernel (k_verify_fold) folds them in a fixed order, so no workgroup ever
 // waits for or signals another.
@@ -79,10 +79,10 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     for (int db = 0; db < DB; ++db) O[qb][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int st = st0 + wave; st < st1; st += 4) {
+  // One key step: loads of the step's K and V^T fragments, and the math on them.  The loop below keeps
+  // the next step's fragments in flight while the current step is being processed (two register sets).
+  auto load_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
     const int key0 = st * KSTEP;
-    // ---- loads: K rows (permuted so that a lane group's accumulators are consecutive keys), V^T
-    uint4 Kf[NT][DSTEPS], Vf[DB];
     #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int key = key0 + (r16 >> 2) * (4 * NT) + t * 4 + (r16 & 3);
@@ -91,7 +91,9 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     }
     #pragma unroll
     for (int db = 0; db < DB; ++db) Vf[db] = ldg16(Vb + (size_t)(db * 16 + r16) * max_kv + key0 + g * PER);
-
+  };
+  auto math_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
+    const int key0 = st * KSTEP;
     const bool tail = (key0 + KSTEP > L);            // this step touches tree rows or rows past the end
     if (key0 + KSTEP > n_keys) {
       // rows past L+T may hold anything (even NaN): zero their values so that 0 * V stays 0
@@ -151,6 +153,21 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
         O[qb][db] = mma16<T>(Vf[db], Pf, O[qb][db]);
       }
     }
+  };
+
+  const int n_w = (st1 - (st0 + wave) + 3) / 4;        // key steps of this wave: st0 + wave, + 4, ...
+  if (n_w > 0) {
+    uint4 KA[NT][DSTEPS], VA_[DB], KB_[NT][DSTEPS], VB_[DB];
+    const int first = st0 + wave;
+    load_step(first, KA, VA_);
+    for (int i = 0; i < n_w; i += 2) {
+      // loads are unconditional (an index past the end re-reads the last step) so that the number of
+      // outstanding loads is the same on every path
+      load_step(first + 4 * min(i + 1, n_w - 1), KB_, VB_);
+      math_step(first + 4 * i, KA, VA_);
+      load_step(first + 4 * min(i + 2, n_w - 1), KA, VA_);
+      if (i + 1 < n_w) math_step(first + 4 * (i + 1), KB_, VB_);
+    }
   }
 
   // ---- lane groups hold partial sums of l for the same query: fold them
@@ -203,39 +220,40 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
 // s ascending.  grid = (heads, B * query groups), 256 threads, 4 dims of one query per thread and iteration.
 template <typename T, int DH>
 __global__ __launch_bounds__(256) void k_verify_fold(const VerifyArgs a, int n_qg, int nqb, int S) {
+  constexpr int QW = 256 / (DH / 4);                    // queries per workgroup: one float4 of one query per thread
   const int NQ = nqb * 16, PART = NQ * DH + 2 * NQ;
   const int h = blockIdx.x, b = blockIdx.y / n_qg, qg = blockIdx.y % n_qg, tid = threadIdx.x;
   const int Tn = a.T, n_h = a.n_heads;
   const int L = a.kv_len[b];
   if (L < 0 || L + Tn > a.max_kv) return;               // the main kernel wrote nothing for this element
+  const int q = blockIdx.z * QW + tid / (DH / 4), d4 = (tid % (DH / 4)) * 4;
+  const int qi = qg * NQ + q;
+  if (q >= NQ || qi >= Tn) return;
   const float *p0 = a.partials + ((size_t)(b * n_qg + qg) * n_h + h) * S * PART;
-  T *outp = (T *)a.out;
-  for (int idx = tid; idx < NQ * (DH / 4); idx += 256) {
-    const int q = idx / (DH / 4), d4 = (idx % (DH / 4)) * 4;
-    const int qi = qg * NQ + q;
-    if (qi >= Tn) continue;
-    float mt = NEG_BIG;
-    for (int s = 0; s < S; ++s) mt = fmaxf(mt, p0[(size_t)s * PART + NQ * DH + q]);
-    f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float l = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const float *ps = p0 + (size_t)s * PART;
-      const float f = exp2f(ps[NQ * DH + q] - mt);
-      o += *reinterpret_cast<const f32x4 *>(ps + (size_t)q * DH + d4) * f;
-      l += ps[NQ * DH + NQ + q] * f;
-    }
-    const float inv = (l > 0.f) ? 1.0f / l : 0.f;
-    float r[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
-    T *dst = outp + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
-    #pragma unroll
-    for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(r[i]);
+  float mt = NEG_BIG;
+  for (int s = 0; s < S; ++s) mt = fmaxf(mt, p0[(size_t)s * PART + NQ * DH + q]);
+  f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float l = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float *ps = p0 + (size_t)s * PART;
+    const float f = exp2f(ps[NQ * DH + q] - mt);
+    o += *reinterpret_cast<const f32x4 *>(ps + (size_t)q * DH + d4) * f;
+    l += ps[NQ * DH + NQ + q] * f;
   }
+  const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+  float r[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+  T *dst = (T *)a.out + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
+  #pragma unroll
+  for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(r[i]);
 }
 
 // queries per workgroup: as few 16-query blocks per wave as cover T in ceil(T/64) groups
+// Queries per workgroup: at most two 16-query blocks per wave.  Larger blocks per wave would save K/V
+// re-reads (they come from L2) but need more registers than leave room for a second set of K/V fragments.
+constexpr int VA_MAX_QB = 2;
 static inline void va_groups(int T, int *nqb, int *n_qg) {
   const int blocks = (T + 15) / 16;
-  *n_qg = (blocks + 3) / 4;
+  *n_qg = (blocks + VA_MAX_QB - 1) / VA_MAX_QB;
   *nqb = (blocks + *n_qg - 1) / *n_qg;
 }
 
@@ -267,11 +285,12 @@ static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
   switch (nqb) {
     case 1: hipLaunchKernelGGL((k_verify_attn<T, DH, 1>), grid, block, 0, st, a, n_qg); break;
     case 2: hipLaunchKernelGGL((k_verify_attn<T, DH, 2>), grid, block, 0, st, a, n_qg); break;
-    case 3: hipLaunchKernelGGL((k_verify_attn<T, DH, 3>), grid, block, 0, st, a, n_qg); break;
-    case 4: hipLaunchKernelGGL((k_verify_attn<T, DH, 4>), grid, block, 0, st, a, n_qg); break;
     default: return hipErrorInvalidValue;
   }
-  if (S > 1) hipLaunchKernelGGL((k_verify_fold<T, DH>), dim3(a.n_heads, a.B * n_qg), block, 0, st, a, n_qg, nqb, S);
+  if (S > 1) {
+    constexpr int QW = 256 / (DH / 4);
+    hipLaunchKernelGGL((k_verify_fold<T, DH>), dim3(a.n_heads, a.B * n_qg, (nqb * 16 + QW - 1) / QW), block, 0, st, a, n_qg, nqb, S);
+  }
   return hipGetLastError();
 }
 
