@@ -2,12 +2,17 @@
 // activation rows (64 per block) against [N, Kd] weights that stream from HBM once, on the matrix
 // cores.
 //
-// A 256-thread workgroup owns a 64 (tokens) x 64 (weight rows) output tile and a slice of the
-// reduction axis.  Each wave keeps 16 weight rows: its A fragments are 16-byte loads straight from
-// global memory (lane = row, 16 contiguous bytes of that row), prefetched three 512-byte chunks (8
-// fragments each) ahead in a register ring, enough to cover HBM latency with one or two workgroups per CU.  The activations of the chunk (64 rows x 512 bytes) are staged
-// through a padded, double-buffered LDS tile and read back as B fragments, so every weight byte is
-// fetched once and multiplied against all 64 tokens.
+// A workgroup owns a 64 (tokens) x 16*NB (weight rows) output tile and a slice of the reduction axis,
+// and its waves have two roles:
+//   * NB math waves, each keeping 16 weight rows.  Their A fragments are 16-byte loads straight from
+//     global memory (lane = row, 16 contiguous bytes of that row), requested one 512-byte chunk (8
+//     fragments) ahead; B fragments come from LDS.  They issue nothing else: no activation loads sit
+//     between their weight loads, so waiting for a chunk of weights never waits for anything younger.
+//   * NLW loader waves, which bring the activations of each chunk (64 rows x 512 bytes, L2 hits) into
+//     a padded, double-buffered LDS tile one chunk ahead.
+// One barrier per chunk joins the two.  The tile height is chosen per shape: every workgroup reads
+// the whole activation slice from L2, so that traffic is (64 / tile height) times the weight bytes and
+// measurably slows the weight stream; taller tiles cut it as far as the number of workgroups allows.
 //
 // No workgroup ever communicates with another inside the kernel (a device-scope fence per workgroup
 // costs far more than the kernel on this chip): a split reduction axis writes one partial slab per
@@ -18,48 +23,68 @@
 
 namespace amph {
 
-constexpr int GM_BM = 64, GM_BN = 64;
+constexpr int GM_BM = 64;
 constexpr int GM_CHUNK_B = 512;                 // bytes of one activation row per chunk
 constexpr int GM_PITCH = GM_CHUNK_B + 16;       // LDS row pitch (bytes): rows shift by 4 banks
 constexpr int GM_STEPS = GM_CHUNK_B / 64;       // matrix-core steps per chunk (64 bytes of k each)
-constexpr int GM_NST = 4;                       // register ring of weight chunks (even)
-constexpr int GM_XL = GM_BM * GM_CHUNK_B / 16 / 256;   // 16-byte activation loads per thread per chunk
-constexpr int GM_CT_PITCH = GM_BN + 4;          // floats
-constexpr int GM_LDS_BYTES = 2 * GM_BM * GM_PITCH;
-static_assert(GM_LDS_BYTES >= GM_BM * GM_CT_PITCH * 4, "output tile must fit in the staging buffers");
+constexpr int GM_STAGE = GM_BM * GM_PITCH;      // one activation stage
+constexpr int GM_LDS_BYTES = 2 * GM_STAGE;
+
+// row blocks (16 weight rows = one math wave) and loader waves per workgroup, by epilogue
+template <int EPI> struct GemmShape;
+template <> struct GemmShape<EPI_STORE> { static constexpr int NB = 4, NLW = 4; };
+template <> struct GemmShape<EPI_QKV_ROPE> { static constexpr int NB = 4, NLW = 4; };   // 32 rows + their 32 RoPE partners
+template <> struct GemmShape<EPI_SWIGLU> { static constexpr int NB = 6, NLW = 2; };     // 48 gate rows + 48 up rows
+template <> struct GemmShape<EPI_ARGMAX> { static constexpr int NB = 8, NLW = 4; };
+
+static int gemm_nb(int epi) {
+  switch (epi) {
+    case EPI_QKV_ROPE: return GemmShape<EPI_QKV_ROPE>::NB;
+    case EPI_SWIGLU: return GemmShape<EPI_SWIGLU>::NB;
+    case EPI_ARGMAX: return GemmShape<EPI_ARGMAX>::NB;
+    default: return GemmShape<EPI_STORE>::NB;
+  }
+}
 
 // weight row (within its matrix) and matrix index of tile row r
 struct RowMap { int seg; int n; bool valid; };
 
-template <int EPI>
+template <int EPI, int BN>
 __device__ __forceinline__ RowMap map_row(const GemmArgs &a, int tile, int r) {
   RowMap o;
   if (EPI == EPI_QKV_ROPE) {
-    const int d = a.n_heads * a.d_h, tps = d / GM_BN;
+    static_assert(EPI != EPI_QKV_ROPE || BN == 64, "RoPE tiles pair 32 rows with their 32 partners");
+    const int d = a.n_heads * a.d_h, tps = d / BN;
     o.seg = tile / tps;
     const int tl = tile % tps;
     if (o.seg < 2) {
-      const int half = a.d_h / 2, tph = a.d_h / GM_BN;
+      const int half = a.d_h / 2, tph = a.d_h / BN;
       const int head = tl / tph, p = tl % tph;
       o.n = head * a.d_h + p * 32 + (r & 31) + ((r >= 32) ? half : 0);
     } else {
-      o.n = tl * GM_BN + r;
+      o.n = tl * BN + r;
     }
     o.valid = true;
   } else if (EPI == EPI_SWIGLU) {
-    o.seg = (r >= 32) ? 1 : 0;
-    o.n = tile * 32 + (r & 31);
+    constexpr int H = BN / 2;
+    o.seg = (r >= H) ? 1 : 0;
+    o.n = tile * H + (r >= H ? r - H : r);
     o.valid = o.n < a.seg_rows;
   } else {
     o.seg = 0;
-    o.n = tile * GM_BN + r;
+    o.n = tile * BN + r;
     o.valid = o.n < a.seg_rows;
   }
   return o;
 }
 
 template <typename T, int EPI>
-__global__ __launch_bounds__(256, 2) void k_gemm_skinny(const GemmArgs a, int tiles) {
+__global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) void k_gemm_skinny(const GemmArgs a, int tiles) {
+  constexpr int NB = GemmShape<EPI>::NB, NLW = GemmShape<EPI>::NLW, BN = 16 * NB, NT = 64 * (NB + NLW);
+  constexpr int CT_PITCH = BN + 4;                       // floats
+  constexpr int XROWS = GM_BM / NLW, XL = XROWS / 2;     // activation rows / 16-byte loads per loader lane per chunk
+  static_assert(GM_LDS_BYTES >= GM_BM * CT_PITCH * 4, "output tile must fit in the staging buffers");
+  static_assert(GM_BM % NLW == 0 && XROWS % 2 == 0, "loader waves split the 64 activation rows evenly");
   __shared__ __align__(16) unsigned char lds[GM_LDS_BYTES];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
   const int S = a.split_k;
@@ -69,90 +94,98 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const GemmArgs a, int ti
   const int total_steps = row_bytes / 64;
   const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
   const int nch = (s1 - s0 + GM_STEPS - 1) / GM_STEPS;
-
-  const RowMap rm = map_row<EPI>(a, tile, wave * 16 + r16);
-  const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
-  const unsigned char *wrow = (const unsigned char *)wm + (size_t)(rm.valid ? rm.n : 0) * row_bytes + g * 16;
-  if (nch <= 0) return;                                // cannot happen: every split owns at least one step
-  const unsigned char *xg = (const unsigned char *)a.x;
-  const int x_row0 = tid >> 5, x_col = (tid & 31) * 16;      // 32 lanes cover one 512-byte row piece
-
-  // Software pipeline.  Weight fragments come from HBM: they are requested GM_NST-1 chunks ahead into a
-  // register ring.  Activation pieces come from L2: requested two chunks ahead into registers, written to
-  // the LDS buffer of the next chunk after the current chunk's math, one barrier per chunk.  Within an
-  // iteration the activation loads are issued before the weight loads, so waiting for them (loads
-  // complete in order) never waits for the younger, slower weight loads.
-  uint4 aw[GM_NST][GM_STEPS], xr[2][GM_XL];
-  auto load_w = [&](int c, uint4 (&af)[GM_STEPS]) {
-    #pragma unroll
-    for (int s = 0; s < GM_STEPS; ++s) {
-      // Unconditional load (a predicated load with a zero alternative makes the compiler wait for every
-      // load at the merge).  Steps past the slice re-read its last step: harmless, because the activation
-      // tile is zero there and weights are finite; rows past N re-read row 0 and are never stored.
-      const int st = min(s0 + c * GM_STEPS + s, s1 - 1);
-      af[s] = ldg16(wrow + (size_t)st * 64);
-    }
-  };
-  auto load_x = [&](int c, uint4 (&xf)[GM_XL]) {
-    const int byte = (s0 + c * GM_STEPS) * 64 + x_col;
-    const bool in_k = byte < s1 * 64;
-    #pragma unroll
-    for (int j = 0; j < GM_XL; ++j) {
-      const int mg = m_base + x_row0 + 8 * j;
-      const bool ok = in_k && mg < a.M;                 // out-of-range pieces read the tensor's first bytes ...
-      xf[j] = ldg16(xg + (ok ? (size_t)mg * row_bytes + byte : (size_t)0));
-    }
-  };
-  auto store_x = [&](int bufi, int c, const uint4 (&xf)[GM_XL]) {
-    unsigned char *buf = lds + bufi * (GM_BM * GM_PITCH);
-    const bool in_k = (s0 + c * GM_STEPS) * 64 + x_col < s1 * 64;
-    #pragma unroll
-    for (int j = 0; j < GM_XL; ++j) {
-      const bool ok = in_k && (m_base + x_row0 + 8 * j) < a.M;   // ... and are replaced by zeros here
-      *reinterpret_cast<uint4 *>(buf + (x_row0 + 8 * j) * GM_PITCH + x_col) = ok ? xf[j] : make_uint4(0u, 0u, 0u, 0u);
-    }
-  };
+  // Both roles run the same number of iterations (a multiple of two, the depth of every ring) with
+  // no conditional inside: chunks past the slice load clamped addresses and stage zeros, so the
+  // compiler can count outstanding loads exactly instead of draining them at every join.
+  const int nch2 = (nch + 1) & ~1;
 
   f32x4 acc[4];
   #pragma unroll
   for (int mb = 0; mb < 4; ++mb) acc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // The chunk loop runs to a multiple of GM_NST with no conditional inside: chunks past the slice load
-  // clamped addresses and stage zeros, so every iteration issues the same number of loads and the
-  // compiler can count outstanding loads exactly instead of draining them at every join.
-  const int nch4 = (nch + GM_NST - 1) / GM_NST * GM_NST;
-  load_x(0, xr[0]);
-  load_w(0, aw[0]);
-  load_x(1, xr[1]);
-  #pragma unroll
-  for (int u = 1; u < GM_NST - 1; ++u) load_w(u, aw[u]);
-  store_x(0, 0, xr[0]);
-  __syncthreads();
-  for (int c = 0; c < nch4; c += GM_NST) {
-    #pragma unroll
-    for (int u = 0; u < GM_NST; ++u) {
-      const int cc = c + u;
-      load_x(cc + 2, xr[u & 1]);                        // slot of chunk cc: already in LDS
-      load_w(cc + GM_NST - 1, aw[(u + GM_NST - 1) % GM_NST]);
-      const unsigned char *buf = lds + (u & 1) * (GM_BM * GM_PITCH);
+  if (wave < NB) {
+    // ------------------------------------------------------------------------------- math wave
+    const RowMap rm = map_row<EPI, BN>(a, tile, wave * 16 + r16);
+    const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
+    const unsigned char *wrow = (const unsigned char *)wm + (size_t)(rm.valid ? rm.n : 0) * row_bytes + g * 16;
+    uint4 aw[2][GM_STEPS];
+    auto load_w = [&](int c, uint4 (&af)[GM_STEPS]) {
       #pragma unroll
       for (int s = 0; s < GM_STEPS; ++s) {
-        #pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          const uint4 bfrag = *reinterpret_cast<const uint4 *>(buf + (mb * 16 + r16) * GM_PITCH + s * 64 + g * 16);
-          acc[mb] = mma16<T>(aw[u][s], bfrag, acc[mb]);
-        }
+        // Unconditional load (a predicated load with a zero alternative makes the compiler wait for every
+        // load at the merge).  Steps past the slice re-read its last step: harmless, because the activation
+        // tile is zero there and weights are finite; rows past N re-read row 0 and are never stored.
+        const int st = min(s0 + c * GM_STEPS + s, s1 - 1);
+        af[s] = ldg16(wrow + (size_t)st * 64);
       }
-      store_x((u + 1) & 1, cc + 1, xr[(u + 1) & 1]);
-      __syncthreads();
+    };
+    load_w(0, aw[0]);
+    __syncthreads();
+    for (int c = 0; c < nch2; c += 2) {
+      #pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        load_w(c + u + 1, aw[u ^ 1]);
+        const unsigned char *buf = lds + u * GM_STAGE;
+        #pragma unroll
+        for (int s = 0; s < GM_STEPS; ++s) {
+          #pragma unroll
+          for (int mb = 0; mb < 4; ++mb) {
+            const uint4 bfrag = *reinterpret_cast<const uint4 *>(buf + (mb * 16 + r16) * GM_PITCH + s * 64 + g * 16);
+            acc[mb] = mma16<T>(aw[u][s], bfrag, acc[mb]);
+          }
+        }
+        __syncthreads();
+      }
+    }
+  } else {
+    // ----------------------------------------------------------------------------- loader wave
+    // 32 lanes cover one 512-byte row piece, a wave instruction two rows; chunk c+1 is written to its
+    // stage while the math waves work on chunk c, and chunk c+2 is already on its way from L2.
+    const unsigned char *xg = (const unsigned char *)a.x;
+    const int x_row0 = (wave - NB) * XROWS + (lane >> 5), x_col = (lane & 31) * 16;
+    uint4 xr[2][XL];
+    auto load_x = [&](int c, uint4 (&xf)[XL]) {
+      const int byte = (s0 + c * GM_STEPS) * 64 + x_col;
+      const bool in_k = byte < s1 * 64;
+      #pragma unroll
+      for (int j = 0; j < XL; ++j) {
+        const int mg = m_base + x_row0 + 2 * j;
+        const bool ok = in_k && mg < a.M;                 // out-of-range pieces read the tensor's first bytes ...
+        xf[j] = ldg16(xg + (ok ? (size_t)mg * row_bytes + byte : (size_t)0));
+      }
+    };
+    auto store_x = [&](int stage, int c, const uint4 (&xf)[XL]) {
+      unsigned char *buf = lds + stage * GM_STAGE;
+      const bool in_k = (s0 + c * GM_STEPS) * 64 + x_col < s1 * 64;
+      #pragma unroll
+      for (int j = 0; j < XL; ++j) {
+        const bool ok = in_k && (m_base + x_row0 + 2 * j) < a.M;   // ... and are replaced by zeros here
+        *reinterpret_cast<uint4 *>(buf + (x_row0 + 2 * j) * GM_PITCH + x_col) = ok ? xf[j] : make_uint4(0u, 0u, 0u, 0u);
+      }
+    };
+    load_x(0, xr[0]);
+    load_x(1, xr[1]);
+    store_x(0, 0, xr[0]);
+    __syncthreads();
+    for (int c = 0; c < nch2; c += 2) {
+      #pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        load_x(c + u + 2, xr[u]);                         // slot of chunk c+u: already in LDS
+        store_x(u ^ 1, c + u + 1, xr[u ^ 1]);
+        __syncthreads();
+      }
     }
   }
 
-  // accumulators -> Ct[m][r] (float32): lane holds rows r = wave*16 + g*4 .. +4 of column m
+  // accumulators -> Ct[m][r] (float32): a math lane holds rows r = wave*16 + g*4 .. +4 of column m.
+  // The last barrier of the loop has passed, so nobody reads the stages any more; the one write still
+  // outstanding (the loaders' zero chunk nch2) went to stage nch2 % 2 before that barrier.
   float *Ct = reinterpret_cast<float *>(lds);
-  #pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
-    *reinterpret_cast<f32x4 *>(Ct + (mb * 16 + r16) * GM_CT_PITCH + wave * 16 + g * 4) = acc[mb];
+  if (wave < NB) {
+    #pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+      *reinterpret_cast<f32x4 *>(Ct + (mb * 16 + r16) * CT_PITCH + wave * 16 + g * 4) = acc[mb];
+  }
   __syncthreads();
 
   // ---------------------------------------------------------------------------------- epilogues
@@ -160,30 +193,31 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const GemmArgs a, int ti
     // out is [split_k][M][N]: slab `split` receives this workgroup's partial sums
     const int N = a.seg_rows;
     float *slab = a.out + (size_t)split * a.M * N;
-    for (int idx = tid; idx < GM_BM * GM_BN; idx += 256) {
-      const int m = idx >> 6, r = idx & 63, mg = m_base + m, n = tile * GM_BN + r;
-      if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * GM_CT_PITCH + r];
+    for (int idx = tid; idx < GM_BM * BN; idx += NT) {
+      const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
+      if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
     }
   } else if (EPI == EPI_SWIGLU) {
+    constexpr int H = BN / 2;
     const int f = a.seg_rows;
     T *act = (T *)a.act;
-    for (int idx = tid; idx < GM_BM * 32; idx += 256) {
-      const int m = idx >> 5, r = idx & 31, mg = m_base + m, j = tile * 32 + r;
+    for (int idx = tid; idx < GM_BM * H; idx += NT) {
+      const int m = idx / H, r = idx % H, mg = m_base + m, j = tile * H + r;
       if (mg < a.M && j < f)
-        act[(size_t)mg * f + j] = Elem<T>::from_f32(silu_f(Ct[m * GM_CT_PITCH + r]) * Ct[m * GM_CT_PITCH + r + 32]);
+        act[(size_t)mg * f + j] = Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + r]) * Ct[m * CT_PITCH + r + H]);
     }
   } else if (EPI == EPI_QKV_ROPE) {
-    const int d_h = a.d_h, d = a.n_heads * d_h, tps = d / GM_BN;
+    const int d_h = a.d_h, d = a.n_heads * d_h, tps = d / BN;
     const int seg = tile / tps, tl = tile % tps;
     if (seg < 2) {
-      const int half = d_h / 2, tph = d_h / GM_BN;
+      const int half = d_h / 2, tph = d_h / BN;
       const int head = tl / tph, p = tl % tph;
-      for (int idx = tid; idx < GM_BM * 32; idx += 256) {
+      for (int idx = tid; idx < GM_BM * 32; idx += NT) {
         const int m = idx >> 5, r = idx & 31, mg = m_base + m;
         if (mg >= a.M) continue;
         const int e = p * 32 + r;
         const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
-        const float x1 = Ct[m * GM_CT_PITCH + r], x2 = Ct[m * GM_CT_PITCH + r + 32];
+        const float x1 = Ct[m * CT_PITCH + r], x2 = Ct[m * CT_PITCH + r + 32];
         const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
         if (seg == 0) {
           T *q = (T *)a.q_out + (size_t)mg * d + head * d_h + e;
@@ -202,41 +236,44 @@ __global__ __launch_bounds__(256, 2) void k_gemm_skinny(const GemmArgs a, int ti
       }
     } else {
       // values: dimension-major cache, consecutive threads -> consecutive tree rows
-      for (int idx = tid; idx < GM_BM * GM_BN; idx += 256) {
+      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
         const int r = idx >> 6, m = idx & 63, mg = m_base + m;
         if (mg >= a.M) continue;
-        const int n = tl * GM_BN + r, head = n / d_h, e = n % d_h;
+        const int n = tl * BN + r, head = n / d_h, e = n % d_h;
         const int b = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[b];
         if (L < 0 || L + a.T_nodes > a.max_kv) continue;
         T *vc = (T *)a.v_cache + (((size_t)b * a.n_heads + head) * d_h + e) * a.max_kv + (L + node);
-        *vc = Elem<T>::from_f32(Ct[m * GM_CT_PITCH + r]);
+        *vc = Elem<T>::from_f32(Ct[m * CT_PITCH + r]);
       }
     }
   } else if (EPI == EPI_ARGMAX) {
     const int N = a.seg_rows;
     if (a.logits) {
-      for (int idx = tid; idx < GM_BM * GM_BN; idx += 256) {
-        const int m = idx >> 6, r = idx & 63, mg = m_base + m, n = tile * GM_BN + r;
-        if (mg < a.M && n < N) a.logits[(size_t)mg * N + n] = Ct[m * GM_CT_PITCH + r];
+      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
+        const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
+        if (mg < a.M && n < N) a.logits[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
       }
     }
-    // 4 threads per token row, 16 columns each, then a 4-lane butterfly (ties -> lower column)
-    const int m = tid >> 2, part = tid & 3, mg = m_base + m;
-    float bv = -__builtin_huge_valf(); int bi = 0x7fffffff;
-    for (int r = part * 16; r < part * 16 + 16; ++r) {
-      const int n = tile * GM_BN + r;
-      const float v = Ct[m * GM_CT_PITCH + r];
-      if (n < N && (v > bv || (v == bv && n < bi))) { bv = v; bi = n; }
-    }
-    #pragma unroll
-    for (int off = 1; off <= 2; off <<= 1) {
-      const float ov = __shfl_xor(bv, off, WAVE);
-      const int oi = __shfl_xor(bi, off, WAVE);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-    }
-    if (part == 0 && mg < a.M) {
-      a.amax_val[(size_t)tile * a.M + mg] = bv;
-      a.amax_idx[(size_t)tile * a.M + mg] = bi;
+    // 4 threads per token row (the first four waves), BN/4 columns each, then a 4-lane butterfly
+    // (ties -> lower column)
+    if (tid < 4 * GM_BM) {
+      const int m = tid >> 2, part = tid & 3, mg = m_base + m;
+      float bv = -__builtin_huge_valf(); int bi = 0x7fffffff;
+      for (int r = part * (BN / 4); r < (part + 1) * (BN / 4); ++r) {
+        const int n = tile * BN + r;
+        const float v = Ct[m * CT_PITCH + r];
+        if (n < N && (v > bv || (v == bv && n < bi))) { bv = v; bi = n; }
+      }
+      #pragma unroll
+      for (int off = 1; off <= 2; off <<= 1) {
+        const float ov = __shfl_xor(bv, off, WAVE);
+        const int oi = __shfl_xor(bi, off, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      if (part == 0 && mg < a.M) {
+        a.amax_val[(size_t)tile * a.M + mg] = bv;
+        a.amax_idx[(size_t)tile * a.M + mg] = bi;
+      }
     }
   }
 }
@@ -302,9 +339,10 @@ hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32
 
 int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h) {
   (void)d_h; (void)n_seg;
-  if (epi == EPI_QKV_ROPE) return 3 * (seg_rows / GM_BN);
-  if (epi == EPI_SWIGLU) return (seg_rows + 31) / 32;
-  return (seg_rows + GM_BN - 1) / GM_BN;
+  const int bn = 16 * gemm_nb(epi);
+  if (epi == EPI_QKV_ROPE) return 3 * (seg_rows / bn);
+  if (epi == EPI_SWIGLU) return (seg_rows + bn / 2 - 1) / (bn / 2);
+  return (seg_rows + bn - 1) / bn;
 }
 
 // Split the reduction axis only where the output alone gives too few workgroups for the chip.
@@ -323,13 +361,13 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a) {
   const int tiles = gemm_tiles_n(epi, a.n_seg, a.seg_rows, a.d_h);
   const int mblocks = (a.M + GM_BM - 1) / GM_BM;
   if (mblocks > 65535) return hipErrorInvalidValue;
-  if (epi == EPI_QKV_ROPE && (a.d_h % 64 || (a.n_heads * a.d_h) % GM_BN || !a.rope_cs)) return hipErrorInvalidValue;
-  const dim3 grid(tiles * a.split_k, mblocks), block(256);
+  if (epi == EPI_QKV_ROPE && (a.d_h % 64 || (a.n_heads * a.d_h) % 64 || !a.rope_cs)) return hipErrorInvalidValue;
+  const dim3 grid(tiles * a.split_k, mblocks);
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE>), grid, block, 0, st, a, tiles); break;
-    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE>), grid, block, 0, st, a, tiles); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU>), grid, block, 0, st, a, tiles); break;
-    case EPI_ARGMAX: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX>), grid, block, 0, st, a, tiles); break;
+    case EPI_STORE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles); break;
+    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles); break;
+    case EPI_ARGMAX: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
