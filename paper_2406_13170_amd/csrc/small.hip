@@ -379,50 +379,62 @@ hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *d
 // Row-wise RMSNorm for the target path, fused with the fold of the previous GEMM's partial slabs:
 //   x[m] (+)= sum_s slabs[s][m]   (or x[m] = embed[tok[m]] on entry to the first layer)
 //   xn[m] = x[m] / rms(x[m]) * g  stored as T for the matrix cores; hidden_out optionally in float32.
-// One workgroup per row; the row lives in registers (d <= 8192).
+// One 1024-thread workgroup per row, one 16-byte piece of every operand per thread and pass.  The
+// number of slabs, the source of the row and the number of passes are template parameters so that the
+// body is straight-line code: every load of a pass is issued before the first use (a run-time loop over
+// slabs costs one memory round trip per slab).  d <= 8192.
 // =====================================================================================================
-constexpr int NR_VEC = 8;
-
-template <typename T>
-__global__ __launch_bounds__(256) void k_norm_fold(float *x, const T *embed, const int32_t *tok, int vocab,
-                                                   const float *slabs, int S, size_t slab_stride, const T *g, int d,
-                                                   float eps, T *xn, float *hidden_out, uint32_t *dev_status) {
-  __shared__ float red[4];
+template <typename T, int S, bool EMB, int NP>
+__global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, const int32_t *tok, int vocab,
+                                                    const float *slabs, size_t slab_stride, const T *g, int d,
+                                                    float eps, T *xn, float *hidden_out, uint32_t *dev_status) {
+  __shared__ float red[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   float *xr = x + (size_t)row * d;
-  float v[NR_VEC][4];
   int t = 0;
-  if (tok) {
+  if (EMB) {
     t = tok[row];
     if (t < 0 || t >= vocab) { if (tid == 0) atomicOr(dev_status, 4u); t = 0; }
   }
+  float v[NP][4], gk[NP][4], p[NP][S > 0 ? S : 1][4];
+  #pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int k = (tid + i * 1024) * 4, kk = k < d ? k : 0;      // pieces past the row re-read its start, unused
+    if (EMB) load4<T>(embed + (size_t)t * d + kk, v[i]);
+    else load4<float>(xr + kk, v[i]);
+    #pragma unroll
+    for (int s = 0; s < S; ++s) load4<float>(slabs + (size_t)s * slab_stride + (size_t)row * d + kk, p[i][s]);
+    load4<T>(g + kk, gk[i]);
+  }
   float ss = 0.f;
   #pragma unroll
-  for (int i = 0; i < NR_VEC; ++i) {
-    const int k = (tid + i * 256) * 4;
+  for (int i = 0; i < NP; ++i) {
+    const int k = (tid + i * 1024) * 4;
+    #pragma unroll
+    for (int s = 0; s < S; ++s) {
+      #pragma unroll
+      for (int j = 0; j < 4; ++j) v[i][j] += p[i][s][j];
+    }
     if (k < d) {
-      if (tok) load4<T>(embed + (size_t)t * d + k, v[i]);
-      else load4<float>(xr + k, v[i]);
-      for (int s = 0; s < S; ++s) {
-        float p[4];
-        load4<float>(slabs + (size_t)s * slab_stride + (size_t)row * d + k, p);
-        #pragma unroll
-        for (int j = 0; j < 4; ++j) v[i][j] += p[j];
-      }
-      if (tok || S > 0) store4<float>(xr + k, v[i]);
+      if (EMB || S > 0) store4<float>(xr + k, v[i]);
       #pragma unroll
       for (int j = 0; j < 4; ++j) ss = fmaf(v[i][j], v[i][j], ss);
     }
   }
-  const float rs = rsqrtf(block_sum_256(ss, red) / (float)d + eps);
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) red[tid >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
   #pragma unroll
-  for (int i = 0; i < NR_VEC; ++i) {
-    const int k = (tid + i * 256) * 4;
+  for (int w = 0; w < 16; ++w) tot += red[w];
+  const float rs = rsqrtf(tot / (float)d + eps);
+  #pragma unroll
+  for (int i = 0; i < NP; ++i) {
+    const int k = (tid + i * 1024) * 4;
     if (k < d) {
-      float gk[4], o[4];
-      load4<T>(g + k, gk);
+      float o[4];
       #pragma unroll
-      for (int j = 0; j < 4; ++j) o[j] = v[i][j] * rs * gk[j];
+      for (int j = 0; j < 4; ++j) o[j] = v[i][j] * rs * gk[i][j];
       store4<T>(xn + (size_t)row * d + k, o);
       if (hidden_out) store4<float>(hidden_out + (size_t)row * d + k, o);
     }
@@ -433,9 +445,24 @@ template <typename T>
 hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
                             const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
                             void *xn, float *hidden_out, uint32_t *dev_status) {
-  if (d % 4 || d > NR_VEC * 256 * 4) return hipErrorInvalidValue;
-  hipLaunchKernelGGL((k_norm_fold<T>), dim3(rows), dim3(256), 0, st, x, (const T *)embed, tok, vocab, slabs, S, slab_stride,
-                     (const T *)g, d, eps, (T *)xn, hidden_out, dev_status);
+  if (d % 4 || d > 8192) return hipErrorInvalidValue;
+  if (tok && S != 0) return hipErrorInvalidValue;                  // the embedding gather starts a fresh residual stream
+  const int np = d > 4096 ? 2 : 1;
+  #define NF_LAUNCH(S_, EMB_, NP_)                                                                                  \
+    hipLaunchKernelGGL((k_norm_fold<T, S_, EMB_, NP_>), dim3(rows), dim3(1024), 0, st, x, (const T *)embed, tok,    \
+                       vocab, slabs, slab_stride, (const T *)g, d, eps, (T *)xn, hidden_out, dev_status)
+  #define NF_CASE(S_)                                                                                               \
+    case S_: if (np == 1) NF_LAUNCH(S_, false, 1); else NF_LAUNCH(S_, false, 2); break
+  if (tok) {
+    if (np == 1) NF_LAUNCH(0, true, 1); else NF_LAUNCH(0, true, 2);
+  } else {
+    switch (S) {
+      NF_CASE(0); NF_CASE(1); NF_CASE(2); NF_CASE(4); NF_CASE(8);
+      default: return hipErrorInvalidValue;
+    }
+  }
+  #undef NF_CASE
+  #undef NF_LAUNCH
   return hipGetLastError();
 }
 template hipError_t launch_norm_fold<float>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
