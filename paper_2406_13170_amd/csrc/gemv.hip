@@ -84,38 +84,68 @@ template <int M> __device__ __forceinline__ void zero_acc(float (&acc)[GV_R][M])
 }
 
 // ---- prologues: fill xs (and zero its padding), return per-row inverse RMS where asked ---------------
+// float4 slot of the 4 consecutive elements starting at k (k % 4 == 0) of row m in the layout above
+template <typename T> __device__ __forceinline__ int xs_quad(int m, int nC, int k) {
+  constexpr int PER = XLayout<T>::PER, NQ = XLayout<T>::NQ, CH = XLayout<T>::CH;
+  const int c = k / CH, r = k % CH;
+  return ((m * nC + c) * NQ + (r % PER) / 4) * 64 + r / PER;
+}
+
+// Rows x[m][k] (float32, leading dimension ldx), optionally multiplied by g[k], into xs; rows
+// m >= m_valid and the padding up to nC chunks become zero.  With NORM, ss[m] receives this thread's
+// share of sum_k x[m][k]^2.  Every thread issues the 16-byte loads of several pieces of all M rows
+// before it uses any of them; pieces out of range read the row's start and are replaced by zeros
+// (a predicated load would make the compiler wait for each load on its own).
+template <typename T, int M, bool NORM>
+__device__ __forceinline__ void fill_xs(float *xs, const float *x, int ldx, const T *g, int m_valid, int Kd, int nC,
+                                        float (&ss)[M]) {
+  constexpr int UJ = (M >= 4) ? 2 : 4;
+  const int nq = nC * XLayout<T>::CH / 4;
+  float4 *xs4 = reinterpret_cast<float4 *>(xs);
+  for (int j0 = threadIdx.x; j0 < nq; j0 += GV_THREADS * UJ) {
+    float v[UJ][M][4], gk[UJ][4];
+    #pragma unroll
+    for (int u = 0; u < UJ; ++u) {
+      const int k = (j0 + u * GV_THREADS) * 4, kk = (k < Kd) ? k : 0;
+      if (NORM) load4<T>(g + kk, gk[u]);
+      #pragma unroll
+      for (int m = 0; m < M; ++m) load4<float>(x + (size_t)(m < m_valid ? m : 0) * ldx + kk, v[u][m]);
+    }
+    #pragma unroll
+    for (int u = 0; u < UJ; ++u) {
+      const int q = j0 + u * GV_THREADS, k = q * 4;
+      if (q < nq) {
+        #pragma unroll
+        for (int m = 0; m < M; ++m) {
+          const bool ok = k < Kd && m < m_valid;
+          float4 o;
+          o.x = ok ? v[u][m][0] : 0.f; o.y = ok ? v[u][m][1] : 0.f; o.z = ok ? v[u][m][2] : 0.f; o.w = ok ? v[u][m][3] : 0.f;
+          if (NORM) {
+            ss[m] = fmaf(o.x, o.x, fmaf(o.y, o.y, fmaf(o.z, o.z, fmaf(o.w, o.w, ss[m]))));
+            o.x *= gk[u][0]; o.y *= gk[u][1]; o.z *= gk[u][2]; o.w *= gk[u][3];
+          }
+          xs4[xs_quad<T>(m, nC, k)] = o;
+        }
+      }
+    }
+  }
+}
+
 // plain float32 rows x[m][k], leading dimension ldx; rows m >= m_valid are zero.
 template <typename T, int M>
 __device__ __forceinline__ void load_x_plain(float *xs, const float *x, int ldx, int m_valid, int Kd, int nC) {
-  constexpr int CH = XLayout<T>::CH;
-  const int Kp = nC * CH;
-  for (int i = threadIdx.x; i < M * Kp; i += GV_THREADS) {
-    const int m = i / Kp, k = i % Kp;
-    float v = 0.f;
-    if (m < m_valid && k < Kd) v = x[(size_t)m * ldx + k];
-    xs[XLayout<T>::index(m, nC, k)] = v;
-  }
+  float ss[M];
+  fill_xs<T, M, false>(xs, x, ldx, (const T *)nullptr, m_valid, Kd, nC, ss);
 }
 
 // x[m][k] * g[k] with the row's 1/rms returned in rs[m] (applied by the caller to the dot products).
 template <typename T, int M>
 __device__ __forceinline__ void load_x_rmsnorm(float *xs, float *red, const float *x, int ldx, const T *g,
                                                int m_valid, int Kd, int nC, float eps, float (&rs)[M]) {
-  constexpr int CH = XLayout<T>::CH;
-  const int Kp = nC * CH;
   float ss[M];
   #pragma unroll
   for (int m = 0; m < M; ++m) ss[m] = 0.f;
-  for (int k = threadIdx.x; k < Kp; k += GV_THREADS) {
-    const float gk = (k < Kd) ? Elem<T>::to_f32(g[k]) : 0.f;
-    #pragma unroll
-    for (int m = 0; m < M; ++m) {
-      float v = 0.f;
-      if (m < m_valid && k < Kd) v = x[(size_t)m * ldx + k];
-      ss[m] = fmaf(v, v, ss[m]);
-      xs[XLayout<T>::index(m, nC, k)] = v * gk;
-    }
-  }
+  fill_xs<T, M, true>(xs, x, ldx, g, m_valid, Kd, nC, ss);
   #pragma unroll
   for (int m = 0; m < M; ++m) {
     const float tot = block_sum_256(ss[m], red);
@@ -134,18 +164,49 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
   constexpr int CH = XLayout<T>::CH;
   const int Kd = 2 * d, nC = (Kd + CH - 1) / CH, Kp = nC * CH;
   float *xs = smem;
-  for (int i = threadIdx.x; i < M * Kp; i += GV_THREADS) {
-    const int m = i / Kp, k = i % Kp;
-    float v = 0.f;
-    if (m < m_valid && k < Kd) {
-      if (k < d) v = u[(size_t)m * d + k];
-      else {
-        const int t = tok[m];
-        if (t >= 0 && t < vocab) v = Elem<T>::to_f32(embed[(size_t)t * d + (k - d)]);
-        else if (blockIdx.x == 0 && k == d) atomicOr(dev_status, 4u);
+  {
+    // [u ; e]: both halves are loaded for every piece (clamped addresses) and the right one is kept
+    float4 *xs4 = reinterpret_cast<float4 *>(xs);
+    const int nq = Kp / 4;
+    int t[M]; bool tok_ok[M];
+    #pragma unroll
+    for (int m = 0; m < M; ++m) {
+      t[m] = tok[m < m_valid ? m : 0];
+      tok_ok[m] = t[m] >= 0 && t[m] < vocab;
+      if (!tok_ok[m]) {
+        if (m < m_valid && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(dev_status, 4u);
+        t[m] = 0;
       }
     }
-    xs[XLayout<T>::index(m, nC, k)] = v;
+    for (int j0 = threadIdx.x; j0 < nq; j0 += GV_THREADS * 2) {
+      float vu[2][M][4], ve[2][M][4];
+      #pragma unroll
+      for (int q2 = 0; q2 < 2; ++q2) {
+        const int k = (j0 + q2 * GV_THREADS) * 4;
+        const int ku = (k < d) ? k : 0, ke = (k >= d && k < Kd) ? k - d : 0;
+        #pragma unroll
+        for (int m = 0; m < M; ++m) {
+          load4<float>(u + (size_t)(m < m_valid ? m : 0) * d + ku, vu[q2][m]);
+          load4<T>(embed + (size_t)t[m] * d + ke, ve[q2][m]);
+        }
+      }
+      #pragma unroll
+      for (int q2 = 0; q2 < 2; ++q2) {
+        const int q = j0 + q2 * GV_THREADS, k = q * 4;
+        if (q < nq) {
+          #pragma unroll
+          for (int m = 0; m < M; ++m) {
+            const bool in_u = k < d, ok = m < m_valid && k < Kd && (in_u || tok_ok[m]);
+            float4 o;
+            o.x = ok ? (in_u ? vu[q2][m][0] : ve[q2][m][0]) : 0.f;
+            o.y = ok ? (in_u ? vu[q2][m][1] : ve[q2][m][1]) : 0.f;
+            o.z = ok ? (in_u ? vu[q2][m][2] : ve[q2][m][2]) : 0.f;
+            o.w = ok ? (in_u ? vu[q2][m][3] : ve[q2][m][3]) : 0.f;
+            xs4[xs_quad<T>(m, nC, k)] = o;
+          }
+        }
+      }
+    }
   }
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;

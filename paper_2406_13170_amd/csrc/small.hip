@@ -5,29 +5,6 @@
 
 namespace amph {
 
-// 4 consecutive elements of T <-> float[4]
-template <typename T> __device__ __forceinline__ void load4(const T *p, float *f);
-template <> __device__ __forceinline__ void load4<float>(const float *p, float *f) {
-  const float4 v = *reinterpret_cast<const float4 *>(p);
-  f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-}
-template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t *p, float *f) {
-  const uint2 v = *reinterpret_cast<const uint2 *>(p);
-  f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-  f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-}
-template <typename T> __device__ __forceinline__ void store4(T *p, const float *f);
-template <> __device__ __forceinline__ void store4<float>(float *p, const float *f) {
-  *reinterpret_cast<float4 *>(p) = make_float4(f[0], f[1], f[2], f[3]);
-}
-template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t *p, const float *f) {
-  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-  bf16x4 v;
-  #pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = (bf16_t)f[i];
-  *reinterpret_cast<bf16x4 *>(p) = v;
-}
-
 // =====================================================================================================
 // Single-query attention over a SAL cache: one new position per (batch, head) against rows
 // [0, sal_len] of the cache (the new row included).  grid = (heads, batch), 1024 threads: the 16
