@@ -173,8 +173,10 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
 
 /* ---- per-kernel timing, for measurement ------------------------------------------------------------
  * Every kernel launch inside amph_draft / amph_target_forward / amph_verify_attn belongs to one kind.
- * amph_profile_kind selects one kind (or -1 for none): from then on each launch of that kind is
- * bracketed by a pair of HIP events on the context's stream, up to max_launches launches.
+ * amph_profile_kind selects one kind (or -1 for none): from then on one launch in `every` (>= 1; the
+ * first, the every+1-th, ...) of that kind is bracketed by a pair of HIP events on the context's stream,
+ * up to max_launches timed launches.  A pair of events costs a few microseconds of stream time, so a
+ * caller that also measures end-to-end time samples sparsely.
  * amph_profile_read SYNCHRONISES the stream, returns the summed elapsed time and the number of launches
  * recorded since the last read, and resets the count.  Not for use under stream capture. */
 typedef enum {
@@ -183,7 +185,7 @@ typedef enum {
   AMPH_K_T_RMSNORM, AMPH_K_T_QKV, AMPH_K_VERIFY, AMPH_K_T_WO, AMPH_K_T_GATEUP, AMPH_K_T_DOWN, AMPH_K_T_LMHEAD,
   AMPH_K_COUNT
 } amph_kernel_kind;
-amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches);
+amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches, int every);
 amph_status amph_profile_read(amph_ctx *ctx, double *total_ms /* host */, int *launches /* host */);
 
 /* ---- single linear layers, exported for per-kernel parity tests and micro-benchmarks ------------

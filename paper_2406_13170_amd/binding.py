@@ -54,7 +54,7 @@ EXPORTS = {
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
     "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.c_int] + [C.c_void_p] * 12),
-    "amph_profile_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_int]),
+    "amph_profile_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "amph_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     "amph_gemv": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "amph_gemm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]),
@@ -233,8 +233,8 @@ class Context:
                                               _ptr(hidden_out), _ptr(logits_out), _ptr(tgt_argmax), _ptr(self.workspace)),
                     "amph_target_forward")
 
-    def amph_profile_kind(self, kind: int, max_launches: int = 4096):
-        self._check(lib().amph_profile_kind(self.handle, kind, max_launches), "amph_profile_kind")
+    def amph_profile_kind(self, kind: int, max_launches: int = 4096, every: int = 1):
+        self._check(lib().amph_profile_kind(self.handle, kind, max_launches, every), "amph_profile_kind")
 
     def amph_profile_read(self):
         ms, n = C.c_double(), C.c_int()

@@ -38,6 +38,8 @@ struct amph_ctx {
   int prof_kind = -1;                 // amph_kernel_kind being timed, -1 = none
   std::vector<hipEvent_t> prof_ev;    // start/stop pairs
   size_t prof_used = 0;
+  int prof_every = 1;                 // one launch in this many is timed
+  long long prof_seen = 0;            // launches of prof_kind since it was selected
 };
 
 struct amph_tree {
@@ -67,7 +69,8 @@ amph_status hip_fail(amph_ctx *ctx, hipError_t e, const char *where) {
 // Launch `expr`; when its kind is the one being profiled, bracket it with a pair of events on the stream.
 #define PROF_TRY(ctx, kind, expr)                                                              \
   do {                                                                                         \
-    const bool p__ = ((ctx)->prof_kind == (kind)) && ((ctx)->prof_used < (ctx)->prof_ev.size() / 2); \
+    const bool p__ = ((ctx)->prof_kind == (kind)) && ((ctx)->prof_seen++ % (ctx)->prof_every == 0) && \
+                     ((ctx)->prof_used < (ctx)->prof_ev.size() / 2);                                   \
     if (p__) HIP_TRY(ctx, hipEventRecord((ctx)->prof_ev[2 * (ctx)->prof_used], (ctx)->stream));       \
     HIP_TRY(ctx, expr);                                                                        \
     if (p__) {                                                                                 \
@@ -490,10 +493,10 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
                             kv_len, hidden_out, logits_out, tgt_argmax, workspace);
 }
 
-amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches) {
+amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches, int every) {
   if (!ctx) return AMPH_EINVAL;
-  if (kind < -1 || kind >= AMPH_K_COUNT || max_launches < 0 || max_launches > 65536)
-    return fail(ctx, AMPH_EINVAL, "amph_profile_kind: bad kind or max_launches");
+  if (kind < -1 || kind >= AMPH_K_COUNT || max_launches < 0 || max_launches > 65536 || every < 1)
+    return fail(ctx, AMPH_EINVAL, "amph_profile_kind: bad kind, max_launches or every");
   while (ctx->prof_ev.size() < (size_t)2 * max_launches) {
     hipEvent_t e;
     HIP_TRY(ctx, hipEventCreate(&e));
@@ -501,6 +504,8 @@ amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches) {
   }
   ctx->prof_kind = kind;
   ctx->prof_used = 0;
+  ctx->prof_every = every;
+  ctx->prof_seen = 0;
   return AMPH_OK;
 }
 

@@ -33,7 +33,7 @@ constexpr int GM_LDS_BYTES = 2 * GM_STAGE;
 // row blocks (16 weight rows = one math wave) and loader waves per workgroup, by epilogue
 template <int EPI> struct GemmShape;
 template <> struct GemmShape<EPI_STORE> { static constexpr int NB = 4, NLW = 4; };
-template <> struct GemmShape<EPI_QKV_ROPE> { static constexpr int NB = 4, NLW = 4; };   // 32 rows + their 32 RoPE partners
+template <> struct GemmShape<EPI_QKV_ROPE> { static constexpr int NB = 3, NLW = 2; };   // 768 row blocks -> 256 tiles at d = 4096
 template <> struct GemmShape<EPI_SWIGLU> { static constexpr int NB = 6, NLW = 2; };     // 48 gate rows + 48 up rows
 template <> struct GemmShape<EPI_ARGMAX> { static constexpr int NB = 8, NLW = 4; };
 
@@ -53,18 +53,16 @@ template <int EPI, int BN>
 __device__ __forceinline__ RowMap map_row(const GemmArgs &a, int tile, int r) {
   RowMap o;
   if (EPI == EPI_QKV_ROPE) {
-    static_assert(EPI != EPI_QKV_ROPE || BN == 64, "RoPE tiles pair 32 rows with their 32 partners");
-    const int d = a.n_heads * a.d_h, tps = d / BN;
-    o.seg = tile / tps;
-    const int tl = tile % tps;
-    if (o.seg < 2) {
-      const int half = a.d_h / 2, tph = a.d_h / BN;
-      const int head = tl / tph, p = tl % tph;
-      o.n = head * a.d_h + p * 32 + (r & 31) + ((r >= 32) ? half : 0);
-    } else {
-      o.n = tl * BN + r;
-    }
-    o.valid = true;
+    // The unit is a row block (one math wave): for q and k, 8 rows of a head and their 8 RoPE partners
+    // (i, i + d_h/2), so that every block rotates on its own and a tile may be any run of blocks; for v,
+    // 16 consecutive rows.  Blocks are numbered q, then k, then v.
+    const int d = a.n_heads * a.d_h, bps = d / 16, bph = a.d_h / 16;
+    const int b = tile * (BN / 16) + r / 16, r16 = r % 16;
+    o.valid = b < 3 * bps;
+    o.seg = o.valid ? b / bps : 0;
+    const int bl = o.valid ? b % bps : 0;
+    if (o.seg < 2) o.n = (bl / bph) * a.d_h + (bl % bph) * 8 + (r16 & 7) + ((r16 >= 8) ? a.d_h / 2 : 0);
+    else o.n = bl * 16 + r16;
   } else if (EPI == EPI_SWIGLU) {
     constexpr int H = BN / 2;
     o.seg = (r >= H) ? 1 : 0;
@@ -207,43 +205,45 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
         act[(size_t)mg * f + j] = Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + r]) * Ct[m * CT_PITCH + r + H]);
     }
   } else if (EPI == EPI_QKV_ROPE) {
-    const int d_h = a.d_h, d = a.n_heads * d_h, tps = d / BN;
-    const int seg = tile / tps, tl = tile % tps;
-    if (seg < 2) {
-      const int half = d_h / 2, tph = d_h / BN;
-      const int head = tl / tph, p = tl % tph;
-      for (int idx = tid; idx < GM_BM * 32; idx += NT) {
-        const int m = idx >> 5, r = idx & 31, mg = m_base + m;
+    // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
+    const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
+    for (int idx = tid; idx < NB * 512; idx += NT) {
+      const int w = idx >> 9, rem = idx & 511, b = tile * NB + w;
+      if (b >= 3 * bps) continue;
+      const int seg = b / bps, bl = b % bps;
+      if (seg < 2) {
+        const int m = rem >> 3, j = rem & 7, mg = m_base + m;
         if (mg >= a.M) continue;
-        const int e = p * 32 + r;
+        const int head = bl / bph, e = (bl % bph) * 8 + j;
         const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
-        const float x1 = Ct[m * CT_PITCH + r], x2 = Ct[m * CT_PITCH + r + 32];
+        const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
         const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
         if (seg == 0) {
           T *q = (T *)a.q_out + (size_t)mg * d + head * d_h + e;
           q[0] = Elem<T>::from_f32(y1);
           q[half] = Elem<T>::from_f32(y2);
         } else {
-          const int b = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[b];
+          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
           if (L < 0 || L + a.T_nodes > a.max_kv) {
-            if (r == 0 && node == 0) atomicOr(a.dev_status, 2u);
+            if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
             continue;
           }
-          T *kc = (T *)a.k_cache + (((size_t)b * a.n_heads + head) * a.max_kv + (L + node)) * d_h + e;
+          T *kc = (T *)a.k_cache + (((size_t)bb * a.n_heads + head) * a.max_kv + (L + node)) * d_h + e;
           kc[0] = Elem<T>::from_f32(y1);
           kc[half] = Elem<T>::from_f32(y2);
         }
-      }
-    } else {
-      // values: dimension-major cache, consecutive threads -> consecutive tree rows
-      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
-        const int r = idx >> 6, m = idx & 63, mg = m_base + m;
+      } else {
+        // values: dimension-major cache, consecutive threads -> consecutive tree rows
+        const int j = rem >> 6, m = rem & 63, mg = m_base + m;
         if (mg >= a.M) continue;
-        const int n = tl * BN + r, head = n / d_h, e = n % d_h;
-        const int b = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[b];
+        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
         if (L < 0 || L + a.T_nodes > a.max_kv) continue;
-        T *vc = (T *)a.v_cache + (((size_t)b * a.n_heads + head) * d_h + e) * a.max_kv + (L + node);
-        *vc = Elem<T>::from_f32(Ct[m * CT_PITCH + r]);
+        #pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
+          T *vc = (T *)a.v_cache + (((size_t)bb * a.n_heads + head) * d_h + e) * a.max_kv + (L + node);
+          *vc = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
+        }
       }
     }
   } else if (EPI == EPI_ARGMAX) {
@@ -340,7 +340,7 @@ hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32
 int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h) {
   (void)d_h; (void)n_seg;
   const int bn = 16 * gemm_nb(epi);
-  if (epi == EPI_QKV_ROPE) return 3 * (seg_rows / bn);
+  if (epi == EPI_QKV_ROPE) return (3 * (seg_rows / 16) + bn / 16 - 1) / (bn / 16);
   if (epi == EPI_SWIGLU) return (seg_rows + bn / 2 - 1) / (bn / 2);
   return (seg_rows + bn - 1) / bn;
 }
@@ -361,7 +361,7 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a) {
   const int tiles = gemm_tiles_n(epi, a.n_seg, a.seg_rows, a.d_h);
   const int mblocks = (a.M + GM_BM - 1) / GM_BM;
   if (mblocks > 65535) return hipErrorInvalidValue;
-  if (epi == EPI_QKV_ROPE && (a.d_h % 64 || (a.n_heads * a.d_h) % 64 || !a.rope_cs)) return hipErrorInvalidValue;
+  if (epi == EPI_QKV_ROPE && (a.d_h % 16 || !a.rope_cs)) return hipErrorInvalidValue;
   const dim3 grid(tiles * a.split_k, mblocks);
   switch (epi) {
     case EPI_STORE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles); break;

@@ -227,9 +227,10 @@ __global__ __launch_bounds__(256) void k_topk_pass1(const float *logits, int V, 
   float x[TK_NPT]; int id[TK_NPT];
   #pragma unroll
   for (int j = 0; j < TK_NPT; ++j) {
+    // unconditional loads from clamped addresses (a predicated load makes the compiler wait for each one)
     const int e = chunk * TK_CHUNK + j * WAVE + lane;
     id[j] = (e < V) ? e : V;
-    x[j] = (e < V) ? src[e] : 0.f;
+    x[j] = src[min(e, V - 1)];
   }
   const size_t o = ((size_t)row * chunks_per_row + chunk) * k;
   wave_select<TK_NPT>(x, id, k, V, cand_v + o, cand_i + o);
@@ -242,11 +243,13 @@ __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const in
   float x[TK_MAXC]; int id[TK_MAXC];
   #pragma unroll
   for (int j = 0; j < TK_MAXC; ++j) {
-    const int c = j * WAVE + lane;
-    const int ci = (c < n_cand) ? cand_i[(size_t)row * n_cand + c] : -1;
-    id[j] = (ci >= 0) ? ci : V;
-    x[j] = (ci >= 0) ? cand_v[(size_t)row * n_cand + c] : 0.f;
+    const int c = min(j * WAVE + lane, n_cand - 1);
+    id[j] = cand_i[(size_t)row * n_cand + c];
+    x[j] = cand_v[(size_t)row * n_cand + c];
   }
+  #pragma unroll
+  for (int j = 0; j < TK_MAXC; ++j)
+    if (j * WAVE + lane >= n_cand || id[j] < 0) id[j] = V;
   __shared__ float sv[AMPH_MAX_TOPK];
   __shared__ int si[AMPH_MAX_TOPK];
   wave_select<TK_MAXC>(x, id, k, V, sv, si);
