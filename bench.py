@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain streaming copy (read 256 MiB, write 256 MiB) so that a counter run can "
+                         "scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
     ap.add_argument("--profile-kind", default=None, help="kernel kind to time live (default: the one with the largest share)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -194,6 +197,16 @@ def main():
         ctx.amph_target_forward(tree, structs, dw["embed"], final_norm, t_lm_head, tree_tok, tree_pos, k_caches, v_caches,
                                 kv_len, None, None, tgt)
         ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
+
+    if args.calibrate_copy:
+        n_cal = 64 * 2 ** 20                                   # float32 elements: 256 MiB in, 256 MiB out
+        cal_src = torch.ones(n_cal, dtype=torch.float32, device=dev)
+        cal_dst = torch.empty_like(cal_src)
+        torch.cuda.synchronize()
+        torch.mul(cal_src, 1.0, out=cal_dst)                   # one elementwise kernel over n_cal elements
+        torch.cuda.synchronize()
+        log(f"[bench] calibration copy: {n_cal} float32 elements, {n_cal * 4} bytes read and as many written")
+        del cal_src, cal_dst
 
     for _ in range(max(args.warmup, 1)):
         step()
