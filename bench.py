@@ -121,6 +121,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
+    ap.add_argument("--row-major", action="store_true",
+                    help="feed the target's GEMMs the row-major matrices instead of their tiled copies (slower; for comparison)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming copy (read 256 MiB, write 256 MiB) so that a counter run can "
                          "scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -182,6 +184,22 @@ def main():
     tree = B.Tree(si.tree_paths(T, cfg.tree_caps), K)
     dstruct = B.Context.draft_struct(dw)
     structs = [B.Context.layer_struct(l) for l in layers]
+    tiled_structs = lm_tiled = tiled_keep = None
+    if not args.row_major:
+        # The target's matrices in the tiled layout the matrix-core GEMM streams (amph_pack_weights, once at load
+        # time); the row-major copies are dropped, as a server would.
+        tiled_structs, tiled_keep = [], []
+        for li, l in enumerate(layers):
+            ts, tt = D.pack_layer(ctx, l)
+            tiled_structs.append(ts)
+            tiled_keep.append(tt)
+            structs[li] = B.amph_layer_w(rms1=l["rms1"].data_ptr(), rms2=l["rms2"].data_ptr())
+            torch.cuda.synchronize()
+            for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+                del l[k]
+        lm_tiled = D.pack_lm_head(ctx, t_lm_head)
+        torch.cuda.synchronize()
+        t_lm_head = None
     i32 = lambda *shape: torch.zeros(shape, dtype=torch.int32, device=dev)
     topk_idx, topk_val = i32(Bsz, K, cfg.topk), torch.zeros((Bsz, K, cfg.topk), dtype=torch.float32, device=dev)
     tree_tok, tree_pos, tgt = i32(Bsz, T), i32(Bsz, T), i32(Bsz, T)
@@ -195,7 +213,7 @@ def main():
         ctx.amph_draft(dstruct, h, tok, sal_kv, sal_len, topk_idx, topk_val, None)
         ctx.amph_tree_build(tree, tok, topk_idx, kv_len, tree_tok, tree_pos)
         ctx.amph_target_forward(tree, structs, dw["embed"], final_norm, t_lm_head, tree_tok, tree_pos, k_caches, v_caches,
-                                kv_len, None, None, tgt)
+                                kv_len, None, None, tgt, tiled_structs=tiled_structs, lm_head_tiled=lm_tiled)
         ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
 
     if args.calibrate_copy:
@@ -267,7 +285,8 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} full step: draft (K={K}, top-{cfg.topk}, SAL cache {Ls}) + {n_layers}-layer "
                                f"tree verification (T={T}, L={L}) + greedy accept, batch {Bsz}",
-                   "layers": n_layers, "tree_nodes": T, "kv_len": L, "batch": Bsz},
+                   "layers": n_layers, "tree_nodes": T, "kv_len": L, "batch": Bsz,
+                   "target_weight_layout": "row-major" if args.row_major else "tiled"},
         "step_algorithmic_GB": sb / 1e9,
         "step_hbm_frac": sb * steps_per_s / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -66,6 +66,20 @@ typedef struct amph_layer_w {
   const void *w_down;               /* [d, f]  */
 } amph_layer_w;
 
+/* The matrices of one target layer in the TILED layout that the matrix-core GEMM streams at full rate
+ * (amph_pack_weights writes it, once per matrix, from the row-major matrices).  A matrix-core operand
+ * fragment is 16 rows x 64 bytes; read from a row-major matrix it touches 16 half cache lines per
+ * load instruction, which the vector L1 of a CU handles about four times slower than one contiguous
+ * 1 KB load.  The tiled copy stores every fragment the kernel will ask for as one contiguous 1 KB piece,
+ * in the order the kernel walks them; its exact form is private to the library (amph_tiled_bytes gives
+ * the size).  A NULL member means "use the row-major matrices of amph_layer_w for this GEMM". */
+typedef struct amph_layer_tiled {
+  const void *qkv;          /* from wq, wk, wv  (AMPH_PACK_QKV)    */
+  const void *wo;           /* from wo          (AMPH_PACK_WO)     */
+  const void *gate_up;      /* from w_gate, w_up (AMPH_PACK_GATEUP) */
+  const void *down;         /* from w_down      (AMPH_PACK_DOWN)   */
+} amph_layer_tiled;
+
 /* Weights of the draft module (host struct of device pointers; all T). */
 typedef struct amph_draft_w {
   const void *embed;        /* [V, d]  target's embedding table: e_{t+1} (Sec. 3.1)                */
@@ -159,17 +173,31 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
  * cache rows [kv_len, kv_len + T), tree attention (as amph_verify_attn), output projection and
  * residual, RMSNorm, SwiGLU FFN and residual; then the final RMSNorm, the LM head and the per-node
  * argmax (ties to the lowest id).
- *   layers     host array [n_layers] of device-pointer structs
+ *   layers     host array [n_layers] of device-pointer structs; rms1 and rms2 are always read, a matrix
+ *              only where the layer's tiled copy is absent (its pointer may then be NULL)
+ *   tiled      host array [n_layers] of tiled copies (amph_pack_weights), or NULL: all row-major
+ *   lm_head    [V, d] row-major, may be NULL when lm_head_tiled (AMPH_PACK_LMHEAD) is given
  *   k_caches   [n_layers, B, n_heads, max_kv, head_dim] T
  *   v_caches   [n_layers, B, n_heads, head_dim, max_kv] T (dimension-major, see amph_verify_attn)
  *   hidden_out [B, T, d] float32 (final-normed hidden states) or NULL
  *   logits_out [B, T, V] float32 or NULL
  *   tgt_argmax [B, T] int32 */
 amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers /* host */,
-                                int n_layers, const void *embed, const void *final_norm,
-                                const void *lm_head, const int32_t *tree_tok, const int32_t *tree_pos,
+                                const amph_layer_tiled *tiled /* host or NULL */, int n_layers,
+                                const void *embed, const void *final_norm, const void *lm_head,
+                                const void *lm_head_tiled, const int32_t *tree_tok, const int32_t *tree_pos,
                                 void *k_caches, void *v_caches, const int32_t *kv_len, float *hidden_out,
                                 float *logits_out, int32_t *tgt_argmax, void *workspace);
+
+/* ---- weight tiling for the target's GEMMs (A7, A9) -----------------------------------------------------
+ * amph_tiled_bytes: size in bytes of the tiled copy for one role, for this context's shapes and type.
+ * amph_pack_weights: writes it (asynchronously, on the context's stream) from the row-major device
+ * matrices: QKV takes (wq, wk, wv), GATEUP takes (w_gate, w_up, NULL), the others (w, NULL, NULL).
+ * dst must be 16-byte aligned and must not overlap the sources.  The results of amph_target_forward
+ * are bit-identical with and without tiling: only addresses change, never the order of the sums. */
+typedef enum { AMPH_PACK_QKV = 0, AMPH_PACK_WO, AMPH_PACK_GATEUP, AMPH_PACK_DOWN, AMPH_PACK_LMHEAD, AMPH_PACK_COUNT } amph_pack_role;
+amph_status amph_tiled_bytes(const amph_ctx *ctx, int role, size_t *bytes /* host */);
+amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const void *w1, const void *w2, void *dst);
 
 /* ---- per-kernel timing, for measurement ------------------------------------------------------------
  * Every kernel launch inside amph_draft / amph_target_forward / amph_verify_attn belongs to one kind.

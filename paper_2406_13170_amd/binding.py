@@ -32,6 +32,13 @@ class amph_layer_w(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("rms1", "wq", "wk", "wv", "wo", "rms2", "w_gate", "w_up", "w_down")]
 
 
+class amph_layer_tiled(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("qkv", "wo", "gate_up", "down")]
+
+
+AMPH_PACK_QKV, AMPH_PACK_WO, AMPH_PACK_GATEUP, AMPH_PACK_DOWN, AMPH_PACK_LMHEAD = range(5)
+
+
 class amph_draft_w(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("fc", C.c_void_p * 2), ("sal", amph_layer_w * 2), ("mlp", C.c_void_p),
                 ("pe", C.c_void_p), ("aeb_wq", C.c_void_p), ("aeb_wk", C.c_void_p), ("aeb_wv", C.c_void_p),
@@ -53,7 +60,10 @@ EXPORTS = {
     "amph_tree_build": (C.c_int, [C.c_void_p] * 7),
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
-    "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.c_int] + [C.c_void_p] * 12),
+    "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.POINTER(amph_layer_tiled), C.c_int]
+                            + [C.c_void_p] * 13),
+    "amph_tiled_bytes": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]),
+    "amph_pack_weights": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "amph_profile_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "amph_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     "amph_gemv": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
@@ -225,13 +235,26 @@ class Context:
                                       _ptr(self.workspace)), "amph_accept")
 
     def amph_target_forward(self, tree: Tree, layer_structs, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches,
-                            v_caches, kv_len, hidden_out, logits_out, tgt_argmax):
+                            v_caches, kv_len, hidden_out, logits_out, tgt_argmax, tiled_structs=None, lm_head_tiled=None):
         n = len(layer_structs)
         arr = (amph_layer_w * max(n, 1))(*layer_structs)
-        self._check(lib().amph_target_forward(self.handle, tree.handle, arr, n, _ptr(embed), _ptr(final_norm), _ptr(lm_head),
-                                              _ptr(tree_tok), _ptr(tree_pos), _ptr(k_caches), _ptr(v_caches), _ptr(kv_len),
-                                              _ptr(hidden_out), _ptr(logits_out), _ptr(tgt_argmax), _ptr(self.workspace)),
+        tarr = None
+        if tiled_structs is not None:
+            assert len(tiled_structs) == n
+            tarr = (amph_layer_tiled * max(n, 1))(*tiled_structs)
+        self._check(lib().amph_target_forward(self.handle, tree.handle, arr, tarr, n, _ptr(embed), _ptr(final_norm),
+                                              _ptr(lm_head), _ptr(lm_head_tiled), _ptr(tree_tok), _ptr(tree_pos),
+                                              _ptr(k_caches), _ptr(v_caches), _ptr(kv_len), _ptr(hidden_out),
+                                              _ptr(logits_out), _ptr(tgt_argmax), _ptr(self.workspace)),
                     "amph_target_forward")
+
+    def amph_tiled_bytes(self, role: int) -> int:
+        n = C.c_size_t()
+        self._check(lib().amph_tiled_bytes(self.handle, role, C.byref(n)), "amph_tiled_bytes")
+        return n.value
+
+    def amph_pack_weights(self, role: int, w0, w1, w2, dst):
+        self._check(lib().amph_pack_weights(self.handle, role, _ptr(w0), _ptr(w1), _ptr(w2), _ptr(dst)), "amph_pack_weights")
 
     def amph_profile_kind(self, kind: int, max_launches: int = 4096, every: int = 1):
         self._check(lib().amph_profile_kind(self.handle, kind, max_launches, every), "amph_profile_kind")

@@ -189,8 +189,9 @@ amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, con
 }
 
 template <typename T>
-amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers, int n_layers, const void *embed,
-                        const void *final_norm, const void *lm_head, const int32_t *tree_tok, const int32_t *tree_pos,
+amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers, const amph_layer_tiled *tiled,
+                        int n_layers, const void *embed, const void *final_norm, const void *lm_head,
+                        const void *lm_head_tiled, const int32_t *tree_tok, const int32_t *tree_pos,
                         void *k_caches, void *v_caches, const int32_t *kv_len, float *hidden_out, float *logits_out,
                         int32_t *tgt_argmax, void *workspace) {
   const amph_config &c = ctx->cfg;
@@ -219,31 +220,32 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   int pending = 0;                        // slabs of the previous GEMM still to be added to the residual stream
   for (int li = 0; li < n_layers; ++li) {
     const amph_layer_w &lw = layers[li];
+    const amph_layer_tiled lt = tiled ? tiled[li] : amph_layer_tiled{nullptr, nullptr, nullptr, nullptr};
     void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, slabs, pending,
                                                         slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status));
     GemmArgs a = g;
-    a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
+    a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.wt = lt.qkv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
     PROF_TRY(ctx, AMPH_K_T_QKV, launch_gemm<T>(st, EPI_QKV_ROPE, a));
     if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
     a = g;
-    a.w0 = lw.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
+    a.w0 = lw.wo; a.wt = lt.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
     PROF_TRY(ctx, AMPH_K_T_WO, launch_gemm<T>(st, EPI_STORE, a));
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, nullptr, nullptr, V, slabs, s_wo, slab, lw.rms2, M, d,
                                                         c.rms_eps, xn, nullptr, ctx->dev_status));
     a = g;
-    a.w0 = lw.w_gate; a.w1 = lw.w_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
+    a.w0 = lw.w_gate; a.w1 = lw.w_up; a.wt = lt.gate_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
     PROF_TRY(ctx, AMPH_K_T_GATEUP, launch_gemm<T>(st, EPI_SWIGLU, a));
     a = g;
-    a.w0 = lw.w_down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = slabs; a.split_k = s_down;
+    a.w0 = lw.w_down; a.wt = lt.down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = slabs; a.split_k = s_down;
     PROF_TRY(ctx, AMPH_K_T_DOWN, launch_gemm<T>(st, EPI_STORE, a));
     pending = s_down;
   }
   PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, slabs, pending,
                                                       slab, final_norm, M, d, c.rms_eps, xn, hidden_out, ctx->dev_status));
   GemmArgs a = g;
-  a.w0 = lm_head; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
+  a.w0 = lm_head; a.wt = lm_head_tiled; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
   a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
   PROF_TRY(ctx, AMPH_K_T_LMHEAD, launch_gemm<T>(st, EPI_ARGMAX, a));
@@ -467,30 +469,73 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
   return AMPH_OK;
 }
 
-amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers, int n_layers,
-                                const void *embed, const void *final_norm, const void *lm_head, const int32_t *tree_tok,
+amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w *layers,
+                                const amph_layer_tiled *tiled, int n_layers, const void *embed, const void *final_norm,
+                                const void *lm_head, const void *lm_head_tiled, const int32_t *tree_tok,
                                 const int32_t *tree_pos, void *k_caches, void *v_caches, const int32_t *kv_len,
                                 float *hidden_out, float *logits_out, int32_t *tgt_argmax, void *workspace) {
   if (!ctx) return AMPH_EINVAL;
   if (n_layers < 0 || (n_layers > 0 && !layers)) return fail(ctx, AMPH_EINVAL, "amph_target_forward: bad layers");
-  if (!embed || !final_norm || !lm_head || !tree_tok || !tree_pos || !kv_len || !tgt_argmax || !workspace ||
-      (n_layers > 0 && (!k_caches || !v_caches)))
+  if (!embed || !final_norm || (!lm_head && !lm_head_tiled) || !tree_tok || !tree_pos || !kv_len || !tgt_argmax ||
+      !workspace || (n_layers > 0 && (!k_caches || !v_caches)))
     return fail(ctx, AMPH_EINVAL, "amph_target_forward: null argument");
   for (int i = 0; i < n_layers; ++i) {
     const amph_layer_w &l = layers[i];
-    const void *lp[] = {l.rms1, l.wq, l.wk, l.wv, l.wo, l.rms2, l.w_gate, l.w_up, l.w_down};
+    const amph_layer_tiled t = tiled ? tiled[i] : amph_layer_tiled{nullptr, nullptr, nullptr, nullptr};
+    // every GEMM needs either its tiled copy or all of its row-major matrices
+    const bool ok = l.rms1 && l.rms2 && (t.qkv || (l.wq && l.wk && l.wv)) && (t.wo || l.wo) &&
+                    (t.gate_up || (l.w_gate && l.w_up)) && (t.down || l.w_down);
+    if (!ok) return fail(ctx, AMPH_EINVAL, "amph_target_forward: a layer lacks a weight in both layouts");
+    const void *lp[] = {l.rms1, l.wq, l.wk, l.wv, l.wo, l.rms2, l.w_gate, l.w_up, l.w_down, t.qkv, t.wo, t.gate_up, t.down};
     for (const void *p : lp)
-      if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_target_forward: null or misaligned layer weight");
+      if (p && !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_target_forward: misaligned layer weight");
   }
-  if (!aligned16(embed) || !aligned16(lm_head) || !aligned16(workspace) || (k_caches && !aligned16(k_caches)) ||
-      (v_caches && !aligned16(v_caches)))
+  if (!aligned16(embed) || !aligned16(lm_head) || !aligned16(lm_head_tiled) || !aligned16(workspace) ||
+      (k_caches && !aligned16(k_caches)) || (v_caches && !aligned16(v_caches)))
     return fail(ctx, AMPH_EINVAL, "amph_target_forward: pointers must be 16-byte aligned");
   if (amph_status s = check_tree(ctx, tree, "amph_target_forward")) return s;
   if (ctx->cfg.dtype == AMPH_BF16)
-    return target_impl<bf16_t>(ctx, tree, layers, n_layers, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches,
-                               v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
-  return target_impl<float>(ctx, tree, layers, n_layers, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches, v_caches,
-                            kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+    return target_impl<bf16_t>(ctx, tree, layers, tiled, n_layers, embed, final_norm, lm_head, lm_head_tiled, tree_tok,
+                               tree_pos, k_caches, v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+  return target_impl<float>(ctx, tree, layers, tiled, n_layers, embed, final_norm, lm_head, lm_head_tiled, tree_tok,
+                            tree_pos, k_caches, v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+}
+
+// shape of the GEMM a packing role belongs to: epilogue kind, stacked matrices, rows per matrix, reduction length
+static bool pack_shape(const amph_config &c, int role, int *epi, int *n_seg, int *rows, int *Kd) {
+  switch (role) {
+    case AMPH_PACK_QKV: *epi = EPI_QKV_ROPE; *n_seg = 3; *rows = c.d_model; *Kd = c.d_model; return true;
+    case AMPH_PACK_WO: *epi = EPI_STORE; *n_seg = 1; *rows = c.d_model; *Kd = c.d_model; return true;
+    case AMPH_PACK_GATEUP: *epi = EPI_SWIGLU; *n_seg = 2; *rows = c.d_ffn; *Kd = c.d_model; return true;
+    case AMPH_PACK_DOWN: *epi = EPI_STORE; *n_seg = 1; *rows = c.d_model; *Kd = c.d_ffn; return true;
+    case AMPH_PACK_LMHEAD: *epi = EPI_ARGMAX; *n_seg = 1; *rows = c.vocab; *Kd = c.d_model; return true;
+    default: return false;
+  }
+}
+
+amph_status amph_tiled_bytes(const amph_ctx *ctx, int role, size_t *bytes) {
+  if (!ctx || !bytes) return AMPH_EINVAL;
+  int epi, n_seg, rows, Kd;
+  if (!pack_shape(ctx->cfg, role, &epi, &n_seg, &rows, &Kd)) return AMPH_EINVAL;
+  *bytes = gemm_tiled_bytes(epi, n_seg, rows, Kd, ctx->cfg.head_dim, (int)ctx->esz);
+  return AMPH_OK;
+}
+
+amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const void *w1, const void *w2, void *dst) {
+  if (!ctx) return AMPH_EINVAL;
+  int epi, n_seg, rows, Kd;
+  if (!pack_shape(ctx->cfg, role, &epi, &n_seg, &rows, &Kd)) return fail(ctx, AMPH_EINVAL, "amph_pack_weights: bad role");
+  if (!w0 || (n_seg >= 2 && !w1) || (n_seg >= 3 && !w2) || !dst)
+    return fail(ctx, AMPH_EINVAL, "amph_pack_weights: null argument");
+  if (!aligned16(w0) || !aligned16(w1) || !aligned16(w2) || !aligned16(dst))
+    return fail(ctx, AMPH_EINVAL, "amph_pack_weights: pointers must be 16-byte aligned");
+  if ((Kd * (int)ctx->esz) % 64) return fail(ctx, AMPH_ESHAPE, "amph_pack_weights: a weight row must be a multiple of 64 bytes");
+  GemmArgs a{};
+  a.w0 = w0; a.w1 = w1; a.w2 = w2; a.n_seg = n_seg; a.seg_rows = rows; a.Kd = Kd;
+  a.n_heads = ctx->cfg.n_heads; a.d_h = ctx->cfg.head_dim;
+  if (ctx->cfg.dtype == AMPH_BF16) HIP_TRY(ctx, launch_pack_weights<bf16_t>(ctx->stream, epi, a, dst));
+  else HIP_TRY(ctx, launch_pack_weights<float>(ctx->stream, epi, a, dst));
+  return AMPH_OK;
 }
 
 amph_status amph_profile_kind(amph_ctx *ctx, int kind, int max_launches, int every) {

@@ -14,12 +14,23 @@
 // the whole activation slice from L2, so that traffic is (64 / tile height) times the weight bytes and
 // measurably slows the weight stream; taller tiles cut it as far as the number of workgroups allows.
 //
+// Weight layouts.  Row-major [N, Kd] works, but a matrix-core A fragment is 16 rows x 64 bytes, so
+// every wave load touches 16 half cache lines; the vector L1 handles such loads at about a quarter of
+// the rate of a contiguous 1 KB load and the weight stream then stalls on the CU side, not on HBM
+// (measured: 41 us against 33 us for the gate/up shape).  The tiled layout (k_pack_weights, run once
+// per matrix) stores, for every row block the kernel uses and every 64-byte step of the reduction
+// axis, the 16 x 64 bytes of that fragment as one contiguous 1 KB piece:
+//   tiled[(block * (Kd * sizeof(T) / 64) + step) * 1024 + r * 64 + byte]  =  W[row(block, r)][step * 64 + byte]
+// with blocks numbered tile-major in the kernel's own row mapping (so q/k blocks are 8 rows + their 8
+// RoPE partners, gate/up tiles are 3 gate blocks + 3 up blocks) and rows past N stored as zeros.
+//
 // No workgroup ever communicates with another inside the kernel (a device-scope fence per workgroup
 // costs far more than the kernel on this chip): a split reduction axis writes one partial slab per
 // split, which the consumer (the RMSNorm kernel of the next sub-layer, or k_sum_slabs) adds up in a
 // fixed order; per-tile argmax candidates are folded by k_argmax_fold.  Fused epilogues: RoPE from a
 // precomputed table + KV-cache write, SwiGLU, per-tile row argmax.
 #include "kernels.h"
+#include <algorithm>
 
 namespace amph {
 
@@ -76,7 +87,7 @@ __device__ __forceinline__ RowMap map_row(const GemmArgs &a, int tile, int r) {
   return o;
 }
 
-template <typename T, int EPI>
+template <typename T, int EPI, bool TILED>
 __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) void k_gemm_skinny(const GemmArgs a, int tiles) {
   constexpr int NB = GemmShape<EPI>::NB, NLW = GemmShape<EPI>::NLW, BN = 16 * NB, NT = 64 * (NB + NLW);
   constexpr int CT_PITCH = BN + 4;                       // floats
@@ -103,9 +114,16 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
 
   if (wave < NB) {
     // ------------------------------------------------------------------------------- math wave
-    const RowMap rm = map_row<EPI, BN>(a, tile, wave * 16 + r16);
-    const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
-    const unsigned char *wrow = (const unsigned char *)wm + (size_t)(rm.valid ? rm.n : 0) * row_bytes + g * 16;
+    const unsigned char *wrow;
+    if (TILED) {
+      // the block's fragments lie one after another: step st is the 1 KB at st * 1024, this lane's 16 bytes at
+      // (r16 * 64 + g * 16) inside it
+      wrow = (const unsigned char *)a.wt + (size_t)(tile * NB + wave) * total_steps * 1024 + r16 * 64 + g * 16;
+    } else {
+      const RowMap rm = map_row<EPI, BN>(a, tile, wave * 16 + r16);
+      const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
+      wrow = (const unsigned char *)wm + (size_t)(rm.valid ? rm.n : 0) * row_bytes + g * 16;
+    }
     uint4 aw[2][GM_STEPS];
     auto load_w = [&](int c, uint4 (&af)[GM_STEPS]) {
       #pragma unroll
@@ -114,7 +132,7 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
         // load at the merge).  Steps past the slice re-read its last step: harmless, because the activation
         // tile is zero there and weights are finite; rows past N re-read row 0 and are never stored.
         const int st = min(s0 + c * GM_STEPS + s, s1 - 1);
-        af[s] = ldg16(wrow + (size_t)st * 64);
+        af[s] = ldg16(wrow + (size_t)st * (TILED ? 1024 : 64));
       }
     };
     load_w(0, aw[0]);
@@ -278,6 +296,52 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   }
 }
 
+// Row-major -> tiled (see the layout above).  One thread per 16-byte piece of the tiled buffer.
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void k_pack_weights(const GemmArgs a, int tiles, unsigned char *dst) {
+  constexpr int NB = GemmShape<EPI>::NB, BN = 16 * NB;
+  const int total_steps = a.Kd * (int)sizeof(T) / 64;
+  const size_t pieces = (size_t)tiles * NB * total_steps * 64;      // 64 pieces of 16 bytes per 1 KB fragment
+  for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pieces; p += (size_t)gridDim.x * 256) {
+    const int g = (int)(p & 3), r16 = (int)((p >> 2) & 15);
+    const size_t frag = p >> 6;
+    const int st = (int)(frag % total_steps);
+    const size_t blk = frag / total_steps;
+    const int tile = (int)(blk / NB), wv = (int)(blk % NB);
+    const RowMap rm = map_row<EPI, BN>(a, tile, wv * 16 + r16);
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (rm.valid) {
+      const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
+      v = ldg16((const unsigned char *)wm + ((size_t)rm.n * a.Kd * sizeof(T) + (size_t)st * 64 + g * 16));
+    }
+    stg16(dst + p * 16, v);
+  }
+}
+
+size_t gemm_tiled_bytes(int epi, int n_seg, int seg_rows, int Kd, int d_h, int elem_bytes) {
+  return (size_t)gemm_tiles_n(epi, n_seg, seg_rows, d_h) * gemm_nb(epi) * 16 * (size_t)Kd * elem_bytes;
+}
+
+template <typename T>
+hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst) {
+  if (a.Kd < 1 || (a.Kd * (int)sizeof(T)) % 64) return hipErrorInvalidValue;
+  if (epi == EPI_QKV_ROPE && a.d_h % 16) return hipErrorInvalidValue;
+  const int tiles = gemm_tiles_n(epi, a.n_seg, a.seg_rows, a.d_h);
+  const size_t pieces = gemm_tiled_bytes(epi, a.n_seg, a.seg_rows, a.Kd, a.d_h, (int)sizeof(T)) / 16;
+  const int blocks = (int)std::min<size_t>((pieces + 255) / 256, 65536);
+  unsigned char *d8 = (unsigned char *)dst;
+  switch (epi) {
+    case EPI_STORE: hipLaunchKernelGGL((k_pack_weights<T, EPI_STORE>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
+    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_pack_weights<T, EPI_QKV_ROPE>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((k_pack_weights<T, EPI_SWIGLU>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
+    case EPI_ARGMAX: hipLaunchKernelGGL((k_pack_weights<T, EPI_ARGMAX>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+template hipError_t launch_pack_weights<float>(hipStream_t, int, const GemmArgs &, void *);
+template hipError_t launch_pack_weights<bf16_t>(hipStream_t, int, const GemmArgs &, void *);
+
 // tgt[m] = index of the best of the per-tile winners (ties -> lower index); one wave per row
 __global__ __launch_bounds__(64) void k_argmax_fold(const float *amax_val, const int32_t *amax_idx, int tiles, int M,
                                                     int32_t *tgt) {
@@ -364,10 +428,22 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a) {
   if (epi == EPI_QKV_ROPE && (a.d_h % 16 || !a.rope_cs)) return hipErrorInvalidValue;
   const dim3 grid(tiles * a.split_k, mblocks);
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles); break;
-    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles); break;
-    case EPI_ARGMAX: hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles); break;
+    case EPI_STORE:
+      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE, true>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles);
+      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE, false>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles);
+      break;
+    case EPI_QKV_ROPE:
+      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE, true>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles);
+      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE, false>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles);
+      break;
+    case EPI_SWIGLU:
+      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU, true>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles);
+      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU, false>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles);
+      break;
+    case EPI_ARGMAX:
+      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX, true>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles);
+      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX, false>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

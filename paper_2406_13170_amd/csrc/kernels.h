@@ -52,7 +52,8 @@ hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const i
 // ---- gemm_skinny.hip (target path, rows on the matrix cores) ----
 enum GemmEpi { EPI_STORE = 0, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
 struct GemmArgs {
-  const void *w0, *w1, *w2;   // stacked matrices (q,k,v | gate,up | single)
+  const void *w0, *w1, *w2;   // stacked matrices (q,k,v | gate,up | single), row-major [seg_rows, Kd]
+  const void *wt;             // the same matrices in the tiled layout (launch_pack_weights), or NULL: then w0..w2 are read
   int n_seg, seg_rows;        // rows per matrix
   int Kd;
   const void *x;              // [M, Kd] T
@@ -76,6 +77,9 @@ struct GemmArgs {
 int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h);
 int gemm_auto_split(int tiles, int Kd, int elem_bytes);
 template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a);
+// bytes of the tiled copy of the matrices of one GEMM, and the kernel that writes it (w0..w2, n_seg, seg_rows, Kd, n_heads, d_h of a)
+size_t gemm_tiled_bytes(int epi, int n_seg, int seg_rows, int Kd, int d_h, int elem_bytes);
+template <typename T> hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst);
 hipError_t launch_rope_table(hipStream_t st, const int32_t *pos, int M, int d_h, float theta, float2 *cs);
 hipError_t launch_sum_slabs(hipStream_t st, const float *slabs, int S, size_t n, float *out);
 hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32_t *amax_idx, int tiles, int M,

@@ -6,7 +6,8 @@ from typing import Dict
 import numpy as np
 import torch
 
-from .binding import AMPH_BF16, AMPH_F32
+from .binding import (AMPH_BF16, AMPH_F32, AMPH_PACK_DOWN, AMPH_PACK_GATEUP, AMPH_PACK_LMHEAD, AMPH_PACK_QKV,
+                      AMPH_PACK_WO, amph_layer_tiled)
 
 
 def dtype_code(name: str) -> int:
@@ -43,3 +44,26 @@ def draft_to_device(dw: Dict[str, object], device="cuda:0") -> Dict[str, object]
 def values_to_dim_major(v_rows: torch.Tensor) -> torch.Tensor:
     """[..., rows, head_dim] -> [..., head_dim, rows] contiguous: the value-cache layout of amph_verify_attn."""
     return v_rows.transpose(-1, -2).contiguous()
+
+
+def pack_layer(ctx, lw: Dict[str, torch.Tensor]):
+    """Tiled copies of one target layer's matrices (amph_pack_weights).  Returns (amph_layer_tiled, tensors):
+    the caller keeps `tensors` alive as long as the struct is used."""
+    dev = lw["wq"].device
+
+    def buf(role):
+        return torch.empty(ctx.amph_tiled_bytes(role), dtype=torch.uint8, device=dev)
+
+    t = {"qkv": buf(AMPH_PACK_QKV), "wo": buf(AMPH_PACK_WO), "gate_up": buf(AMPH_PACK_GATEUP), "down": buf(AMPH_PACK_DOWN)}
+    ctx.amph_pack_weights(AMPH_PACK_QKV, lw["wq"], lw["wk"], lw["wv"], t["qkv"])
+    ctx.amph_pack_weights(AMPH_PACK_WO, lw["wo"], None, None, t["wo"])
+    ctx.amph_pack_weights(AMPH_PACK_GATEUP, lw["w_gate"], lw["w_up"], None, t["gate_up"])
+    ctx.amph_pack_weights(AMPH_PACK_DOWN, lw["w_down"], None, None, t["down"])
+    s = amph_layer_tiled(*[t[k].data_ptr() for k in ("qkv", "wo", "gate_up", "down")])
+    return s, t
+
+
+def pack_lm_head(ctx, lm_head: torch.Tensor) -> torch.Tensor:
+    out = torch.empty(ctx.amph_tiled_bytes(AMPH_PACK_LMHEAD), dtype=torch.uint8, device=lm_head.device)
+    ctx.amph_pack_weights(AMPH_PACK_LMHEAD, lm_head, None, None, out)
+    return out

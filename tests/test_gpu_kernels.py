@@ -113,6 +113,20 @@ def test_verify_attn_batch_independent_lengths_share_a_launch():
     verify_case(si.MINI, 64, (10,) * 4, 77, B_=3)
 
 
+@pytest.mark.parametrize("cfg,T,caps,L,B_", [
+    (si.MINI, 64, (10,) * 4, 77, 4),            # 4 x 4 heads x 4 query blocks
+    (si.MINI, 22, (10,) * 4, 37, 8),            # ragged last query block
+    (si.TINY, 64, (10,) * 4, 130, 4),           # float32 (16-key steps, 64-wide heads)
+    (si.MINI, 64, (10,) * 4, 0, 4),             # empty cache
+])
+def test_verify_attn_many_workgroups(cfg, T, caps, L, B_):
+    """Batches large enough that (batch, head, query block) alone fill a quarter of the chip: the launch
+    heuristics then pick few or no key splits."""
+    say(f"verify_attn {cfg.name} T={T} L={L} B={B_}")
+    worst = verify_case(cfg, T, caps, L, B_=B_)
+    say(f"  worst row error {worst:.2e}")
+
+
 def test_verify_attn_vicuna7b_shape():
     """Full 7B layer shape (32 heads x 128, L = 1024, T = 64) in the launch configuration the bench uses;
     every head checked against the oracle."""

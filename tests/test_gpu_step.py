@@ -115,7 +115,7 @@ def test_draft_is_deterministic_and_flags_overflow():
 
 
 # ---------------------------------------------------------------------------- amph_target_forward (A7-A9)
-def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1):
+def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False, oracle=True):
     cfg = si.with_(cfg, batch=Bsz, K=len(caps), topk=min(16, max(caps)))
     n_h, d_h, d, V = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab
     max_kv = (L + T + 31) // 32 * 32
@@ -140,10 +140,22 @@ def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1):
     hidden = torch.full((Bsz, T, d), float("nan"), dtype=torch.float32, device=DEV)
     logits = torch.full((Bsz, T, V), float("nan"), dtype=torch.float32, device=DEV)
     tgt = torch.full((Bsz, T), -1, dtype=torch.int32, device=DEV)
-    ctx.amph_target_forward(tree, structs, embed_d, fn_d, lm_d, i32_to_dev(tok), i32_to_dev(pos), k_caches, v_caches,
-                            i32_to_dev(np.full(Bsz, L)), hidden, logits, tgt)
+    tiled_structs = lm_t = keep = None
+    if tiled:
+        # tiled copies of every matrix; the row-major pointers are withheld to show that nothing reads them
+        packed = [D.pack_layer(ctx, l) for l in layers_d]
+        tiled_structs, keep = [p[0] for p in packed], [p[1] for p in packed]
+        lm_t = D.pack_lm_head(ctx, lm_d)
+        structs = [B.amph_layer_w(rms1=l["rms1"].data_ptr(), rms2=l["rms2"].data_ptr()) for l in layers_d]
+    ctx.amph_target_forward(tree, structs, embed_d, fn_d, None if tiled else lm_d, i32_to_dev(tok), i32_to_dev(pos),
+                            k_caches, v_caches, i32_to_dev(np.full(Bsz, L)), hidden, logits, tgt,
+                            tiled_structs=tiled_structs, lm_head_tiled=lm_t)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
+    del keep
+    if not oracle:
+        return cfg, None, dict(hidden=np_of(hidden), logits=np_of(logits), tgt=np_of(tgt), k_caches=k_caches,
+                               v_caches=v_caches, L=L, T=T), (ctx, tree, otree)
     two = dict(embed=tw["embed"].f32, layers=f32_layers(tw["layers"]), final_norm=tw["final_norm"].f32, lm_head=tw["lm_head"].f32)
     refs = [orc.target_forward(two, tok[b], pos[b], otree.mask, [kcs[li].f32[b] for li in range(n_layers)],
                                [vcs[li].f32[b] for li in range(n_layers)], n_h, cfg.rms_eps, cfg.rope_theta, keep=True)
@@ -182,6 +194,7 @@ def check_target(cfg, refs, got):
             assert_rows_close(vc, lay["v_new"], tol, f"layer {li} tree values")
 
 
+@pytest.mark.parametrize("tiled", [False, True], ids=["rowmajor", "tiled"])
 @pytest.mark.parametrize("cfg,n_layers,T,caps,L", [
     (si.TINY, 2, 16, (4, 2, 2, 2), 128),
     (si.TINY, 0, 16, (4, 2, 2, 2), 128),           # embedding -> final norm -> LM head only
@@ -189,9 +202,9 @@ def check_target(cfg, refs, got):
     (si.MINI, 2, 64, (10,) * 4, 200),
     (si.MINI, 3, 35, (10,) * 4, 61),
 ])
-def test_target_forward_matches_oracle(cfg, n_layers, T, caps, L):
-    say(f"target_forward {cfg.name} layers={n_layers} T={T} L={L}")
-    cfgx, refs, got, _ = run_target(cfg, n_layers, T, caps, L)
+def test_target_forward_matches_oracle(cfg, n_layers, T, caps, L, tiled):
+    say(f"target_forward {cfg.name} layers={n_layers} T={T} L={L} tiled={tiled}")
+    cfgx, refs, got, _ = run_target(cfg, n_layers, T, caps, L, tiled=tiled)
     check_target(cfgx, refs, got)
 
 
@@ -204,9 +217,14 @@ def test_target_forward_batch_two():
 def test_target_forward_vicuna7b_two_layers():
     """Configuration 3 at full width (d 4096, FFN 11008, 32 x 128 heads, V 32000, L 1024, T 64) with two
     layers: the per-layer launch configuration is the one the bench times."""
-    say("target_forward vicuna7b 2 layers")
-    cfgx, refs, got, _ = run_target(si.V7B, 2, 64, (10,) * 4, 1024)
+    say("target_forward vicuna7b 2 layers (tiled weights, as the bench runs them)")
+    cfgx, refs, got, _ = run_target(si.V7B, 2, 64, (10,) * 4, 1024, tiled=True)
     check_target(cfgx, refs, got)
+    say("  same inputs with row-major weights: results must be bit-identical")
+    _, _, got_rm, _ = run_target(si.V7B, 2, 64, (10,) * 4, 1024, tiled=False, oracle=False)
+    assert np.array_equal(got["logits"], got_rm["logits"]) and np.array_equal(got["tgt"], got_rm["tgt"])
+    assert np.array_equal(got["hidden"], got_rm["hidden"])
+    assert torch.equal(got["k_caches"][:, :, :, 1024:1088].view(torch.int16), got_rm["k_caches"][:, :, :, 1024:1088].view(torch.int16))
 
 
 # ---------------------------------------------------------------------------- one whole step (A1-A10)
