@@ -168,10 +168,10 @@ def main():
     final_norm = torch.ones(d, dtype=tdt, device=dev)
     t_lm_head = randn((V, d), 0.02)
     k_caches = torch.zeros((max(n_layers, 1), Bsz, n_h, max_kv, d_h), dtype=tdt, device=dev)
-    v_caches = torch.zeros((max(n_layers, 1), Bsz, n_h, d_h, max_kv), dtype=tdt, device=dev)
-    for li in range(n_layers):
+    v_caches = torch.zeros((max(n_layers, 1), Bsz, n_h, max_kv, d_h), dtype=tdt, device=dev)
+    for li in range(n_layers):      # random rows: the step-tiled storage order does not matter for throughput
         k_caches[li, :, :, :L] = randn((Bsz, n_h, L, d_h), 1.0)
-        v_caches[li, :, :, :, :L] = randn((Bsz, n_h, d_h, L), 1.0)
+        v_caches[li, :, :, :L] = randn((Bsz, n_h, L, d_h), 1.0)
     sal_kv = torch.zeros((2, Bsz, 2, n_h, max_kv, d_h), dtype=tdt, device=dev)
     sal_kv[:, :, :, :, :Ls] = randn((2, Bsz, 2, n_h, Ls, d_h), 1.0)
     h = torch.randn((Bsz, d), generator=gen, device=dev, dtype=torch.float32).to(tdt).float()

@@ -149,10 +149,17 @@ amph_status amph_tree_build(amph_ctx *ctx, const amph_tree *tree, const int32_t 
  * out[b, i, h] = sum_j softmax_j(q[b,i,h] . k_j / sqrt(head_dim)) v_j over all committed rows
  * j < kv_len[b] and the tree rows kv_len[b] + j' with j' = i or an ancestor of i.
  *   q, out  [B, T, n_heads, head_dim] T
- *   k_cache [B, n_heads, max_kv, head_dim] T   keys (already rotated); tree keys at rows
- *           [kv_len[b], kv_len[b] + T) in node order
- *   v_cache [B, n_heads, head_dim, max_kv] T   values stored dimension-major (transposed) so that a
- *           16-byte load yields consecutive rows of one dimension; same row numbering as k_cache
+ *   k_cache, v_cache   per (b, head) max_kv * head_dim elements of T each: rows (already rotated keys;
+ *           values) numbered as usual, tree rows at [kv_len[b], kv_len[b] + T) in node order, but stored
+ *           STEP-TILED so that every matrix-core fragment of the kernel is one contiguous 1 KB piece (a
+ *           row-major cache costs 16 half cache lines per fragment load, about four times slower in the
+ *           CU's vector L1).  With E = sizeof(T), P = 16/E, a key step = 4P rows (32 bf16 / 16 float):
+ *             K element (row r, dim c): step s = r / 4P, kk = r % 4P, tile t = (kk % P) / 4,
+ *               slot i = (kk / P) * 4 + kk % 4, piece ds = c*E / 64:
+ *               byte offset ((s * P/4 + t) * (head_dim*E/64) + ds) * 1024 + i * 64 + (c*E) % 64
+ *             V element (row r, dim c): step s = r / 4P, block db = c / 16:
+ *               byte offset (s * head_dim/16 + db) * 1024 + (c % 16) * 64 + (r % 4P) * E
+ *           (K: 16 rows x 64 bytes of their dims per piece; V: 16 dims x the step's 4P rows per piece.)
  * Device-side error: kv_len[b] + T > max_kv (AMPH_DEV_KV_OVERFLOW). */
 amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache,
                              const void *v_cache, const int32_t *kv_len, void *out, void *workspace);
@@ -177,8 +184,8 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
  *              only where the layer's tiled copy is absent (its pointer may then be NULL)
  *   tiled      host array [n_layers] of tiled copies (amph_pack_weights), or NULL: all row-major
  *   lm_head    [V, d] row-major, may be NULL when lm_head_tiled (AMPH_PACK_LMHEAD) is given
- *   k_caches   [n_layers, B, n_heads, max_kv, head_dim] T
- *   v_caches   [n_layers, B, n_heads, head_dim, max_kv] T (dimension-major, see amph_verify_attn)
+ *   k_caches, v_caches   [n_layers, B, n_heads] caches of max_kv * head_dim elements each, step-tiled as
+ *              amph_verify_attn describes; the call writes the tree rows of every layer
  *   hidden_out [B, T, d] float32 (final-normed hidden states) or NULL
  *   logits_out [B, T, V] float32 or NULL
  *   tgt_argmax [B, T] int32 */

@@ -57,6 +57,17 @@ static int gemm_nb(int epi) {
   }
 }
 
+// Element index of (row, dim) in the step-tiled K and V caches of one head (layout: header of the C ABI).
+template <typename T> __device__ __forceinline__ size_t k_tiled_index(int row, int c, int d_h) {
+  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);   // elements in 64 bytes
+  const int s = row / KSTEP, kk = row % KSTEP, t = (kk % PER) / 4, i = (kk / PER) * 4 + (kk & 3);
+  return ((size_t)(s * (PER / 4) + t) * (d_h / PIECE) + c / PIECE) * (16 * PIECE) + i * PIECE + c % PIECE;
+}
+template <typename T> __device__ __forceinline__ size_t v_tiled_index(int row, int c, int d_h) {
+  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);
+  return ((size_t)(row / KSTEP) * (d_h / 16) + c / 16) * (16 * PIECE) + (c % 16) * PIECE + row % KSTEP;
+}
+
 // weight row (within its matrix) and matrix index of tile row r
 struct RowMap { int seg; int n; bool valid; };
 
@@ -111,6 +122,24 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   f32x4 acc[4];
   #pragma unroll
   for (int mb = 0; mb < 4; ++mb) acc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  // RoPE epilogue: the table entries and cache lengths this thread will need are requested now, so that
+  // they arrive during the main loop instead of costing a memory round trip per epilogue iteration.
+  constexpr int QK_ITEMS = (NB * 512 + NT - 1) / NT;
+  float2 cs_pre[EPI == EPI_QKV_ROPE ? QK_ITEMS : 1];
+  int len_pre[EPI == EPI_QKV_ROPE ? QK_ITEMS : 1];
+  if (EPI == EPI_QKV_ROPE) {
+    const int d_h = a.d_h, bps = a.n_heads * d_h / 16, bph = d_h / 16, half = d_h / 2;
+    #pragma unroll
+    for (int it = 0; it < QK_ITEMS; ++it) {
+      const int idx = tid + it * NT, w = min(idx >> 9, NB - 1), rem = idx & 511;
+      const int b = min(tile * NB + w, 3 * bps - 1), seg = b / bps, bl = b % bps;
+      const int m = (seg < 2) ? (rem >> 3) : (rem & 63), mg = min(m_base + m, a.M - 1);
+      const int e = (seg < 2) ? (bl % bph) * 8 + (rem & 7) : 0;
+      cs_pre[it] = a.rope_cs[(size_t)mg * half + e];
+      len_pre[it] = a.kv_len[mg / a.T_nodes];
+    }
+  }
 
   if (wave < NB) {
     // ------------------------------------------------------------------------------- math wave
@@ -225,15 +254,18 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   } else if (EPI == EPI_QKV_ROPE) {
     // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
     const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
-    for (int idx = tid; idx < NB * 512; idx += NT) {
+    #pragma unroll
+    for (int it = 0; it < QK_ITEMS; ++it) {
+      const int idx = tid + it * NT;
+      if (idx >= NB * 512) continue;
       const int w = idx >> 9, rem = idx & 511, b = tile * NB + w;
       if (b >= 3 * bps) continue;
-      const int seg = b / bps, bl = b % bps;
+      const int seg = b / bps, bl = b % bps, L = len_pre[it];
       if (seg < 2) {
         const int m = rem >> 3, j = rem & 7, mg = m_base + m;
         if (mg >= a.M) continue;
         const int head = bl / bph, e = (bl % bph) * 8 + j;
-        const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
+        const float2 cs = cs_pre[it];                                 // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
         const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
         const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
         if (seg == 0) {
@@ -241,26 +273,26 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
           q[0] = Elem<T>::from_f32(y1);
           q[half] = Elem<T>::from_f32(y2);
         } else {
-          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+          const int bb = mg / a.T_nodes, node = mg % a.T_nodes;
           if (L < 0 || L + a.T_nodes > a.max_kv) {
             if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
             continue;
           }
-          T *kc = (T *)a.k_cache + (((size_t)bb * a.n_heads + head) * a.max_kv + (L + node)) * d_h + e;
-          kc[0] = Elem<T>::from_f32(y1);
-          kc[half] = Elem<T>::from_f32(y2);
+          T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+          kc[k_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(y1);
+          kc[k_tiled_index<T>(L + node, e + half, d_h)] = Elem<T>::from_f32(y2);
         }
       } else {
-        // values: dimension-major cache, consecutive threads -> consecutive tree rows
+        // values: consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
         const int j = rem >> 6, m = rem & 63, mg = m_base + m;
         if (mg >= a.M) continue;
-        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+        const int bb = mg / a.T_nodes, node = mg % a.T_nodes;
         if (L < 0 || L + a.T_nodes > a.max_kv) continue;
         #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
           const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
-          T *vc = (T *)a.v_cache + (((size_t)bb * a.n_heads + head) * d_h + e) * a.max_kv + (L + node);
-          *vc = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
+          T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+          vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
         }
       }
     }

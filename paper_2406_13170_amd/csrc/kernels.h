@@ -65,7 +65,7 @@ struct GemmArgs {
   void *act;                  // EPI_SWIGLU: [M, f] T
   // QKV
   void *q_out;                // [M, d] T
-  void *k_cache, *v_cache;    // this layer: [B, n_h, max_kv, d_h] and [B, n_h, d_h, max_kv] T
+  void *k_cache, *v_cache;    // this layer: [B, n_h] step-tiled caches of max_kv * d_h elements each
   const float2 *rope_cs;      // [M, d_h/2] (cos, sin) of each row's position
   const int32_t *kv_len;      // [B]
   int T_nodes, n_heads, d_h, max_kv;

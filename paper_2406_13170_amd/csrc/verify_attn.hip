@@ -4,7 +4,9 @@
 //
 // Everything runs on the matrix cores with operands taken straight from global memory:
 //   S^T[key, q] = K[key, :] . Q[q, :]      A = 16 keys x 64 bytes of K rows, B = 16 queries of Q
-//   O^T[d, q]  += V^T[d, keys] . P^T[keys, q]   A = 16 dims x 16 bytes of the dimension-major V cache
+//   O^T[d, q]  += V^T[d, keys] . P^T[keys, q]   A = 16 dims x the step's keys of V
+// Both caches are stored step-tiled (layout in the header of the C ABI): each A fragment is one
+// contiguous 1 KB piece, in the order the loop below asks for them.
 // The 16 keys fed to one S^T tile are chosen so that the accumulator a lane ends up with (4 keys of
 // its lane group per tile) is exactly the contraction-slot layout the second product expects from
 // its B operand, so P never leaves registers.  A wave owns whole key steps (32 keys in bf16, 16 in
@@ -51,8 +53,8 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
   const float scale = 1.4426950408889634f * rsqrtf((float)DH);
   const float NEG_INF = -__builtin_huge_valf();
 
-  const T *Kb = (const T *)a.k_cache + ((size_t)b * n_h + h) * (size_t)max_kv * DH;
-  const T *Vb = (const T *)a.v_cache + ((size_t)b * n_h + h) * (size_t)DH * max_kv;
+  const unsigned char *Kb = (const unsigned char *)((const T *)a.k_cache + ((size_t)b * n_h + h) * (size_t)max_kv * DH) + r16 * 64 + g * 16;
+  const unsigned char *Vb = (const unsigned char *)((const T *)a.v_cache + ((size_t)b * n_h + h) * (size_t)DH * max_kv) + r16 * 64 + g * 16;
   const int q_base = qg * NQ;
 
   // queries as B fragments: lane = query r16 of block qb, 16 bytes of dims per 64-byte piece
@@ -82,15 +84,15 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
   // One key step: loads of the step's K and V^T fragments, and the math on them.  The loop below keeps
   // the next step's fragments in flight while the current step is being processed (two register sets).
   auto load_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
-    const int key0 = st * KSTEP;
+    // fragment (t, ds) of the step holds keys st*KSTEP + (i>>2)*(4*NT) + t*4 + (i&3) at slot i = lane & 15, so
+    // that the S^T accumulators come out in the contraction-slot order of the second product
     #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const int key = key0 + (r16 >> 2) * (4 * NT) + t * 4 + (r16 & 3);
       #pragma unroll
-      for (int ds = 0; ds < DSTEPS; ++ds) Kf[t][ds] = ldg16(Kb + (size_t)key * DH + ds * (4 * PER) + g * PER);
+      for (int ds = 0; ds < DSTEPS; ++ds) Kf[t][ds] = ldg16(Kb + ((size_t)(st * NT + t) * DSTEPS + ds) * 1024);
     }
     #pragma unroll
-    for (int db = 0; db < DB; ++db) Vf[db] = ldg16(Vb + (size_t)(db * 16 + r16) * max_kv + key0 + g * PER);
+    for (int db = 0; db < DB; ++db) Vf[db] = ldg16(Vb + ((size_t)st * DB + db) * 1024);
   };
   auto math_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
     const int key0 = st * KSTEP;

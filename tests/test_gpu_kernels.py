@@ -73,10 +73,11 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None):
     v = si.normal(cfgx, seed, "va.v", (B_, n_h, L + T, d_h), 1.0)
     tdt = D.torch_dtype(cfg.dtype)
     # caches start as NaN everywhere outside the valid rows: nothing beyond L + T may leak in
-    kc = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
-    vc = torch.full((B_, n_h, d_h, max_kv), float("nan"), dtype=tdt, device=DEV)
-    kc[:, :, :L + T] = cfg_tensor_to_dev(k)
-    vc[:, :, :, :L + T] = D.values_to_dim_major(cfg_tensor_to_dev(v))
+    k_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
+    v_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
+    k_rows[:, :, :L + T] = cfg_tensor_to_dev(k)
+    v_rows[:, :, :L + T] = cfg_tensor_to_dev(v)
+    kc, vc = D.keys_to_tiled(k_rows), D.values_to_tiled(v_rows)
     out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
     kv_len = i32_to_dev(np.full(B_, L))
     ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), kc, vc, kv_len, out)

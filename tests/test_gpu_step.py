@@ -131,10 +131,11 @@ def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False,
     kcs = [si.normal(cfg, seed, f"tkv{li}.k", (Bsz, n_h, L, d_h), 1.0) for li in range(n_layers)]
     vcs = [si.normal(cfg, seed, f"tkv{li}.v", (Bsz, n_h, L, d_h), 1.0) for li in range(n_layers)]
     k_caches = torch.full((max(n_layers, 1), Bsz, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
-    v_caches = torch.full((max(n_layers, 1), Bsz, n_h, d_h, max_kv), float("nan"), dtype=tdt, device=DEV)
+    v_caches = torch.full((max(n_layers, 1), Bsz, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
     for li in range(n_layers):
         k_caches[li, :, :, :L] = cfg_tensor_to_dev(kcs[li])
-        v_caches[li, :, :, :, :L] = D.values_to_dim_major(cfg_tensor_to_dev(vcs[li]))
+        v_caches[li, :, :, :L] = cfg_tensor_to_dev(vcs[li])
+    k_caches, v_caches = D.keys_to_tiled(k_caches), D.values_to_tiled(v_caches)      # rows -> step-tiled storage
     tok = si.tokens(cfg, seed, "tree.tok", (Bsz, T))
     pos = np.stack([L + otree.depth for _ in range(Bsz)]).astype(np.int32)
     hidden = torch.full((Bsz, T, d), float("nan"), dtype=torch.float32, device=DEV)
@@ -188,8 +189,8 @@ def check_target(cfg, refs, got):
         say(f"  b={b} nodes with an oracle top-1/top-2 gap below tolerance: {undecided}/{T}")
         # tree K/V rows written by every layer at rows [L, L+T)
         for li, lay in enumerate(r["layers"]):
-            kc = np_of(got["k_caches"][li, b, :, L:L + T])                    # [n_h, T, d_h]
-            vc = np_of(got["v_caches"][li, b, :, :, L:L + T]).transpose(0, 2, 1)
+            kc = np_of(D.tiled_to_keys(got["k_caches"][li, b])[:, L:L + T])                    # [n_h, T, d_h]
+            vc = np_of(D.tiled_to_values(got["v_caches"][li, b])[:, L:L + T])
             assert_rows_close(kc, lay["k_new"], tol, f"layer {li} tree keys")
             assert_rows_close(vc, lay["v_new"], tol, f"layer {li} tree values")
 
@@ -224,7 +225,8 @@ def test_target_forward_vicuna7b_two_layers():
     _, _, got_rm, _ = run_target(si.V7B, 2, 64, (10,) * 4, 1024, tiled=False, oracle=False)
     assert np.array_equal(got["logits"], got_rm["logits"]) and np.array_equal(got["tgt"], got_rm["tgt"])
     assert np.array_equal(got["hidden"], got_rm["hidden"])
-    assert torch.equal(got["k_caches"][:, :, :, 1024:1088].view(torch.int16), got_rm["k_caches"][:, :, :, 1024:1088].view(torch.int16))
+    for name in ("k_caches", "v_caches"):       # tree rows 1024..1087 = the last two key steps of the tiled storage
+        assert torch.equal(got[name][:, :, :, 1024:1088].view(torch.int16), got_rm[name][:, :, :, 1024:1088].view(torch.int16))
 
 
 # ---------------------------------------------------------------------------- one whole step (A1-A10)
@@ -260,10 +262,11 @@ def test_full_step_matches_oracle(cfg):
     kcs = [si.normal(cfg, seed, f"tkv{li}.k", (1, n_h, L, d_h), 1.0) for li in range(nl)]
     vcs = [si.normal(cfg, seed, f"tkv{li}.v", (1, n_h, L, d_h), 1.0) for li in range(nl)]
     k_caches = torch.zeros((nl, 1, n_h, max_kv, d_h), dtype=tdt, device=DEV)
-    v_caches = torch.zeros((nl, 1, n_h, d_h, max_kv), dtype=tdt, device=DEV)
+    v_caches = torch.zeros((nl, 1, n_h, max_kv, d_h), dtype=tdt, device=DEV)
     for li in range(nl):
         k_caches[li, :, :, :L] = cfg_tensor_to_dev(kcs[li])
-        v_caches[li, :, :, :, :L] = D.values_to_dim_major(cfg_tensor_to_dev(vcs[li]))
+        v_caches[li, :, :, :L] = cfg_tensor_to_dev(vcs[li])
+    k_caches, v_caches = D.keys_to_tiled(k_caches), D.values_to_tiled(v_caches)
     i32 = lambda *shape: torch.full(shape, -9, dtype=torch.int32, device=DEV)
     topk_idx, topk_val = i32(1, K, cfg.topk), torch.zeros((1, K, cfg.topk), dtype=torch.float32, device=DEV)
     tree_tok, tree_pos, tgt = i32(1, T), i32(1, T), i32(1, T)
