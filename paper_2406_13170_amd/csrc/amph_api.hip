@@ -98,7 +98,7 @@ WsLayout make_layout(const amph_config &c) {
   // partial slabs of the split-K GEMMs (Wo, W_down: up to 8 slabs of [M, d]); amph_gemm may use the same area
   w.slabs_floats = std::max((size_t)8 * M * d, (size_t)8 * 1024 * 1024);
   w.slabs = take(w.slabs_floats * 4);
-  const size_t tilesV = (V + 63) / 64;
+  const size_t tilesV = (V + 31) / 32 + 1;      // upper bound on the LM head's tiles (at least two 16-row blocks each)
   w.amax_val = take(tilesV * M * 4); w.amax_idx = take(tilesV * M * 4);
   size_t vfl = 0;                                           // any tree size up to max_tree may be used
   for (int t = 1; t <= c.max_tree; ++t) vfl = std::max(vfl, verify_ws_floats(c.batch, t, c.n_heads, c.head_dim, c.max_kv, (int)esz));
@@ -211,7 +211,7 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   g.M = M; g.T_nodes = Tn; g.n_heads = n_h; g.d_h = d_h; g.max_kv = c.max_kv;
   g.rope_cs = rope_cs; g.kv_len = kv_len; g.split_k = 1;
   auto split_for = [&](int rows, int Kd) {
-    int s = gemm_auto_split(gemm_tiles_n(EPI_STORE, 1, rows, d_h) * mblocks, Kd, (int)sizeof(T));
+    int s = gemm_plan(EPI_STORE, rows, Kd, (int)sizeof(T), M, 0).split;
     while (s > 1 && (size_t)s * slab > ctx->ws.slabs_floats) s /= 2;
     return s;
   };
@@ -249,7 +249,8 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
   PROF_TRY(ctx, AMPH_K_T_LMHEAD, launch_gemm<T>(st, EPI_ARGMAX, a));
-  HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_tiles_n(EPI_ARGMAX, 1, V, d_h), M, tgt_argmax));
+  HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_plan(EPI_ARGMAX, V, d, (int)sizeof(T), M, 1).tiles, M,
+                                  tgt_argmax));
   return AMPH_OK;
 }
 
@@ -517,7 +518,7 @@ amph_status amph_tiled_bytes(const amph_ctx *ctx, int role, size_t *bytes) {
   if (!ctx || !bytes) return AMPH_EINVAL;
   int epi, n_seg, rows, Kd;
   if (!pack_shape(ctx->cfg, role, &epi, &n_seg, &rows, &Kd)) return AMPH_EINVAL;
-  *bytes = gemm_tiled_bytes(epi, n_seg, rows, Kd, ctx->cfg.head_dim, (int)ctx->esz);
+  *bytes = gemm_tiled_bytes(epi, rows, Kd, (int)ctx->esz);
   return AMPH_OK;
 }
 
@@ -586,8 +587,7 @@ amph_status amph_gemm(amph_ctx *ctx, const void *x, const void *W, float *y, int
   if (!x || !W || !y || !workspace || !aligned16(x) || !aligned16(W) || !aligned16(workspace))
     return fail(ctx, AMPH_EINVAL, "amph_gemm: null or misaligned argument");
   if (M < 1 || N < 1 || Kd < 1 || (Kd * ctx->esz) % 64) return fail(ctx, AMPH_ESHAPE, "amph_gemm: a row of x must be a multiple of 64 bytes");
-  const int tiles = (N + 63) / 64, mblocks = (M + 63) / 64;
-  if (split_k == 0) split_k = gemm_auto_split(tiles * mblocks, Kd, ctx->esz);
+  if (split_k == 0) split_k = gemm_plan(EPI_STORE, N, Kd, ctx->esz, M, 0).split;
   if (split_k != 1 && split_k != 2 && split_k != 4 && split_k != 8) return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k");
   if (split_k > 1 && (size_t)split_k * M * N > ctx->ws.slabs_floats)
     return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k * M * N exceeds the workspace's slab area");

@@ -2,27 +2,31 @@
 // activation rows (64 per block) against [N, Kd] weights that stream from HBM once, on the matrix
 // cores.
 //
-// A workgroup owns a 64 (tokens) x 16*NB (weight rows) output tile and a slice of the reduction axis,
+// The unit of work is a ROW BLOCK: 16 weight rows that one wave keeps as matrix-core A fragments and
+// whose outputs need nothing from any other block:
+//   * plain / LM head: rows 16b .. 16b+15;
+//   * q and k: 8 rows of a head and their 8 RoPE partners (i, i + d_h/2); v: 16 consecutive rows
+//     (blocks numbered q, then k, then v);
+//   * gate/up: rows 8b .. 8b+7 of W_gate and the same rows of W_up.
+// A workgroup owns nb consecutive blocks (a 64 x 16*nb output tile) and a slice of the reduction axis,
 // and its waves have two roles:
-//   * NB math waves, each keeping 16 weight rows.  Their A fragments are 16-byte loads straight from
-//     global memory (lane = row, 16 contiguous bytes of that row), requested one 512-byte chunk (8
-//     fragments) ahead; B fragments come from LDS.  They issue nothing else: no activation loads sit
-//     between their weight loads, so waiting for a chunk of weights never waits for anything younger.
-//   * NLW loader waves, which bring the activations of each chunk (64 rows x 512 bytes, L2 hits) into
-//     a padded, double-buffered LDS tile one chunk ahead.
-// One barrier per chunk joins the two.  The tile height is chosen per shape: every workgroup reads
-// the whole activation slice from L2, so that traffic is (64 / tile height) times the weight bytes and
-// measurably slows the weight stream; taller tiles cut it as far as the number of workgroups allows.
+//   * nb math waves, one block each.  Their A fragments are 16-byte loads straight from global memory,
+//     requested one 512-byte chunk (8 fragments) ahead; B fragments come from LDS.  They issue nothing
+//     else, so waiting for a chunk of weights never waits for anything younger.
+//   * 4 loader waves, which bring the activations of each chunk (64 rows x 512 bytes, L2 hits) into a
+//     padded, double-buffered LDS tile one chunk ahead.
+// One barrier per chunk joins the two.  nb (2..12) and the split of the reduction axis are chosen per
+// shape by gemm_plan: every workgroup reads the whole activation slice from L2, so that traffic is
+// (64 / tile height) times the weight bytes and measurably slows the weight stream; taller tiles cut
+// it as far as filling the 256 CUs in whole rounds allows.
 //
 // Weight layouts.  Row-major [N, Kd] works, but a matrix-core A fragment is 16 rows x 64 bytes, so
 // every wave load touches 16 half cache lines; the vector L1 handles such loads at about a quarter of
 // the rate of a contiguous 1 KB load and the weight stream then stalls on the CU side, not on HBM
 // (measured: 41 us against 33 us for the gate/up shape).  The tiled layout (k_pack_weights, run once
-// per matrix) stores, for every row block the kernel uses and every 64-byte step of the reduction
-// axis, the 16 x 64 bytes of that fragment as one contiguous 1 KB piece:
+// per matrix) stores every fragment as one contiguous 1 KB piece, block-major:
 //   tiled[(block * (Kd * sizeof(T) / 64) + step) * 1024 + r * 64 + byte]  =  W[row(block, r)][step * 64 + byte]
-// with blocks numbered tile-major in the kernel's own row mapping (so q/k blocks are 8 rows + their 8
-// RoPE partners, gate/up tiles are 3 gate blocks + 3 up blocks) and rows past N stored as zeros.
+// with rows past N stored as zeros.
 //
 // No workgroup ever communicates with another inside the kernel (a device-scope fence per workgroup
 // costs far more than the kernel on this chip): a split reduction axis writes one partial slab per
@@ -40,22 +44,11 @@ constexpr int GM_PITCH = GM_CHUNK_B + 16;       // LDS row pitch (bytes): rows s
 constexpr int GM_STEPS = GM_CHUNK_B / 64;       // matrix-core steps per chunk (64 bytes of k each)
 constexpr int GM_STAGE = GM_BM * GM_PITCH;      // one activation stage
 constexpr int GM_LDS_BYTES = 2 * GM_STAGE;
-
-// row blocks (16 weight rows = one math wave) and loader waves per workgroup, by epilogue
-template <int EPI> struct GemmShape;
-template <> struct GemmShape<EPI_STORE> { static constexpr int NB = 4, NLW = 4; };
-template <> struct GemmShape<EPI_QKV_ROPE> { static constexpr int NB = 3, NLW = 2; };   // 768 row blocks -> 256 tiles at d = 4096
-template <> struct GemmShape<EPI_SWIGLU> { static constexpr int NB = 6, NLW = 2; };     // 48 gate rows + 48 up rows
-template <> struct GemmShape<EPI_ARGMAX> { static constexpr int NB = 8, NLW = 4; };
-
-static int gemm_nb(int epi) {
-  switch (epi) {
-    case EPI_QKV_ROPE: return GemmShape<EPI_QKV_ROPE>::NB;
-    case EPI_SWIGLU: return GemmShape<EPI_SWIGLU>::NB;
-    case EPI_ARGMAX: return GemmShape<EPI_ARGMAX>::NB;
-    default: return GemmShape<EPI_STORE>::NB;
-  }
-}
+constexpr int GM_NLW = 4;                       // loader waves
+constexpr int GM_XROWS = GM_BM / GM_NLW, GM_XL = GM_XROWS / 2;   // activation rows / 16-byte loads per loader lane per chunk
+constexpr int GM_MIN_NB = 2, GM_MAX_NB = 12;    // math waves (= row blocks) per workgroup
+static_assert(GM_LDS_BYTES >= GM_BM * (16 * GM_MAX_NB + 4) * 4, "output tile must fit in the staging buffers");
+static_assert(64 * (GM_MAX_NB + GM_NLW) <= 1024, "workgroup size");
 
 // Element index of (row, dim) in the step-tiled K and V caches of one head (layout: header of the C ABI).
 template <typename T> __device__ __forceinline__ size_t k_tiled_index(int row, int c, int d_h) {
@@ -68,44 +61,42 @@ template <typename T> __device__ __forceinline__ size_t v_tiled_index(int row, i
   return ((size_t)(row / KSTEP) * (d_h / 16) + c / 16) * (16 * PIECE) + (c % 16) * PIECE + row % KSTEP;
 }
 
-// weight row (within its matrix) and matrix index of tile row r
+// number of row blocks of a GEMM
+__host__ __device__ inline int gemm_blocks(int epi, int seg_rows) {
+  if (epi == EPI_QKV_ROPE) return 3 * (seg_rows / 16);
+  if (epi == EPI_SWIGLU) return (seg_rows + 7) / 8;
+  return (seg_rows + 15) / 16;
+}
+
+// weight row (within its matrix) and matrix index of row r16 of block b
 struct RowMap { int seg; int n; bool valid; };
 
-template <int EPI, int BN>
-__device__ __forceinline__ RowMap map_row(const GemmArgs &a, int tile, int r) {
+template <int EPI>
+__device__ __forceinline__ RowMap map_block(const GemmArgs &a, int b, int r16) {
   RowMap o;
   if (EPI == EPI_QKV_ROPE) {
-    // The unit is a row block (one math wave): for q and k, 8 rows of a head and their 8 RoPE partners
-    // (i, i + d_h/2), so that every block rotates on its own and a tile may be any run of blocks; for v,
-    // 16 consecutive rows.  Blocks are numbered q, then k, then v.
     const int d = a.n_heads * a.d_h, bps = d / 16, bph = a.d_h / 16;
-    const int b = tile * (BN / 16) + r / 16, r16 = r % 16;
-    o.valid = b < 3 * bps;
-    o.seg = o.valid ? b / bps : 0;
-    const int bl = o.valid ? b % bps : 0;
+    o.valid = true;
+    o.seg = b / bps;
+    const int bl = b % bps;
     if (o.seg < 2) o.n = (bl / bph) * a.d_h + (bl % bph) * 8 + (r16 & 7) + ((r16 >= 8) ? a.d_h / 2 : 0);
     else o.n = bl * 16 + r16;
   } else if (EPI == EPI_SWIGLU) {
-    constexpr int H = BN / 2;
-    o.seg = (r >= H) ? 1 : 0;
-    o.n = tile * H + (r >= H ? r - H : r);
+    o.seg = (r16 >= 8) ? 1 : 0;
+    o.n = b * 8 + (r16 & 7);
     o.valid = o.n < a.seg_rows;
   } else {
     o.seg = 0;
-    o.n = tile * BN + r;
+    o.n = b * 16 + r16;
     o.valid = o.n < a.seg_rows;
   }
   return o;
 }
 
 template <typename T, int EPI, bool TILED>
-__global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) void k_gemm_skinny(const GemmArgs a, int tiles) {
-  constexpr int NB = GemmShape<EPI>::NB, NLW = GemmShape<EPI>::NLW, BN = 16 * NB, NT = 64 * (NB + NLW);
-  constexpr int CT_PITCH = BN + 4;                       // floats
-  constexpr int XROWS = GM_BM / NLW, XL = XROWS / 2;     // activation rows / 16-byte loads per loader lane per chunk
-  static_assert(GM_LDS_BYTES >= GM_BM * CT_PITCH * 4, "output tile must fit in the staging buffers");
-  static_assert(GM_BM % NLW == 0 && XROWS % 2 == 0, "loader waves split the 64 activation rows evenly");
+__global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const GemmArgs a, int tiles) {
   __shared__ __align__(16) unsigned char lds[GM_LDS_BYTES];
+  const int nb = a.nb, BN = 16 * nb, NT = 64 * (nb + GM_NLW), CT_PITCH = BN + 4;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
   const int S = a.split_k;
   const int tile = blockIdx.x / S, split = blockIdx.x % S, mblock = blockIdx.y;
@@ -114,6 +105,7 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   const int total_steps = row_bytes / 64;
   const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
   const int nch = (s1 - s0 + GM_STEPS - 1) / GM_STEPS;
+  const int nblk = gemm_blocks(EPI, a.seg_rows);
   // Both roles run the same number of iterations (a multiple of two, the depth of every ring) with
   // no conditional inside: chunks past the slice load clamped addresses and stage zeros, so the
   // compiler can count outstanding loads exactly instead of draining them at every join.
@@ -123,33 +115,17 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   #pragma unroll
   for (int mb = 0; mb < 4; ++mb) acc[mb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // RoPE epilogue: the table entries and cache lengths this thread will need are requested now, so that
-  // they arrive during the main loop instead of costing a memory round trip per epilogue iteration.
-  constexpr int QK_ITEMS = (NB * 512 + NT - 1) / NT;
-  float2 cs_pre[EPI == EPI_QKV_ROPE ? QK_ITEMS : 1];
-  int len_pre[EPI == EPI_QKV_ROPE ? QK_ITEMS : 1];
-  if (EPI == EPI_QKV_ROPE) {
-    const int d_h = a.d_h, bps = a.n_heads * d_h / 16, bph = d_h / 16, half = d_h / 2;
-    #pragma unroll
-    for (int it = 0; it < QK_ITEMS; ++it) {
-      const int idx = tid + it * NT, w = min(idx >> 9, NB - 1), rem = idx & 511;
-      const int b = min(tile * NB + w, 3 * bps - 1), seg = b / bps, bl = b % bps;
-      const int m = (seg < 2) ? (rem >> 3) : (rem & 63), mg = min(m_base + m, a.M - 1);
-      const int e = (seg < 2) ? (bl % bph) * 8 + (rem & 7) : 0;
-      cs_pre[it] = a.rope_cs[(size_t)mg * half + e];
-      len_pre[it] = a.kv_len[mg / a.T_nodes];
-    }
-  }
-
-  if (wave < NB) {
+  if (wave < nb) {
     // ------------------------------------------------------------------------------- math wave
+    // A block past the end (last tile only) re-reads the last block; its results are never stored.
+    const int blk = min(tile * nb + wave, nblk - 1);
     const unsigned char *wrow;
     if (TILED) {
       // the block's fragments lie one after another: step st is the 1 KB at st * 1024, this lane's 16 bytes at
       // (r16 * 64 + g * 16) inside it
-      wrow = (const unsigned char *)a.wt + (size_t)(tile * NB + wave) * total_steps * 1024 + r16 * 64 + g * 16;
+      wrow = (const unsigned char *)a.wt + (size_t)blk * total_steps * 1024 + r16 * 64 + g * 16;
     } else {
-      const RowMap rm = map_row<EPI, BN>(a, tile, wave * 16 + r16);
+      const RowMap rm = map_block<EPI>(a, blk, r16);
       const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
       wrow = (const unsigned char *)wm + (size_t)(rm.valid ? rm.n : 0) * row_bytes + g * 16;
     }
@@ -187,23 +163,23 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
     // 32 lanes cover one 512-byte row piece, a wave instruction two rows; chunk c+1 is written to its
     // stage while the math waves work on chunk c, and chunk c+2 is already on its way from L2.
     const unsigned char *xg = (const unsigned char *)a.x;
-    const int x_row0 = (wave - NB) * XROWS + (lane >> 5), x_col = (lane & 31) * 16;
-    uint4 xr[2][XL];
-    auto load_x = [&](int c, uint4 (&xf)[XL]) {
+    const int x_row0 = (wave - nb) * GM_XROWS + (lane >> 5), x_col = (lane & 31) * 16;
+    uint4 xr[2][GM_XL];
+    auto load_x = [&](int c, uint4 (&xf)[GM_XL]) {
       const int byte = (s0 + c * GM_STEPS) * 64 + x_col;
       const bool in_k = byte < s1 * 64;
       #pragma unroll
-      for (int j = 0; j < XL; ++j) {
+      for (int j = 0; j < GM_XL; ++j) {
         const int mg = m_base + x_row0 + 2 * j;
         const bool ok = in_k && mg < a.M;                 // out-of-range pieces read the tensor's first bytes ...
         xf[j] = ldg16(xg + (ok ? (size_t)mg * row_bytes + byte : (size_t)0));
       }
     };
-    auto store_x = [&](int stage, int c, const uint4 (&xf)[XL]) {
+    auto store_x = [&](int stage, int c, const uint4 (&xf)[GM_XL]) {
       unsigned char *buf = lds + stage * GM_STAGE;
       const bool in_k = (s0 + c * GM_STEPS) * 64 + x_col < s1 * 64;
       #pragma unroll
-      for (int j = 0; j < XL; ++j) {
+      for (int j = 0; j < GM_XL; ++j) {
         const bool ok = in_k && (m_base + x_row0 + 2 * j) < a.M;   // ... and are replaced by zeros here
         *reinterpret_cast<uint4 *>(buf + (x_row0 + 2 * j) * GM_PITCH + x_col) = ok ? xf[j] : make_uint4(0u, 0u, 0u, 0u);
       }
@@ -226,7 +202,7 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
   // The last barrier of the loop has passed, so nobody reads the stages any more; the one write still
   // outstanding (the loaders' zero chunk nch2) went to stage nch2 % 2 before that barrier.
   float *Ct = reinterpret_cast<float *>(lds);
-  if (wave < NB) {
+  if (wave < nb) {
     #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
       *reinterpret_cast<f32x4 *>(Ct + (mb * 16 + r16) * CT_PITCH + wave * 16 + g * 4) = acc[mb];
@@ -243,29 +219,27 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
       if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
     }
   } else if (EPI == EPI_SWIGLU) {
-    constexpr int H = BN / 2;
-    const int f = a.seg_rows;
+    // block w of the tile: columns 0..7 = gate rows, 8..15 = the same rows of up
+    const int f = a.seg_rows, H = 8 * nb;
     T *act = (T *)a.act;
     for (int idx = tid; idx < GM_BM * H; idx += NT) {
-      const int m = idx / H, r = idx % H, mg = m_base + m, j = tile * H + r;
+      const int m = idx / H, jj = idx % H, w = jj >> 3, j8 = jj & 7, mg = m_base + m, j = tile * H + jj;
       if (mg < a.M && j < f)
-        act[(size_t)mg * f + j] = Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + r]) * Ct[m * CT_PITCH + r + H]);
+        act[(size_t)mg * f + j] =
+            Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + w * 16 + j8]) * Ct[m * CT_PITCH + w * 16 + 8 + j8]);
     }
   } else if (EPI == EPI_QKV_ROPE) {
     // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
     const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
-    #pragma unroll
-    for (int it = 0; it < QK_ITEMS; ++it) {
-      const int idx = tid + it * NT;
-      if (idx >= NB * 512) continue;
-      const int w = idx >> 9, rem = idx & 511, b = tile * NB + w;
-      if (b >= 3 * bps) continue;
-      const int seg = b / bps, bl = b % bps, L = len_pre[it];
+    for (int idx = tid; idx < nb * 512; idx += NT) {
+      const int w = idx >> 9, rem = idx & 511, b = tile * nb + w;
+      if (b >= nblk) continue;
+      const int seg = b / bps, bl = b % bps;
       if (seg < 2) {
         const int m = rem >> 3, j = rem & 7, mg = m_base + m;
         if (mg >= a.M) continue;
         const int head = bl / bph, e = (bl % bph) * 8 + j;
-        const float2 cs = cs_pre[it];                                 // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
+        const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
         const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
         const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
         if (seg == 0) {
@@ -273,7 +247,7 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
           q[0] = Elem<T>::from_f32(y1);
           q[half] = Elem<T>::from_f32(y2);
         } else {
-          const int bb = mg / a.T_nodes, node = mg % a.T_nodes;
+          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
           if (L < 0 || L + a.T_nodes > a.max_kv) {
             if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
             continue;
@@ -286,7 +260,7 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
         // values: consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
         const int j = rem >> 6, m = rem & 63, mg = m_base + m;
         if (mg >= a.M) continue;
-        const int bb = mg / a.T_nodes, node = mg % a.T_nodes;
+        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
         if (L < 0 || L + a.T_nodes > a.max_kv) continue;
         #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
@@ -330,17 +304,15 @@ __global__ __launch_bounds__(64 * (GemmShape<EPI>::NB + GemmShape<EPI>::NLW)) vo
 
 // Row-major -> tiled (see the layout above).  One thread per 16-byte piece of the tiled buffer.
 template <typename T, int EPI>
-__global__ __launch_bounds__(256) void k_pack_weights(const GemmArgs a, int tiles, unsigned char *dst) {
-  constexpr int NB = GemmShape<EPI>::NB, BN = 16 * NB;
+__global__ __launch_bounds__(256) void k_pack_weights(const GemmArgs a, unsigned char *dst) {
   const int total_steps = a.Kd * (int)sizeof(T) / 64;
-  const size_t pieces = (size_t)tiles * NB * total_steps * 64;      // 64 pieces of 16 bytes per 1 KB fragment
+  const size_t pieces = (size_t)gemm_blocks(EPI, a.seg_rows) * total_steps * 64;   // 64 pieces of 16 bytes per fragment
   for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pieces; p += (size_t)gridDim.x * 256) {
     const int g = (int)(p & 3), r16 = (int)((p >> 2) & 15);
     const size_t frag = p >> 6;
     const int st = (int)(frag % total_steps);
-    const size_t blk = frag / total_steps;
-    const int tile = (int)(blk / NB), wv = (int)(blk % NB);
-    const RowMap rm = map_row<EPI, BN>(a, tile, wv * 16 + r16);
+    const int blk = (int)(frag / total_steps);
+    const RowMap rm = map_block<EPI>(a, blk, r16);
     uint4 v = make_uint4(0u, 0u, 0u, 0u);
     if (rm.valid) {
       const void *wm = (rm.seg == 0) ? a.w0 : (rm.seg == 1) ? a.w1 : a.w2;
@@ -350,23 +322,22 @@ __global__ __launch_bounds__(256) void k_pack_weights(const GemmArgs a, int tile
   }
 }
 
-size_t gemm_tiled_bytes(int epi, int n_seg, int seg_rows, int Kd, int d_h, int elem_bytes) {
-  return (size_t)gemm_tiles_n(epi, n_seg, seg_rows, d_h) * gemm_nb(epi) * 16 * (size_t)Kd * elem_bytes;
+size_t gemm_tiled_bytes(int epi, int seg_rows, int Kd, int elem_bytes) {
+  return (size_t)gemm_blocks(epi, seg_rows) * 16 * (size_t)Kd * elem_bytes;
 }
 
 template <typename T>
 hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst) {
   if (a.Kd < 1 || (a.Kd * (int)sizeof(T)) % 64) return hipErrorInvalidValue;
-  if (epi == EPI_QKV_ROPE && a.d_h % 16) return hipErrorInvalidValue;
-  const int tiles = gemm_tiles_n(epi, a.n_seg, a.seg_rows, a.d_h);
-  const size_t pieces = gemm_tiled_bytes(epi, a.n_seg, a.seg_rows, a.Kd, a.d_h, (int)sizeof(T)) / 16;
+  if (epi == EPI_QKV_ROPE && (a.d_h % 16 || a.seg_rows != a.n_heads * a.d_h)) return hipErrorInvalidValue;
+  const size_t pieces = gemm_tiled_bytes(epi, a.seg_rows, a.Kd, (int)sizeof(T)) / 16;
   const int blocks = (int)std::min<size_t>((pieces + 255) / 256, 65536);
   unsigned char *d8 = (unsigned char *)dst;
   switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((k_pack_weights<T, EPI_STORE>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
-    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_pack_weights<T, EPI_QKV_ROPE>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((k_pack_weights<T, EPI_SWIGLU>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
-    case EPI_ARGMAX: hipLaunchKernelGGL((k_pack_weights<T, EPI_ARGMAX>), dim3(blocks), dim3(256), 0, st, a, tiles, d8); break;
+    case EPI_STORE: hipLaunchKernelGGL((k_pack_weights<T, EPI_STORE>), dim3(blocks), dim3(256), 0, st, a, d8); break;
+    case EPI_QKV_ROPE: hipLaunchKernelGGL((k_pack_weights<T, EPI_QKV_ROPE>), dim3(blocks), dim3(256), 0, st, a, d8); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((k_pack_weights<T, EPI_SWIGLU>), dim3(blocks), dim3(256), 0, st, a, d8); break;
+    case EPI_ARGMAX: hipLaunchKernelGGL((k_pack_weights<T, EPI_ARGMAX>), dim3(blocks), dim3(256), 0, st, a, d8); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -433,51 +404,59 @@ hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32
   return hipGetLastError();
 }
 
-int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h) {
-  (void)d_h; (void)n_seg;
-  const int bn = 16 * gemm_nb(epi);
-  if (epi == EPI_QKV_ROPE) return (3 * (seg_rows / 16) + bn / 16 - 1) / (bn / 16);
-  if (epi == EPI_SWIGLU) return (seg_rows + bn / 2 - 1) / (bn / 2);
-  return (seg_rows + bn - 1) / bn;
-}
-
-// Split the reduction axis only where the output alone gives too few workgroups for the chip.
-int gemm_auto_split(int tiles, int Kd, int elem_bytes) {
+// Tile height and reduction split for one GEMM.  Model, in units of one weight fragment: a workgroup's
+// time is its steps times (nb fragments + 2 for its share of the activation chunk); the kernel's time
+// is that times the number of rounds the grid needs on 256 CUs; every split beyond the first costs the
+// write and the later read of one more float32 slab.  The two constants are fitted to measurements of
+// the 7B shapes (Wo: 4 blocks x 4 splits beats 2 x 2 and 8 x 8; down: 4 x 4 beats 8 x 8).
+GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req) {
+  GemmPlan best{};
+  const int blocks = gemm_blocks(epi, seg_rows);
   const int total_steps = Kd * elem_bytes / 64;
-  int s = 1;
-  while (s < 8 && tiles * s < 192 && total_steps / (s * 2) >= 16) s *= 2;
-  return s;
+  const int mblocks = (M + GM_BM - 1) / GM_BM;
+  const bool fused = epi != EPI_STORE;
+  const double slab_units = fused ? 0.0 : (double)M * seg_rows * 1.0e-4 + 2.0;   // per extra split
+  double best_cost = 1e300;
+  for (int s = 1; s <= 8; s *= 2) {
+    if (split_req > 0 && s != split_req) continue;
+    if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GM_STEPS))) continue;
+    for (int nb = GM_MIN_NB; nb <= GM_MAX_NB; ++nb) {
+      if (nb > std::max(blocks, GM_MIN_NB)) break;
+      const int tiles = (blocks + nb - 1) / nb;
+      const long wgs = (long)tiles * s * mblocks;
+      const long rounds = (wgs + 255) / 256;
+      const double cost = (double)rounds * ((total_steps + s - 1) / s) * (nb + 2) + slab_units * (s - 1);
+      if (cost <= best_cost) { best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles; }
+    }
+  }
+  best.blocks = blocks;
+  return best;
 }
 
 template <typename T>
-hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a) {
+hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in) {
+  GemmArgs a = a_in;
   if (a.M < 1 || a.Kd < 1 || (a.Kd * (int)sizeof(T)) % 64) return hipErrorInvalidValue;
   if (a.split_k != 1 && a.split_k != 2 && a.split_k != 4 && a.split_k != 8) return hipErrorInvalidValue;
   if (epi != EPI_STORE && a.split_k != 1) return hipErrorInvalidValue;     // fused epilogues need complete sums
-  const int tiles = gemm_tiles_n(epi, a.n_seg, a.seg_rows, a.d_h);
+  if (epi == EPI_QKV_ROPE && (a.d_h % 16 || a.seg_rows != a.n_heads * a.d_h || !a.rope_cs)) return hipErrorInvalidValue;
+  const GemmPlan pl = gemm_plan(epi, a.seg_rows, a.Kd, (int)sizeof(T), a.M, a.split_k);
+  a.nb = pl.nb;
+  const int tiles = pl.tiles;
   const int mblocks = (a.M + GM_BM - 1) / GM_BM;
   if (mblocks > 65535) return hipErrorInvalidValue;
-  if (epi == EPI_QKV_ROPE && (a.d_h % 16 || !a.rope_cs)) return hipErrorInvalidValue;
-  const dim3 grid(tiles * a.split_k, mblocks);
+  const dim3 grid(tiles * a.split_k, mblocks), block(64 * (a.nb + GM_NLW));
+  #define GM_LAUNCH(E)                                                                        \
+    if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, E, true>), grid, block, 0, st, a, tiles);  \
+    else hipLaunchKernelGGL((k_gemm_skinny<T, E, false>), grid, block, 0, st, a, tiles)
   switch (epi) {
-    case EPI_STORE:
-      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE, true>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles);
-      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_STORE, false>), grid, dim3(64 * (GemmShape<EPI_STORE>::NB + GemmShape<EPI_STORE>::NLW)), 0, st, a, tiles);
-      break;
-    case EPI_QKV_ROPE:
-      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE, true>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles);
-      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_QKV_ROPE, false>), grid, dim3(64 * (GemmShape<EPI_QKV_ROPE>::NB + GemmShape<EPI_QKV_ROPE>::NLW)), 0, st, a, tiles);
-      break;
-    case EPI_SWIGLU:
-      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU, true>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles);
-      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_SWIGLU, false>), grid, dim3(64 * (GemmShape<EPI_SWIGLU>::NB + GemmShape<EPI_SWIGLU>::NLW)), 0, st, a, tiles);
-      break;
-    case EPI_ARGMAX:
-      if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX, true>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles);
-      else hipLaunchKernelGGL((k_gemm_skinny<T, EPI_ARGMAX, false>), grid, dim3(64 * (GemmShape<EPI_ARGMAX>::NB + GemmShape<EPI_ARGMAX>::NLW)), 0, st, a, tiles);
-      break;
+    case EPI_STORE: GM_LAUNCH(EPI_STORE); break;
+    case EPI_QKV_ROPE: GM_LAUNCH(EPI_QKV_ROPE); break;
+    case EPI_SWIGLU: GM_LAUNCH(EPI_SWIGLU); break;
+    case EPI_ARGMAX: GM_LAUNCH(EPI_ARGMAX); break;
     default: return hipErrorInvalidValue;
   }
+  #undef GM_LAUNCH
   return hipGetLastError();
 }
 template hipError_t launch_gemm<float>(hipStream_t, int, const GemmArgs &);

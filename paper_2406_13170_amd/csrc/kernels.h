@@ -59,6 +59,7 @@ struct GemmArgs {
   const void *x;              // [M, Kd] T
   int M;
   int split_k;                // 1, 2, 4, 8 (fused epilogues: 1)
+  int nb;                     // row blocks per workgroup: filled in by launch_gemm from gemm_plan
   // epilogue operands
   float *out;                 // EPI_STORE: [split_k][M, seg_rows] float32 partial slabs
   float *logits;              // EPI_ARGMAX: optional [M, seg_rows]
@@ -74,11 +75,14 @@ struct GemmArgs {
   int32_t *amax_idx;          // [tiles_n][M]
   uint32_t *dev_status;
 };
-int gemm_tiles_n(int epi, int n_seg, int seg_rows, int d_h);
-int gemm_auto_split(int tiles, int Kd, int elem_bytes);
+// Tile height (row blocks per workgroup), reduction split and resulting tile count of one GEMM.  split_req: 0 lets
+// the plan choose (fused epilogues always 1), else the caller's split.  The same call must be used to size
+// whatever depends on the plan (partial slabs: split; per-tile argmax candidates: tiles).
+struct GemmPlan { int nb, split, tiles, blocks; };
+GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req);
 template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a);
-// bytes of the tiled copy of the matrices of one GEMM, and the kernel that writes it (w0..w2, n_seg, seg_rows, Kd, n_heads, d_h of a)
-size_t gemm_tiled_bytes(int epi, int n_seg, int seg_rows, int Kd, int d_h, int elem_bytes);
+// bytes of the tiled copy of the matrices of one GEMM, and the kernel that writes it (w0..w2, seg_rows, Kd, n_heads, d_h of a)
+size_t gemm_tiled_bytes(int epi, int seg_rows, int Kd, int elem_bytes);
 template <typename T> hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst);
 hipError_t launch_rope_table(hipStream_t st, const int32_t *pos, int M, int d_h, float theta, float2 *cs);
 hipError_t launch_sum_slabs(hipStream_t st, const float *slabs, int S, size_t n, float *out);
