@@ -94,6 +94,13 @@ def test_draft_vicuna7b_shape():
     check_draft(cfgx, outs, got)
 
 
+def test_draft_vicuna13b_shape():
+    """Configuration 4's draft module (d 5120, 40 x 128 heads, FFN 13824, SAL cache 2048)."""
+    say("draft vicuna13b")
+    cfgx, ctx, outs, got = run_draft(si.V13B)
+    check_draft(cfgx, outs, got)
+
+
 def test_draft_is_deterministic_and_flags_overflow():
     say("draft determinism / overflow")
     cfg = si.TINY
@@ -227,6 +234,14 @@ def test_target_forward_vicuna7b_two_layers():
     assert np.array_equal(got["hidden"], got_rm["hidden"])
     for name in ("k_caches", "v_caches"):       # tree rows 1024..1087 = the last two key steps of the tiled storage
         assert torch.equal(got[name][:, :, :, 1024:1088].view(torch.int16), got_rm[name][:, :, :, 1024:1088].view(torch.int16))
+
+
+def test_target_forward_vicuna13b_two_layers():
+    """Configuration 4 at full width (d 5120, FFN 13824, 40 x 128 heads, L 2048, T 64), two layers, tiled
+    weights: the per-layer launch configuration (tile heights 4 / 5 / 7 / 5 blocks) differs from 7B's."""
+    say("target_forward vicuna13b 2 layers (tiled weights)")
+    cfgx, refs, got, _ = run_target(si.V13B, 2, 64, (10,) * 4, 2048, tiled=True)
+    check_target(cfgx, refs, got)
 
 
 # ---------------------------------------------------------------------------- one whole step (A1-A10)
