@@ -117,7 +117,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="vicuna7b", choices=["vicuna7b", "vicuna13b", "tiny", "mini_bf16"])
+    ap.add_argument("--workload", default="vicuna7b", choices=["vicuna7b", "vicuna13b", "vicuna33b", "tiny", "mini_bf16"])
     ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")

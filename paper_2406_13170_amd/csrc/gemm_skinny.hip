@@ -99,7 +99,13 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
   const int nb = a.nb, BN = 16 * nb, NT = 64 * (nb + GM_NLW), CT_PITCH = BN + 4;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
   const int S = a.split_k;
-  const int tile = blockIdx.x / S, split = blockIdx.x % S, mblock = blockIdx.y;
+  // Workgroup index -> (unit = tile and split, block of 64 activation rows).  With more than one row block
+  // the workgroups that stream the SAME weights get indices 8 apart: they are dispatched together and
+  // land on the same XCD, so the weights come from HBM once and from that XCD's L2 for the others.
+  const int mblocks = (a.M + GM_BM - 1) / GM_BM;
+  const int id = blockIdx.x, unit = (id / 8 / mblocks) * 8 + (id & 7), mblock = (id / 8) % mblocks;
+  if (unit >= tiles * S) return;                          // padding of the last group of 8 units (whole workgroup)
+  const int tile = unit / S, split = unit % S;
   const int m_base = mblock * GM_BM;
   const int row_bytes = a.Kd * (int)sizeof(T);
   const int total_steps = row_bytes / 64;
@@ -444,8 +450,9 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in) {
   a.nb = pl.nb;
   const int tiles = pl.tiles;
   const int mblocks = (a.M + GM_BM - 1) / GM_BM;
-  if (mblocks > 65535) return hipErrorInvalidValue;
-  const dim3 grid(tiles * a.split_k, mblocks), block(64 * (a.nb + GM_NLW));
+  const long long wgs = (long long)((tiles * a.split_k + 7) / 8) * mblocks * 8;     // see the index mapping in the kernel
+  if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)wgs), block(64 * (a.nb + GM_NLW));
   #define GM_LAUNCH(E)                                                                        \
     if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, E, true>), grid, block, 0, st, a, tiles);  \
     else hipLaunchKernelGGL((k_gemm_skinny<T, E, false>), grid, block, 0, st, a, tiles)

@@ -9,6 +9,7 @@
 // cache write, residual add, SwiGLU, head MLP) is applied to them directly.  No matrix cores: with
 // M <= 8 the contraction is a stream of dot products bound by HBM.
 #include "kernels.h"
+#include <algorithm>
 
 namespace amph {
 
@@ -462,19 +463,33 @@ template <typename T, typename Kern> static hipError_t gv_set_smem(Kern kern, si
   return hipSuccess;
 }
 
+// Rows per launch: the activation rows of a launch sit in LDS as float32, so a call with more rows than
+// fit (wide models with batch > 1) is served in several launches over row ranges; every launch then
+// streams the weights again.  Returns 0 if not even one row fits.
+static inline int gv_rows_per_launch(int M, size_t bytes_per_row, size_t extra) {
+  static const int sizes[] = {8, 5, 4, 2, 1};       // the instantiated row counts
+  for (int mm : sizes)
+    if (mm * bytes_per_row + extra <= GV_MAX_SMEM) return mm < M ? mm : M;
+  return 0;
+}
+
 template <typename T>
 hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const void *embed, const int32_t *tok,
                             int vocab, int d, int M, float *out, uint32_t *dev_status) {
-  if (M < 1 || M > 8) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  GV_DISPATCH_M(M, {
-    const size_t sm = gv_xs_bytes<T>(MM, 2 * d);
-    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
-    e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W, u,
-                       (const T *)embed, tok, vocab, d, M, out, dev_status);
-  });
+  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, 2 * d), 0);
+  if (mc < 1) return hipErrorInvalidValue;
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = gv_xs_bytes<T>(MM, 2 * d);
+      e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W,
+                         u + (size_t)m0 * d, (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status);
+    });
+  }
   return hipGetLastError();
 }
 
@@ -482,17 +497,22 @@ template <typename T>
 hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int n_heads, int d_h, int M,
                           float eps, float theta, const int32_t *sal_len, int max_kv, void *kv_stage, float *qbuf,
                           uint32_t *dev_status) {
-  if (M < 1 || M > 8 || d % 4 || d_h % 4) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  GV_DISPATCH_M(M, {
-    const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
-    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
-    e = gv_set_smem<T>(k_sal_qkv<T, MM>, sm);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_sal_qkv<T, MM>), dim3(gv_grid(3 * d / 4)), dim3(GV_THREADS), sm, st, (const T *)lw.wq,
-                       (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1, x, d, n_heads, d_h, M, eps, theta, sal_len,
-                       max_kv, (T *)kv_stage, qbuf, dev_status);
-  });
+  if (M < 1 || M > 8 || d % 8 || d_h % 4) return hipErrorInvalidValue;
+  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 16);
+  if (mc < 1) return hipErrorInvalidValue;
+  const size_t kv_row = (size_t)2 * n_heads * max_kv * d_h;           // cache elements of one batch element
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
+      e = gv_set_smem<T>(k_sal_qkv<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_sal_qkv<T, MM>), dim3(gv_grid(3 * d / 4)), dim3(GV_THREADS), sm, st, (const T *)lw.wq,
+                         (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1, x + (size_t)m0 * d, d, n_heads, d_h, m, eps,
+                         theta, sal_len + m0, max_kv, (T *)kv_stage + (size_t)m0 * kv_row, qbuf + (size_t)m0 * d, dev_status);
+    });
+  }
   return hipGetLastError();
 }
 
@@ -500,15 +520,21 @@ template <typename T>
 hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const void *w2, int n_seg, int seg_rows, int Kd,
                          const float *x, int ldx, int M, const float *res, float *o0, float *o1, float *o2, int ldo) {
   if (M < 1 || M > 8 || Kd % 8) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  GV_DISPATCH_M(M, {
-    const size_t sm = gv_xs_bytes<T>(MM, Kd);
-    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
-    e = gv_set_smem<T>(k_linear<T, MM>, sm);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_linear<T, MM>), dim3(gv_grid(n_seg * ((seg_rows + 3) / 4))), dim3(GV_THREADS), sm, st,
-                       (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows, Kd, x, ldx, M, res, o0, o1, o2, ldo);
-  });
+  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd), 0);
+  if (mc < 1) return hipErrorInvalidValue;
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    const size_t oo = (size_t)m0 * ldo;
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = gv_xs_bytes<T>(MM, Kd);
+      e = gv_set_smem<T>(k_linear<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_linear<T, MM>), dim3(gv_grid(n_seg * ((seg_rows + 3) / 4))), dim3(GV_THREADS), sm, st,
+                         (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m,
+                         res ? res + oo : nullptr, o0 + oo, o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
+    });
+  }
   return hipGetLastError();
 }
 
@@ -516,15 +542,19 @@ template <typename T>
 hipError_t launch_gate_up(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int f, int M, float eps,
                           float *act) {
   if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  GV_DISPATCH_M(M, {
-    const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
-    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
-    e = gv_set_smem<T>(k_gate_up<T, MM>, sm);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_gate_up<T, MM>), dim3(gv_grid((f + 1) / 2)), dim3(GV_THREADS), sm, st, (const T *)lw.w_gate,
-                       (const T *)lw.w_up, (const T *)lw.rms2, x, d, f, M, eps, act);
-  });
+  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 16);
+  if (mc < 1) return hipErrorInvalidValue;
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
+      e = gv_set_smem<T>(k_gate_up<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_gate_up<T, MM>), dim3(gv_grid((f + 1) / 2)), dim3(GV_THREADS), sm, st, (const T *)lw.w_gate,
+                         (const T *)lw.w_up, (const T *)lw.rms2, x + (size_t)m0 * d, d, f, m, eps, act + (size_t)m0 * f);
+    });
+  }
   return hipGetLastError();
 }
 
@@ -532,15 +562,19 @@ template <typename T>
 hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, const float *h1, const float *h2, int d,
                            int K, int M, float *Hp) {
   if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
-  hipError_t e = hipSuccess;
-  GV_DISPATCH_M(M, {
-    const size_t sm = 2 * gv_xs_bytes<T>(MM, d);
-    if (sm > GV_MAX_SMEM) return hipErrorInvalidValue;
-    e = gv_set_smem<T>(k_head_mlp<T, MM>, sm);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((k_head_mlp<T, MM>), dim3(gv_grid(K * ((d + 3) / 4))), dim3(GV_THREADS), sm, st, (const T *)w_mlp,
-                       (const T *)pe, h1, h2, d, K, M, Hp);
-  });
+  const int mc = gv_rows_per_launch(M, 2 * gv_xs_bytes<T>(1, d), 0);
+  if (mc < 1) return hipErrorInvalidValue;
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = 2 * gv_xs_bytes<T>(MM, d);
+      e = gv_set_smem<T>(k_head_mlp<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_head_mlp<T, MM>), dim3(gv_grid(K * ((d + 3) / 4))), dim3(GV_THREADS), sm, st, (const T *)w_mlp,
+                         (const T *)pe, h1 + (size_t)m0 * d, h2 + (size_t)m0 * d, d, K, m, Hp + (size_t)m0 * K * d);
+    });
+  }
   return hipGetLastError();
 }
 
