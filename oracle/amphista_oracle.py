@@ -32,6 +32,11 @@ incremental = full recompute, closed forms of Eq. 5 (K = 1, Wq = 0, row
 permutation), full-sort top-k, planted-argmax acceptance and equality with the
 target's own autoregressive greedy continuation.  The numeric output of a whole
 step is otherwise "parity unpinned": the paper prints no worked numbers.
+
+The decode loop around the step (commit of the accepted path, the adaptation
+layers catching up over the newly committed positions -- Eq. 1 keeps one cache
+row per position --, and the generator) is written out at the end of the file;
+its pin is that N steps emit exactly the target's autoregressive greedy tokens.
 """
 from __future__ import annotations
 
@@ -383,3 +388,63 @@ def step(dw, tw, tree: Tree, h_t, tok, sal_k, sal_v, k_caches, v_caches, n_heads
     a, path, nxt, best = accept_greedy(tree, tree_tok, t["tgt"])
     return dict(draft=d, tree_tok=tree_tok, tree_pos=tree_pos, target=t,
                 accept_len=a, path=path, next_tok=nxt, best_node=best)
+
+
+# ----------------------------------------------------------------------------
+# The decode loop around the step (Sec. 2 "Speculative Decoding"; Eq. 1's kv_{1:t-1})
+# ----------------------------------------------------------------------------
+def commit_rows(cache_rows: np.ndarray, new_rows: np.ndarray, path_nodes: Sequence[int]) -> np.ndarray:
+    """Committed cache after a step: the old rows followed by the tree rows of the accepted path
+    (root first), in path order.  cache_rows [n_heads, L, d_h], new_rows [n_heads, T, d_h]."""
+    return np.concatenate([_f(cache_rows), _f(new_rows)[:, list(path_nodes), :]], axis=1)
+
+
+def draft_catchup(dw: Dict[str, object], h_rows: np.ndarray, toks: Sequence[int], sal_k: List[np.ndarray],
+                  sal_v: List[np.ndarray], n_heads: int, topk: int, eps: float, theta: float):
+    """Eq. 1 applied to several newly committed positions, oldest first: position j contributes
+    the pair (h_j, token that follows it) and appends one row to each stage's cache; the heads
+    (Eq. 2-6) of the LAST position are the draft.  Returns (draft of the last position, caches)."""
+    sal_k = [_f(k) for k in sal_k]
+    sal_v = [_f(v) for v in sal_v]
+    d = None
+    for h_t, tok in zip(h_rows, toks):
+        d = draft(dw, h_t, int(tok), sal_k, sal_v, n_heads, topk, eps, theta)
+        for s in range(2):
+            sal_k[s] = np.concatenate([sal_k[s], d["k_new"][s][:, None, :]], axis=1)
+            sal_v[s] = np.concatenate([sal_v[s], d["v_new"][s][:, None, :]], axis=1)
+    return d, sal_k, sal_v
+
+
+def generate(dw, tw, tree: Tree, prompt: Sequence[int], n_steps: int, n_heads: int, topk: int, eps: float,
+             theta: float):
+    """Speculate-and-verify decoding from a prompt (at least two tokens).  The target runs causally over
+    prompt[:-1]; prompt[-1] is the first root.  Every step: draft over the newly committed
+    positions, tree, verification, greedy acceptance, commit.  Returns (emitted tokens, per-step
+    records); the emitted tokens are the target's own greedy continuation of the prompt."""
+    prompt = [int(t) for t in prompt]
+    P = len(prompt) - 1
+    d_h = _f(tw["embed"]).shape[1] // n_heads
+    empty = [np.zeros((n_heads, 0, d_h)) for _ in tw["layers"]]
+    pre = target_forward(tw, np.asarray(prompt[:-1]), np.arange(P), np.tril(np.ones((P, P), dtype=bool)),
+                         empty, empty, n_heads, eps, theta, keep=True)
+    k_caches = [l["k_new"] for l in pre["layers"]]
+    v_caches = [l["v_new"] for l in pre["layers"]]
+    sal_k = [np.zeros((n_heads, 0, d_h)) for _ in range(2)]
+    sal_v = [np.zeros((n_heads, 0, d_h)) for _ in range(2)]
+    h_rows, toks, root = pre["hidden"], prompt[1:], prompt[-1]
+    emitted, records = [], []
+    for _ in range(n_steps):
+        d, sal_k, sal_v = draft_catchup(dw, h_rows, toks, sal_k, sal_v, n_heads, topk, eps, theta)
+        L = k_caches[0].shape[1]
+        tree_tok, tree_pos = tree_tokens(tree, root, d["topk_idx"], L)
+        t = target_forward(tw, tree_tok, tree_pos, tree.mask, k_caches, v_caches, n_heads, eps, theta, keep=True)
+        a, path, nxt, best = accept_greedy(tree, tree_tok, t["tgt"])
+        nodes = [int(n) for n in path[:a + 1]]
+        new_toks = [int(tree_tok[n]) for n in nodes[1:]] + [int(nxt)]
+        emitted += new_toks
+        records.append(dict(draft=d, tree_tok=tree_tok, target=t, accept_len=a, path=path, next_tok=nxt,
+                            nodes=nodes, h_rows=h_rows, toks=list(toks), kv_len=L))
+        k_caches = [commit_rows(k_caches[li], t["layers"][li]["k_new"], nodes) for li in range(len(k_caches))]
+        v_caches = [commit_rows(v_caches[li], t["layers"][li]["v_new"], nodes) for li in range(len(v_caches))]
+        h_rows, toks, root = t["hidden"][nodes], new_toks, int(nxt)
+    return emitted, records

@@ -262,6 +262,57 @@ def test_step_output_equals_autoregressive_greedy_continuation():
     assert hits > 0          # the test exercised at least one accepted draft token
 
 
+def test_generator_emits_the_autoregressive_greedy_continuation():
+    """N steps of the whole loop (draft over the newly committed positions, tree, verification, greedy
+    acceptance, commit) emit exactly the target's own greedy tokens, whatever the draft proposes; and the
+    committed caches after the loop are the caches of a causal pass over the same tokens."""
+    cfg, dw, tw = tiny_setup(seed=2)
+    rng = np.random.default_rng(11)
+    tree = orc.tree_from_paths(si.tree_paths(16, (4, 2, 2, 2)), 4)
+    prompt = [int(t) for t in rng.integers(0, cfg.vocab, size=9)]
+    emitted, recs = orc.generate(dw, tw, tree, prompt, 4, cfg.n_heads, 4, cfg.rms_eps, cfg.rope_theta)
+    assert len(emitted) == sum(r["accept_len"] + 1 for r in recs) >= 4
+    assert emitted == greedy_continuation(cfg, tw, prompt, len(emitted))
+    # cache bookkeeping: the length grows by a + 1 per step and the adaptation layers see one row per position
+    L = len(prompt) - 1
+    for r in recs:
+        assert r["kv_len"] == L and len(r["toks"]) == len(r["h_rows"])
+        L += r["accept_len"] + 1
+    # the first step's draft saw positions 0..P-2 with the tokens that follow them
+    assert recs[0]["toks"] == prompt[1:]
+
+
+def test_draft_catchup_is_the_single_position_draft_repeated():
+    cfg, dw, tw = tiny_setup(seed=3)
+    rng = np.random.default_rng(5)
+    n_h, d_h, d = cfg.n_heads, cfg.head_dim, cfg.d_model
+    sal_k = [rng.standard_normal((n_h, 5, d_h)) for _ in range(2)]
+    sal_v = [rng.standard_normal((n_h, 5, d_h)) for _ in range(2)]
+    hs, toks = rng.standard_normal((3, d)), [3, 9, 27]
+    dl, k3, v3 = orc.draft_catchup(dw, hs, toks, sal_k, sal_v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    # by hand: two single-position drafts to grow the caches, then the third gives the heads
+    k, v = [x.copy() for x in sal_k], [x.copy() for x in sal_v]
+    for j in range(2):
+        dj = orc.draft(dw, hs[j], toks[j], k, v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+        k = [np.concatenate([k[s], dj["k_new"][s][:, None]], axis=1) for s in range(2)]
+        v = [np.concatenate([v[s], dj["v_new"][s][:, None]], axis=1) for s in range(2)]
+    d3 = orc.draft(dw, hs[2], toks[2], k, v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    assert np.array_equal(dl["topk_idx"], d3["topk_idx"]) and np.allclose(dl["logits"], d3["logits"], rtol=0, atol=1e-12)
+    assert all(k3[s].shape[1] == 8 for s in range(2))
+    # the order of the positions matters (each row attends to the earlier ones)
+    dr, _, _ = orc.draft_catchup(dw, hs[::-1], toks[::-1], sal_k, sal_v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    assert not np.allclose(dr["logits"], dl["logits"])
+
+
+def test_commit_rows_keeps_the_path_in_order():
+    old = np.arange(2 * 3 * 4, dtype=float).reshape(2, 3, 4)
+    new = 100 + np.arange(2 * 6 * 4, dtype=float).reshape(2, 6, 4)
+    out = orc.commit_rows(old, new, [0, 2, 5])
+    assert out.shape == (2, 6, 4)
+    assert np.array_equal(out[:, :3], old) and np.array_equal(out[:, 3], new[:, 0])
+    assert np.array_equal(out[:, 4], new[:, 2]) and np.array_equal(out[:, 5], new[:, 5])
+
+
 def test_draft_step_shapes_and_cache_rows():
     cfg, dw, tw = tiny_setup(seed=2)
     rng = np.random.default_rng(9)
