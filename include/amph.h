@@ -112,16 +112,23 @@ amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits);
  * x2 = fc2 [h1; e]; h2 = SAL2(x2); H_p[k] = MLP_k(h1 or h2) + PE[k] (heads 1..floor(K/2) read h1);
  * attn_o = bi-directional multi-head self-attention over the K rows; logits[k] = lm_head attn_o[k];
  * top-k per row, sorted by descending logit, ties to the lower token id.
- *   h_new    [B, n_new, d] float32     tok_new [B, n_new] int32     n_new must be 1
- *   sal_kv   [2 stages, B, 2 (K then V), n_heads, max_kv, head_dim] T; row sal_len[b] of both stages
- *            is written (keys after RoPE at position sal_len[b]) and attended together with rows below it
- *   sal_len  [B] int32, read on the device and advanced by n_new when the call completes
+ * Eq. 1 keeps one cache row per committed position, so after a step that accepted a draft tokens the
+ * adaptation layers first catch up over the a + 1 new positions, oldest first (each row attends to the
+ * cache and to the new rows before it); the heads read the LAST live position.
+ *   h_new    [B, n_new, d] float32     tok_new [B, n_new] int32 (the token that follows each position)
+ *            1 <= n_new, B * n_new <= 8
+ *   n_valid  [B] int32 on the device or NULL: positions j >= n_valid[b] of element b are ignored (no
+ *            cache row, no effect on the heads); NULL = all n_new live.  amph_commit writes such a triple.
+ *   sal_kv   [2 stages, B, 2 (K then V), n_heads, max_kv, head_dim] T; rows sal_len[b] + j of both stages
+ *            are written (keys after RoPE at that position) and attended together with the rows below them
+ *   sal_len  [B] int32, read on the device and advanced by n_valid[b] (or n_new) when the call completes
  *   topk_idx [B, K, topk] int32        topk_val [B, K, topk] float32
  *   logits   [B, K, V] float32 or NULL (then the logits live only in the workspace)
  * Device-side errors: sal_len[b] + 1 > max_kv (AMPH_DEV_SAL_OVERFLOW), token id outside [0, V). */
 amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w /* host */, const float *h_new,
-                       const int32_t *tok_new, int n_new, void *sal_kv, int32_t *sal_len,
-                       int32_t *topk_idx, float *topk_val, float *logits, void *workspace);
+                       const int32_t *tok_new, int n_new, const int32_t *n_valid, void *sal_kv,
+                       int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits,
+                       void *workspace);
 
 /* ---- draft tree (Appendix "Draft Tree") -------------------------------------------------------
  * paths: host array [n, K] of top-k ranks, -1 padded; one row per non-root node, any order; the
@@ -174,6 +181,22 @@ amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q
 amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok,
                         const int32_t *tgt_argmax, const float *tgt_logits, int32_t *accept_len,
                         int32_t *accept_path, int32_t *next_tok, int32_t *best_node, void *workspace);
+
+/* ---- between two steps: commit the accepted path (Sec. 2 "Speculative Decoding") ---------------------
+ * After amph_accept, for every batch element b with a = accept_len[b] and path nodes p_0 = root .. p_a:
+ *   * in every layer the K/V rows of p_1 .. p_a move from tree slots kv_len[b] + p_j to rows kv_len[b] + j
+ *     (the root already sits at kv_len[b]), so the committed rows are again contiguous;
+ *   * if h_new != NULL the inputs of the next amph_draft are gathered: h_new[b, j] = hidden[b, p_j] (the
+ *     target's final-normed hidden state), tok_new[b, j] = the token that follows position j (tree_tok of
+ *     p_{j+1}, or next_tok[b] after p_a), rows j > a zero, n_new[b] = a + 1;
+ *   * kv_len[b] += a + 1.
+ * next_tok[b] is the root of the next tree.  All device pointers; nothing is read on the host.
+ *   k_caches, v_caches as in amph_target_forward     hidden [B, T, d] float32 (its hidden_out)
+ *   h_new [B, K+1, d] float32   tok_new [B, K+1] int32   n_new [B] int32   (call amph_draft with n_new = K+1) */
+amph_status amph_commit(amph_ctx *ctx, const amph_tree *tree, int n_layers, void *k_caches, void *v_caches,
+                        int32_t *kv_len, const int32_t *accept_len, const int32_t *accept_path,
+                        const int32_t *next_tok, const int32_t *tree_tok, const float *hidden, float *h_new,
+                        int32_t *tok_new, int32_t *n_new);
 
 /* ---- A7 + A8 + A9: the target's forward pass over the tree tokens -------------------------------
  * x = embed[tree_tok]; for every layer: RMSNorm, Q/K/V projections, RoPE at tree_pos, K/V written to

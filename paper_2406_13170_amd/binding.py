@@ -53,7 +53,8 @@ EXPORTS = {
     "amph_last_error": (C.c_char_p, [C.c_void_p]),
     "amph_device_status": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
     "amph_draft": (C.c_int, [C.c_void_p, C.POINTER(amph_draft_w), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
-                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "amph_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int] + [C.c_void_p] * 11),
     "amph_tree_create": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
     "amph_tree_destroy": (None, [C.c_void_p]),
     "amph_tree_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)] + [C.POINTER(C.c_void_p)] * 5),
@@ -216,10 +217,17 @@ class Context:
         return s
 
     # -- the calls of include/amph.h
-    def amph_draft(self, dw_struct: amph_draft_w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits=None, n_new=1):
-        self._check(lib().amph_draft(self.handle, C.byref(dw_struct), _ptr(h_new), _ptr(tok_new), n_new, _ptr(sal_kv),
-                                     _ptr(sal_len), _ptr(topk_idx), _ptr(topk_val), _ptr(logits), _ptr(self.workspace)),
-                    "amph_draft")
+    def amph_draft(self, dw_struct: amph_draft_w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits=None, n_new=1,
+                   n_valid=None):
+        self._check(lib().amph_draft(self.handle, C.byref(dw_struct), _ptr(h_new), _ptr(tok_new), n_new, _ptr(n_valid),
+                                     _ptr(sal_kv), _ptr(sal_len), _ptr(topk_idx), _ptr(topk_val), _ptr(logits),
+                                     _ptr(self.workspace)), "amph_draft")
+
+    def amph_commit(self, tree: Tree, n_layers, k_caches, v_caches, kv_len, accept_len, accept_path, next_tok=None,
+                    tree_tok=None, hidden=None, h_new=None, tok_new=None, n_new=None):
+        self._check(lib().amph_commit(self.handle, tree.handle, n_layers, _ptr(k_caches), _ptr(v_caches), _ptr(kv_len),
+                                      _ptr(accept_len), _ptr(accept_path), _ptr(next_tok), _ptr(tree_tok), _ptr(hidden),
+                                      _ptr(h_new), _ptr(tok_new), _ptr(n_new)), "amph_commit")
 
     def amph_tree_build(self, tree: Tree, root_tok, topk_idx, kv_len, tree_tok, tree_pos):
         self._check(lib().amph_tree_build(self.handle, tree.handle, _ptr(root_tok), _ptr(topk_idx), _ptr(kv_len),

@@ -88,8 +88,9 @@ WsLayout make_layout(const amph_config &c) {
   const size_t M = B * (size_t)c.max_tree;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
-  w.x = take(B * d * 4); w.q = take(B * d * 4); w.att = take(B * d * 4); w.y = take(B * d * 4);
-  w.act = take(B * f * 4); w.h[0] = take(B * d * 4); w.h[1] = take(B * d * 4);
+  const size_t Mr = std::max<size_t>(B, 8);     // adaptation-layer rows: up to 8 (batch element, new position) pairs
+  w.x = take(Mr * d * 4); w.q = take(Mr * d * 4); w.att = take(Mr * d * 4); w.y = take(Mr * d * 4);
+  w.act = take(Mr * f * 4); w.h[0] = take(Mr * d * 4); w.h[1] = take(Mr * d * 4);
   w.Hp = take(BK * d * 4); w.Qa = take(BK * d * 4); w.Ka = take(BK * d * 4); w.Va = take(BK * d * 4);
   w.ctxa = take(BK * d * 4); w.attn_o = take(BK * d * 4); w.logits = take(BK * V * 4);
   w.topk_ws = take(std::max(topk_ws_floats((int)BK, c.vocab, c.topk), topk_ws_floats((int)M, c.vocab, 1)) * 4);
@@ -126,10 +127,12 @@ amph_status tree_upload(amph_ctx *ctx, amph_tree *t) {
 }
 
 template <typename T>
-amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new, const int32_t *tok_new, void *sal_kv,
-                       int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits, void *workspace) {
+amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new, const int32_t *tok_new, int R,
+                       const int32_t *n_valid, void *sal_kv, int32_t *sal_len, int32_t *topk_idx, float *topk_val,
+                       float *logits, void *workspace) {
   const amph_config &c = ctx->cfg;
   const int B = c.batch, d = c.d_model, f = c.d_ffn, V = c.vocab, K = c.K, n_h = c.n_heads, d_h = c.head_dim;
+  const int M = B * R;                     // rows of the adaptation layers: (batch element, new position)
   hipStream_t st = ctx->stream;
   char *ws = (char *)workspace;
   auto F = [&](size_t off) { return (float *)(ws + off); };
@@ -139,18 +142,25 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   for (int s = 0; s < 2; ++s) {
     const float *u = (s == 0) ? h_new : h[0];
     void *kv_stage = (T *)sal_kv + s * stage_stride;
-    PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, B, x, ctx->dev_status));
-    PROF_TRY(ctx, AMPH_K_SAL_QKV, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, B, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
-                                   q, ctx->dev_status));
-    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, att));
-    PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, B, x, y, nullptr, nullptr, d));
-    PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, B, c.rms_eps, act));
-    PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, B, y, h[s], nullptr, nullptr, d));
+    PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, M, x, ctx->dev_status));
+    PROF_TRY(ctx, AMPH_K_SAL_QKV, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, M, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
+                                   q, ctx->dev_status, R, n_valid));
+    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, att, R, n_valid));
+    PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, M, x, y, nullptr, nullptr, d));
+    PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, M, c.rms_eps, act));
+    PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, M, y, h[s], nullptr, nullptr, d));
+  }
+  // the heads (Eq. 2-6) read the last live position of every batch element
+  const float *h1 = h[0], *h2 = h[1];
+  if (R > 1) {
+    HIP_TRY(ctx, launch_gather_rows(st, h[0], B, R, d, n_valid, x));
+    HIP_TRY(ctx, launch_gather_rows(st, h[1], B, R, d, n_valid, y));
+    h1 = x; h2 = y;
   }
   float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);
   float *attn_o = F(ctx->ws.attn_o);
   float *lg = logits ? logits : F(ctx->ws.logits);
-  PROF_TRY(ctx, AMPH_K_HEAD_MLP, launch_head_mlp<T>(st, w->mlp, w->pe, h[0], h[1], d, K, B, Hp));
+  PROF_TRY(ctx, AMPH_K_HEAD_MLP, launch_head_mlp<T>(st, w->mlp, w->pe, h1, h2, d, K, B, Hp));
   const int BK = B * K;
   for (int r0 = 0; r0 < BK; r0 += 8) {
     const int m = std::min(8, BK - r0);
@@ -170,7 +180,7 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
                                   lg + (size_t)r0 * V, nullptr, nullptr, V));
   }
-  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, 1, F(ctx->ws.topk_ws)));
+  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, R, n_valid, F(ctx->ws.topk_ws)));
   return AMPH_OK;
 }
 
@@ -317,11 +327,13 @@ amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits) {
 }
 
 amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new, const int32_t *tok_new, int n_new,
-                       void *sal_kv, int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits, void *workspace) {
+                       const int32_t *n_valid, void *sal_kv, int32_t *sal_len, int32_t *topk_idx, float *topk_val,
+                       float *logits, void *workspace) {
   if (!ctx) return AMPH_EINVAL;
   if (!w || !h_new || !tok_new || !sal_kv || !sal_len || !topk_idx || !topk_val || !workspace)
     return fail(ctx, AMPH_EINVAL, "amph_draft: null argument");
-  if (n_new != 1) return fail(ctx, AMPH_ESHAPE, "amph_draft: n_new must be 1");
+  if (n_new < 1 || (long long)n_new * ctx->cfg.batch > 8)
+    return fail(ctx, AMPH_ESHAPE, "amph_draft: need 1 <= n_new and batch * n_new <= 8");
   const void *ptrs[] = {w->embed, w->fc[0], w->fc[1], w->mlp, w->pe, w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, w->lm_head,
                         h_new, sal_kv, workspace};
   for (const void *p : ptrs)
@@ -334,8 +346,8 @@ amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   }
   if (ctx->cfg.batch > 8) return fail(ctx, AMPH_ESHAPE, "amph_draft: batch > 8 is not supported");
   if (ctx->cfg.dtype == AMPH_BF16)
-    return draft_impl<bf16_t>(ctx, w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
-  return draft_impl<float>(ctx, w, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
+    return draft_impl<bf16_t>(ctx, w, h_new, tok_new, n_new, n_valid, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
+  return draft_impl<float>(ctx, w, h_new, tok_new, n_new, n_valid, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
 }
 
 amph_status amph_tree_create(const int32_t *paths, int n, int K, amph_tree **out) {
@@ -500,6 +512,28 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
                                tree_pos, k_caches, v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
   return target_impl<float>(ctx, tree, layers, tiled, n_layers, embed, final_norm, lm_head, lm_head_tiled, tree_tok,
                             tree_pos, k_caches, v_caches, kv_len, hidden_out, logits_out, tgt_argmax, workspace);
+}
+
+amph_status amph_commit(amph_ctx *ctx, const amph_tree *tree, int n_layers, void *k_caches, void *v_caches,
+                        int32_t *kv_len, const int32_t *accept_len, const int32_t *accept_path, const int32_t *next_tok,
+                        const int32_t *tree_tok, const float *hidden, float *h_new, int32_t *tok_new, int32_t *n_new) {
+  if (!ctx) return AMPH_EINVAL;
+  if (n_layers < 0 || !kv_len || !accept_len || !accept_path || (n_layers > 0 && (!k_caches || !v_caches)))
+    return fail(ctx, AMPH_EINVAL, "amph_commit: null argument");
+  if (h_new && (!tok_new || !n_new || !next_tok || !tree_tok || !hidden || !aligned16(h_new) || !aligned16(hidden)))
+    return fail(ctx, AMPH_EINVAL, "amph_commit: the draft's next inputs need tok_new, n_new, next_tok, tree_tok and hidden");
+  if (!aligned16(k_caches) || !aligned16(v_caches)) return fail(ctx, AMPH_EINVAL, "amph_commit: misaligned cache");
+  if (amph_status s = check_tree(ctx, tree, "amph_commit")) return s;
+  const amph_config &c = ctx->cfg;
+  if (ctx->cfg.dtype == AMPH_BF16)
+    HIP_TRY(ctx, launch_commit<bf16_t>(ctx->stream, k_caches, v_caches, n_layers, c.batch, c.n_heads, c.head_dim, c.max_kv,
+                                       tree->T, c.d_model, c.K, kv_len, accept_len, accept_path, next_tok, tree_tok, hidden,
+                                       h_new, tok_new, n_new));
+  else
+    HIP_TRY(ctx, launch_commit<float>(ctx->stream, k_caches, v_caches, n_layers, c.batch, c.n_heads, c.head_dim, c.max_kv,
+                                      tree->T, c.d_model, c.K, kv_len, accept_len, accept_path, next_tok, tree_tok, hidden,
+                                      h_new, tok_new, n_new));
+  return AMPH_OK;
 }
 
 // shape of the GEMM a packing role belongs to: epilogue kind, stacked matrices, rows per matrix, reduction length

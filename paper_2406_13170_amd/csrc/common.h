@@ -93,6 +93,17 @@ template <> __device__ __forceinline__ f32x4 mma16<float>(const uint4 &a, const 
   return acc;
 }
 
+// Element index of (row, dim) in the step-tiled K and V caches of one head (layout: header of the C ABI).
+template <typename T> __device__ __forceinline__ size_t k_tiled_index(int row, int c, int d_h) {
+  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);   // elements in 64 bytes
+  const int s = row / KSTEP, kk = row % KSTEP, t = (kk % PER) / 4, i = (kk / PER) * 4 + (kk & 3);
+  return ((size_t)(s * (PER / 4) + t) * (d_h / PIECE) + c / PIECE) * (16 * PIECE) + i * PIECE + c % PIECE;
+}
+template <typename T> __device__ __forceinline__ size_t v_tiled_index(int row, int c, int d_h) {
+  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);
+  return ((size_t)(row / KSTEP) * (d_h / 16) + c / 16) * (16 * PIECE) + (c % 16) * PIECE + row % KSTEP;
+}
+
 // ---- wave-level reductions ---------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
   #pragma unroll

@@ -50,17 +50,6 @@ constexpr int GM_MIN_NB = 2, GM_MAX_NB = 12;    // math waves (= row blocks) per
 static_assert(GM_LDS_BYTES >= GM_BM * (16 * GM_MAX_NB + 4) * 4, "output tile must fit in the staging buffers");
 static_assert(64 * (GM_MAX_NB + GM_NLW) <= 1024, "workgroup size");
 
-// Element index of (row, dim) in the step-tiled K and V caches of one head (layout: header of the C ABI).
-template <typename T> __device__ __forceinline__ size_t k_tiled_index(int row, int c, int d_h) {
-  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);   // elements in 64 bytes
-  const int s = row / KSTEP, kk = row % KSTEP, t = (kk % PER) / 4, i = (kk / PER) * 4 + (kk & 3);
-  return ((size_t)(s * (PER / 4) + t) * (d_h / PIECE) + c / PIECE) * (16 * PIECE) + i * PIECE + c % PIECE;
-}
-template <typename T> __device__ __forceinline__ size_t v_tiled_index(int row, int c, int d_h) {
-  constexpr int PER = Elem<T>::PER, KSTEP = 4 * PER, PIECE = 64 / (int)sizeof(T);
-  return ((size_t)(row / KSTEP) * (d_h / 16) + c / 16) * (16 * PIECE) + (c % 16) * PIECE + row % KSTEP;
-}
-
 // number of row blocks of a GEMM
 __host__ __device__ inline int gemm_blocks(int epi, int seg_rows) {
   if (epi == EPI_QKV_ROPE) return 3 * (seg_rows / 16);

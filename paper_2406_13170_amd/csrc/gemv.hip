@@ -233,16 +233,18 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
 }
 
 // =====================================================================================================
-// K2: SAL q/k/v projections on RMSNorm(x) with RoPE at position sal_len[b]; k and v go straight into
-// row sal_len[b] of the stage's cache, q (float32) to qbuf [M, d].  Row m is batch element m.
-// A wave step handles the two RoPE pairs (i, i + half), (i + 1, i + 1 + half) of one head.
-// kv_stage points at [B, 2, n_heads, max_kv, d_h] of this stage.
+// K2: SAL q/k/v projections on RMSNorm(x) with RoPE; k and v go straight into the stage's cache, q
+// (float32) to qbuf [M, d].  Row row0 + m of the call is new position j = row % R of batch element
+// b = row / R: its RoPE position and cache row are sal_len[b] + j; positions j >= n_valid[b] (when
+// n_valid is given) write nothing.  A wave step handles the two RoPE pairs (i, i + half),
+// (i + 1, i + 1 + half) of one head.  kv_stage points at [B, 2, n_heads, max_kv, d_h] of this stage.
 // =====================================================================================================
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk, const T *wv, const T *norm_w,
                                                         const float *x, int d, int n_heads, int d_h, int m_valid,
                                                         float eps, float theta, const int32_t *sal_len, int max_kv,
-                                                        T *kv_stage, float *qbuf, uint32_t *dev_status) {
+                                                        T *kv_stage, float *qbuf, uint32_t *dev_status, int row0, int R,
+                                                        const int32_t *n_valid) {
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -277,8 +279,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
       #pragma unroll
       for (int m = 0; m < M; ++m) {
         if (m >= m_valid) continue;
-        const int pos = sal_len[m];
-        if (pos < 0 || pos + 1 > max_kv) {
+        const int bb = (row0 + m) / R, jn = (row0 + m) % R;
+        if (n_valid && jn >= n_valid[bb]) continue;
+        const int pos = sal_len[bb] + jn;
+        if (sal_len[bb] < 0 || pos + 1 > max_kv) {
           if (g == 0) atomicOr(dev_status, 1u);
           continue;
         }
@@ -304,7 +308,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
           #pragma unroll
           for (int r = 0; r < GV_R; ++r) {
             const int hh = n[r] / d_h, e = n[r] % d_h;
-            T *dst = kv_stage + ((((size_t)m * 2 + (seg - 1)) * n_heads + hh) * max_kv + pos) * d_h + e;
+            T *dst = kv_stage + ((((size_t)bb * 2 + (seg - 1)) * n_heads + hh) * max_kv + pos) * d_h + e;
             *dst = Elem<T>::from_f32(y[r]);
           }
         }
@@ -496,11 +500,10 @@ hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const
 template <typename T>
 hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int n_heads, int d_h, int M,
                           float eps, float theta, const int32_t *sal_len, int max_kv, void *kv_stage, float *qbuf,
-                          uint32_t *dev_status) {
+                          uint32_t *dev_status, int R, const int32_t *n_valid) {
   if (M < 1 || M > 8 || d % 8 || d_h % 4) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 16);
   if (mc < 1) return hipErrorInvalidValue;
-  const size_t kv_row = (size_t)2 * n_heads * max_kv * d_h;           // cache elements of one batch element
   for (int m0 = 0; m0 < M; m0 += mc) {
     const int m = std::min(mc, M - m0);
     hipError_t e = hipSuccess;
@@ -510,7 +513,7 @@ hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL((k_sal_qkv<T, MM>), dim3(gv_grid(3 * d / 4)), dim3(GV_THREADS), sm, st, (const T *)lw.wq,
                          (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1, x + (size_t)m0 * d, d, n_heads, d_h, m, eps,
-                         theta, sal_len + m0, max_kv, (T *)kv_stage + (size_t)m0 * kv_row, qbuf + (size_t)m0 * d, dev_status);
+                         theta, sal_len, max_kv, (T *)kv_stage, qbuf + (size_t)m0 * d, dev_status, m0, R, n_valid);
     });
   }
   return hipGetLastError();
@@ -582,7 +585,8 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
   template hipError_t launch_fc_concat<T>(hipStream_t, const void *, const float *, const void *, const int32_t *, int, \
                                           int, int, float *, uint32_t *);                                               \
   template hipError_t launch_sal_qkv<T>(hipStream_t, const amph_layer_w &, const float *, int, int, int, int, float,    \
-                                        float, const int32_t *, int, void *, float *, uint32_t *);                      \
+                                        float, const int32_t *, int, void *, float *, uint32_t *, int,                  \
+                                        const int32_t *);                                                               \
   template hipError_t launch_linear<T>(hipStream_t, const void *, const void *, const void *, int, int, int,            \
                                        const float *, int, int, const float *, float *, float *, float *, int);         \
   template hipError_t launch_gate_up<T>(hipStream_t, const amph_layer_w &, const float *, int, int, int, float, float *); \

@@ -14,7 +14,7 @@ hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const
 template <typename T>
 hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int n_heads, int d_h, int M,
                           float eps, float theta, const int32_t *sal_len, int max_kv, void *kv_stage, float *qbuf,
-                          uint32_t *dev_status);
+                          uint32_t *dev_status, int R, const int32_t *n_valid);   // rows = (batch element, new position < R)
 template <typename T>
 hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const void *w2, int n_seg, int seg_rows, int Kd,
                          const float *x, int ldx, int M, const float *res, float *o0, float *o1, float *o2, int ldo);
@@ -28,13 +28,13 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
 // ---- small.hip (attention of the draft path, top-k, tree, accept, norms) ----
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *out);
+                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid);
 hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, const float *V, int B, int K, int n_heads,
                            int d_h, float *ctx);
 // ws: topk_ws_floats(rows, V, k) floats of scratch for the per-wave candidates
 size_t topk_ws_floats(int rows, int V, int k);
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by, float *ws);
+                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, float *ws);
 hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws);
 hipError_t launch_tree_build(hipStream_t st, const int32_t *depth, const int32_t *rank, int T, int B, int K, int topk,
                              const int32_t *root_tok, const int32_t *topk_idx, const int32_t *kv_len, int32_t *tree_tok,
@@ -42,6 +42,14 @@ hipError_t launch_tree_build(hipStream_t st, const int32_t *depth, const int32_t
 hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *depth, int T, int B, int K,
                          const int32_t *tree_tok, const int32_t *tgt, int32_t *accept_len, int32_t *accept_path,
                          int32_t *next_tok, int32_t *best_node);
+// the loop around the step: compaction of the accepted path's K/V rows in every layer, the rows the draft
+// consumes next (h_new may be NULL: then only the caches and kv_len are updated), kv_len += accepted + 1
+template <typename T>
+hipError_t launch_commit(hipStream_t st, void *k_caches, void *v_caches, int n_layers, int B, int n_heads, int d_h, int max_kv,
+                         int T_nodes, int d, int K, int32_t *kv_len, const int32_t *accept_len, const int32_t *accept_path,
+                         const int32_t *next_tok, const int32_t *tree_tok, const float *hidden, float *h_new, int32_t *tok_new,
+                         int32_t *n_new);
+hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, int d, const int32_t *n_valid, float *out);
 // x[m] (+)= sum_s slabs[s][m] (or x[m] = embed[tok[m]] when tok != NULL); xn[m] = RMSNorm(x[m]) * g as T;
 // hidden_out (float32, optional) receives the same normalised rows.
 template <typename T>

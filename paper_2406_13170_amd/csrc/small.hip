@@ -6,8 +6,9 @@
 namespace amph {
 
 // =====================================================================================================
-// Single-query attention over a SAL cache: one new position per (batch, head) against rows
-// [0, sal_len] of the cache (the new row included).  grid = (heads, batch), 1024 threads: the 16
+// Single-query attention over a SAL cache: query row (b, j) = new position j of batch element b against
+// rows [0, sal_len[b] + j] of the cache (its own new row included, later new rows excluded: causal among
+// the new positions).  grid = (heads, batch * R), 1024 threads: the 16
 // waves of a workgroup stride over the rows.  Each 16-byte fragment of a key/value row belongs to one
 // lane; LPR lanes share a row, so a wave covers 64/LPR rows per load.  Running (max, sum, weighted
 // values) are merged lane group -> wave -> workgroup; no workgroup depends on another.
@@ -17,23 +18,25 @@ constexpr int SA_WAVES = 16;
 
 template <typename T, int DH>
 __global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, const T *kv_stage, const int32_t *sal_len,
-                                                            int n_heads, int max_kv, float *out) {
+                                                            int n_heads, int max_kv, float *out, int R,
+                                                            const int32_t *n_valid) {
   constexpr int PER = Elem<T>::PER;
   constexpr int LPR = DH / PER;          // lanes per row
   constexpr int G = WAVE / LPR;          // rows per wave load
   constexpr int U = 4;
   __shared__ float sm_m[SA_WAVES], sm_l[SA_WAVES];
   __shared__ float sm_o[SA_WAVES][DH];
-  const int b = blockIdx.y, h = blockIdx.x;
+  const int row = blockIdx.y, b = row / R, jn = row % R, h = blockIdx.x;
   const int d = n_heads * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int grp = lane / LPR, li = lane % LPR;
-  const int len = sal_len[b];
-  const int n = (len < 0 || len + 1 > max_kv) ? 0 : len + 1;
+  const int len = sal_len[b] + jn;
+  const bool live = !(n_valid && jn >= n_valid[b]);
+  const int n = (!live || sal_len[b] < 0 || len + 1 > max_kv) ? 0 : len + 1;
   const float scale = 1.4426950408889634f * rsqrtf((float)DH);
   float qv[PER];
   #pragma unroll
-  for (int j = 0; j < PER; ++j) qv[j] = qbuf[(size_t)b * d + h * DH + li * PER + j] * scale;
+  for (int j = 0; j < PER; ++j) qv[j] = qbuf[(size_t)row * d + h * DH + li * PER + j] * scale;
   const T *kbase = kv_stage + (((size_t)b * 2 + 0) * n_heads + h) * (size_t)max_kv * DH;
   const T *vbase = kv_stage + (((size_t)b * 2 + 1) * n_heads + h) * (size_t)max_kv * DH;
   float m = NEG_BIG, l = 0.f, o[PER];
@@ -100,26 +103,28 @@ __global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, c
       lw += sm_l[w] * f;
       ow += sm_o[w][threadIdx.x] * f;
     }
-    out[(size_t)b * d + h * DH + threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
+    out[(size_t)row * d + h * DH + threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
   }
 }
 
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *out) {
-  const dim3 grid(n_heads, B), block(SA_WAVES * 64);
+                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid) {
+  const dim3 grid(n_heads, B * R), block(SA_WAVES * 64);
   if (d_h == 64)
-    hipLaunchKernelGGL((k_sal_attn<T, 64>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out);
+    hipLaunchKernelGGL((k_sal_attn<T, 64>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out, R,
+                       n_valid);
   else if (d_h == 128)
-    hipLaunchKernelGGL((k_sal_attn<T, 128>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out);
+    hipLaunchKernelGGL((k_sal_attn<T, 128>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out, R,
+                       n_valid);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 template hipError_t launch_sal_attn<float>(hipStream_t, const float *, const void *, const int32_t *, int, int, int, int,
-                                           float *);
+                                           float *, int, const int32_t *);
 template hipError_t launch_sal_attn<bf16_t>(hipStream_t, const float *, const void *, const int32_t *, int, int, int,
-                                            int, float *);
+                                            int, float *, int, const int32_t *);
 
 // =====================================================================================================
 // Eq. 5 core: for one (batch, head) the K x K score matrix of the K head positions, a row softmax
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(256) void k_topk_pass1(const float *logits, int V, 
 
 __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const int *cand_i, int n_cand, int V, int k,
                                                    int32_t *idx, float *val, int32_t *advance, int n_advance,
-                                                   int advance_by) {
+                                                   int advance_by, const int32_t *advance_each) {
   const int row = blockIdx.x, lane = threadIdx.x;
   float x[TK_MAXC]; int id[TK_MAXC];
   #pragma unroll
@@ -258,7 +263,8 @@ __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const in
     if (idx) idx[(size_t)row * k + lane] = si[lane];
     if (val) val[(size_t)row * k + lane] = sv[lane];
   }
-  if (row == 0 && advance) for (int i = lane; i < n_advance; i += WAVE) advance[i] += advance_by;
+  if (row == 0 && advance)
+    for (int i = lane; i < n_advance; i += WAVE) advance[i] += advance_each ? advance_each[i] : advance_by;
 }
 
 size_t topk_ws_floats(int rows, int V, int k) {
@@ -267,7 +273,7 @@ size_t topk_ws_floats(int rows, int V, int k) {
 }
 
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by, float *ws) {
+                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, float *ws) {
   if (rows < 1 || V < 1 || k < 1 || k > V || k > AMPH_MAX_TOPK) return hipErrorInvalidValue;
   const int chunks = (V + TK_CHUNK - 1) / TK_CHUNK;
   const int n_cand = chunks * k;
@@ -276,12 +282,12 @@ hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V
   int *cand_i = reinterpret_cast<int *>(ws + (size_t)rows * n_cand);
   hipLaunchKernelGGL(k_topk_pass1, dim3((chunks + 3) / 4, rows), dim3(256), 0, st, logits, V, k, chunks, cand_v, cand_i);
   hipLaunchKernelGGL(k_topk_pass2, dim3(rows), dim3(64), 0, st, cand_v, cand_i, n_cand, V, k, idx, val, advance, n_advance,
-                     advance_by);
+                     advance_by, advance_each);
   return hipGetLastError();
 }
 
 hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws) {
-  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0, ws);
+  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0, nullptr, ws);
 }
 
 // =====================================================================================================
@@ -352,6 +358,117 @@ hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *d
                          int32_t *next_tok, int32_t *best_node) {
   hipLaunchKernelGGL(k_accept, dim3(B), dim3(AMPH_MAX_TREE), 0, st, parent, depth, T, K, tree_tok, tgt, accept_len,
                      accept_path, next_tok, best_node);
+  return hipGetLastError();
+}
+
+// =====================================================================================================
+// The loop around the step (Sec. 2 "Speculative Decoding"; Eq. 1 keeps one adaptation-layer cache row per
+// committed position).
+//   k_kv_commit: for one (layer, batch element, head), the K/V rows of the accepted path's nodes 1..a move
+//     from tree slots kv_len + node to kv_len + j (node 0, the root, already sits at kv_len).  All sources
+//     are read before the first write (a destination may be another node's source).
+//   k_gather_accepted: row j <= a of h_new is the target's hidden state at path node j, tok_new[j] the
+//     token that follows it (the next path node's token, or next_tok after the last); n_new = a + 1.
+//   k_advance_len: kv_len += a + 1, as its own launch, after every workgroup above has read kv_len.
+//   k_gather_rows: out[b] = rows[b * R + (n_valid ? n_valid[b] : R) - 1] (the last live row of each element).
+// =====================================================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void k_kv_commit(T *k_caches, T *v_caches, int B, int n_heads, int d_h, int max_kv,
+                                                   int T_nodes, const int32_t *kv_len, const int32_t *accept_len,
+                                                   const int32_t *accept_path, int K) {
+  const int h = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
+  const int L = kv_len[b];
+  int a = accept_len[b];
+  if (L < 0 || L + T_nodes > max_kv || a < 0) return;       // the target pass wrote nothing (flagged there)
+  if (a > K) a = K;
+  const size_t head = (((size_t)li * B + b) * n_heads + h) * (size_t)max_kv * d_h;
+  T *kc = k_caches + head, *vc = v_caches + head;
+  constexpr int MAXE = (AMPH_MAX_HEADS_K * 128 + 255) / 256;     // elements per thread: a * d_h <= 8 * 128
+  T kr[MAXE], vr[MAXE];
+  #pragma unroll
+  for (int i = 0; i < MAXE; ++i) {
+    const int idx = threadIdx.x + i * 256, j = idx / d_h + 1, e = idx % d_h;
+    if (j <= a) {
+      int node = accept_path[(size_t)b * (K + 1) + j];
+      node = min(max(node, 0), T_nodes - 1);
+      kr[i] = kc[k_tiled_index<T>(L + node, e, d_h)];
+      vr[i] = vc[v_tiled_index<T>(L + node, e, d_h)];
+    }
+  }
+  __syncthreads();
+  #pragma unroll
+  for (int i = 0; i < MAXE; ++i) {
+    const int idx = threadIdx.x + i * 256, j = idx / d_h + 1, e = idx % d_h;
+    if (j <= a) {
+      kc[k_tiled_index<T>(L + j, e, d_h)] = kr[i];
+      vc[v_tiled_index<T>(L + j, e, d_h)] = vr[i];
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void k_gather_accepted(const float *hidden, const int32_t *tree_tok, int T_nodes, int d,
+                                                         int K, const int32_t *accept_len, const int32_t *accept_path,
+                                                         const int32_t *next_tok, float *h_new, int32_t *tok_new,
+                                                         int32_t *n_new) {
+  const int j = blockIdx.x, b = blockIdx.y;
+  const int a = min(max(accept_len[b], 0), K);
+  const int32_t *path = accept_path + (size_t)b * (K + 1);
+  float *dst = h_new + ((size_t)b * (K + 1) + j) * d;
+  if (j <= a) {
+    const int node = min(max(path[j], 0), T_nodes - 1);
+    const float *src = hidden + ((size_t)b * T_nodes + node) * d;
+    for (int k = threadIdx.x * 4; k < d; k += 256 * 4) *reinterpret_cast<float4 *>(dst + k) = *reinterpret_cast<const float4 *>(src + k);
+    if (threadIdx.x == 0)
+      tok_new[(size_t)b * (K + 1) + j] = (j < a) ? tree_tok[(size_t)b * T_nodes + min(max(path[j + 1], 0), T_nodes - 1)] : next_tok[b];
+  } else {
+    for (int k = threadIdx.x * 4; k < d; k += 256 * 4) *reinterpret_cast<float4 *>(dst + k) = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (threadIdx.x == 0) tok_new[(size_t)b * (K + 1) + j] = 0;
+  }
+  if (j == 0 && threadIdx.x == 0) n_new[b] = a + 1;
+}
+
+__global__ void k_advance_len(int32_t *kv_len, const int32_t *accept_len, int B, int K, int T_nodes, int max_kv) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int L = kv_len[b];
+  if (L < 0 || L + T_nodes > max_kv) return;
+  kv_len[b] = L + min(max(accept_len[b], 0), K) + 1;
+}
+
+__global__ __launch_bounds__(256) void k_gather_rows(const float *rows, int R, int d, const int32_t *n_valid, float *out) {
+  const int b = blockIdx.x;
+  int r = n_valid ? n_valid[b] : R;
+  r = min(max(r, 1), R) - 1;
+  const float *src = rows + ((size_t)b * R + r) * d;
+  for (int k = threadIdx.x * 4; k < d; k += 256 * 4)
+    *reinterpret_cast<float4 *>(out + (size_t)b * d + k) = *reinterpret_cast<const float4 *>(src + k);
+}
+
+template <typename T>
+hipError_t launch_commit(hipStream_t st, void *k_caches, void *v_caches, int n_layers, int B, int n_heads, int d_h, int max_kv,
+                         int T_nodes, int d, int K, int32_t *kv_len, const int32_t *accept_len, const int32_t *accept_path,
+                         const int32_t *next_tok, const int32_t *tree_tok, const float *hidden, float *h_new, int32_t *tok_new,
+                         int32_t *n_new) {
+  if (K < 1 || K > AMPH_MAX_HEADS_K || d_h > 128 || d % 4) return hipErrorInvalidValue;
+  if (n_layers > 0)
+    hipLaunchKernelGGL((k_kv_commit<T>), dim3(n_heads, B, n_layers), dim3(256), 0, st, (T *)k_caches, (T *)v_caches, B, n_heads,
+                       d_h, max_kv, T_nodes, kv_len, accept_len, accept_path, K);
+  if (h_new)
+    hipLaunchKernelGGL(k_gather_accepted, dim3(K + 1, B), dim3(256), 0, st, hidden, tree_tok, T_nodes, d, K, accept_len,
+                       accept_path, next_tok, h_new, tok_new, n_new);
+  hipLaunchKernelGGL(k_advance_len, dim3((B + 63) / 64), dim3(64), 0, st, kv_len, accept_len, B, K, T_nodes, max_kv);
+  return hipGetLastError();
+}
+template hipError_t launch_commit<float>(hipStream_t, void *, void *, int, int, int, int, int, int, int, int, int32_t *,
+                                         const int32_t *, const int32_t *, const int32_t *, const int32_t *, const float *,
+                                         float *, int32_t *, int32_t *);
+template hipError_t launch_commit<bf16_t>(hipStream_t, void *, void *, int, int, int, int, int, int, int, int, int32_t *,
+                                          const int32_t *, const int32_t *, const int32_t *, const int32_t *, const float *,
+                                          float *, int32_t *, int32_t *);
+
+hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, int d, const int32_t *n_valid, float *out) {
+  if (d % 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, st, rows, R, d, n_valid, out);
   return hipGetLastError();
 }
 
