@@ -18,6 +18,10 @@
 
 namespace amph {
 
+// 2^x through the hardware instruction alone: arguments here are <= 0 (or hugely negative for masked keys), so
+// the library version's rescue of results below the normal range (four more instructions per call) buys nothing.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <typename T, int DH, int NQB>
 struct VA {
   static constexpr int PER = Elem<T>::PER;
@@ -81,9 +85,10 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     for (int db = 0; db < DB; ++db) O[qb][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  // One key step: loads of the step's K and V^T fragments, and the math on them.  The loop below keeps
-  // the next step's fragments in flight while the current step is being processed (two register sets).
-  auto load_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
+  // One key step.  K fragments are requested one step ahead (two register sets); the V^T fragments of a step are
+  // requested when its math starts and arrive while the scores and the softmax are computed, which keeps the
+  // live registers below what a second V set would need.
+  auto load_k = [&](int st, uint4 (&Kf)[NT][DSTEPS]) {
     // fragment (t, ds) of the step holds keys st*KSTEP + (i>>2)*(4*NT) + t*4 + (i&3) at slot i = lane & 15, so
     // that the S^T accumulators come out in the contraction-slot order of the second product
     #pragma unroll
@@ -91,24 +96,15 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
       #pragma unroll
       for (int ds = 0; ds < DSTEPS; ++ds) Kf[t][ds] = ldg16(Kb + ((size_t)(st * NT + t) * DSTEPS + ds) * 1024);
     }
+  };
+  auto math_step = [&](int st, int st_next, bool first, uint4 (&Kf)[NT][DSTEPS], uint4 (&Kn)[NT][DSTEPS]) {
+    uint4 Vf[DB];
     #pragma unroll
     for (int db = 0; db < DB; ++db) Vf[db] = ldg16(Vb + ((size_t)st * DB + db) * 1024);
-  };
-  auto math_step = [&](int st, uint4 (&Kf)[NT][DSTEPS], uint4 (&Vf)[DB]) {
+    load_k(st_next, Kn);
     const int key0 = st * KSTEP;
     const bool tail = (key0 + KSTEP > L);            // this step touches tree rows or rows past the end
-    if (key0 + KSTEP > n_keys) {
-      // rows past L+T may hold anything (even NaN): zero their values so that 0 * V stays 0
-      #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        float vv[PER];
-        Elem<T>::unpack(Vf[db], vv);
-        #pragma unroll
-        for (int j = 0; j < PER; ++j) if (key0 + g * PER + j >= n_keys) vv[j] = 0.f;
-        Vf[db] = pack16<T>(vv);
-      }
-    }
-
+    float pv_all[NQB][PER], corr_all[NQB];
     #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
       // ---- S^T tiles: lane gets keys key0 + g*PER + (t*4 + i), query r16
@@ -141,17 +137,31 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
       mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
       mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
       const float mn = fmaxf(m_run[qb], mx);
-      const float corr = exp2f(m_run[qb] - mn);
-      float pv[PER], ls = 0.f;
+      corr_all[qb] = fast_exp2(m_run[qb] - mn);
+      float ls = 0.f;
       #pragma unroll
-      for (int j = 0; j < PER; ++j) { pv[j] = exp2f(sv[j] - mn); ls += pv[j]; }
-      l_run[qb] = l_run[qb] * corr + ls;
+      for (int j = 0; j < PER; ++j) { pv_all[qb][j] = fast_exp2(sv[j] - mn); ls += pv_all[qb][j]; }
+      l_run[qb] = l_run[qb] * corr_all[qb] + ls;
       m_run[qb] = mn;
-      const uint4 Pf = pack16<T>(pv);
-      // ---- O^T += V^T P^T
+    }
+    if (key0 + KSTEP > n_keys) {
+      // rows past L+T may hold anything (even NaN): zero their values so that 0 * V stays 0
       #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        O[qb][db] *= corr;
+        float vv[PER];
+        Elem<T>::unpack(Vf[db], vv);
+        #pragma unroll
+        for (int j = 0; j < PER; ++j) if (key0 + g * PER + j >= n_keys) vv[j] = 0.f;
+        Vf[db] = pack16<T>(vv);
+      }
+    }
+    #pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const uint4 Pf = pack16<T>(pv_all[qb]);
+      // ---- O^T += V^T P^T; on a wave's first step O is still zero and needs no rescaling
+      #pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        if (!first) O[qb][db] *= corr_all[qb];
         O[qb][db] = mma16<T>(Vf[db], Pf, O[qb][db]);
       }
     }
@@ -159,16 +169,14 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
 
   const int n_w = (st1 - (st0 + wave) + 3) / 4;        // key steps of this wave: st0 + wave, + 4, ...
   if (n_w > 0) {
-    uint4 KA[NT][DSTEPS], VA_[DB], KB_[NT][DSTEPS], VB_[DB];
+    uint4 KA[NT][DSTEPS], KB_[NT][DSTEPS];
     const int first = st0 + wave;
-    load_step(first, KA, VA_);
-    for (int i = 0; i < n_w; i += 2) {
-      // loads are unconditional (an index past the end re-reads the last step) so that the number of
-      // outstanding loads is the same on every path
-      load_step(first + 4 * min(i + 1, n_w - 1), KB_, VB_);
-      math_step(first + 4 * i, KA, VA_);
-      load_step(first + 4 * min(i + 2, n_w - 1), KA, VA_);
-      if (i + 1 < n_w) math_step(first + 4 * (i + 1), KB_, VB_);
+    load_k(first, KA);
+    // the next step's index is clamped (it re-reads the last step) so that every iteration issues the same loads
+    math_step(first, first + 4 * min(1, n_w - 1), true, KA, KB_);
+    for (int i = 1; i < n_w; i += 2) {
+      math_step(first + 4 * i, first + 4 * min(i + 1, n_w - 1), false, KB_, KA);
+      if (i + 1 < n_w) math_step(first + 4 * (i + 1), first + 4 * min(i + 2, n_w - 1), false, KA, KB_);
     }
   }
 
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     float l = 0.f;
     #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float f = exp2f(sm_m[w][q] - mw);
+      const float f = fast_exp2(sm_m[w][q] - mw);
       o += *reinterpret_cast<const f32x4 *>(&sm_o[w][q][d4]) * f;
       l += sm_l[w][q] * f;
     }
