@@ -85,9 +85,13 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     for (int db = 0; db < DB; ++db) O[qb][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  // One key step.  K fragments are requested one step ahead (two register sets); the V^T fragments of a step are
-  // requested when its math starts and arrive while the scores and the softmax are computed, which keeps the
-  // live registers below what a second V set would need.
+  // A wave's key steps are processed in groups of GS.  Pass 1 of a group computes all its scores (S^T tiles) and
+  // keeps them in registers; the running maximum then moves once per group, so the accumulators are rescaled once
+  // per group (never on the first one) instead of once per step, and one cross-lane maximum serves the whole group.
+  // Pass 2 turns the scores into probabilities and adds V^T P^T.  K fragments are requested one step ahead, V
+  // fragments one step ahead within pass 2 (two register sets each); every load is unconditional: steps past
+  // the wave's last one re-read it and contribute nothing.
+  constexpr int GS = 4;
   auto load_k = [&](int st, uint4 (&Kf)[NT][DSTEPS]) {
     // fragment (t, ds) of the step holds keys st*KSTEP + (i>>2)*(4*NT) + t*4 + (i&3) at slot i = lane & 15, so
     // that the S^T accumulators come out in the contraction-slot order of the second product
@@ -97,25 +101,24 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
       for (int ds = 0; ds < DSTEPS; ++ds) Kf[t][ds] = ldg16(Kb + ((size_t)(st * NT + t) * DSTEPS + ds) * 1024);
     }
   };
-  auto math_step = [&](int st, int st_next, bool first, uint4 (&Kf)[NT][DSTEPS], uint4 (&Kn)[NT][DSTEPS]) {
-    uint4 Vf[DB];
+  auto load_v = [&](int st, uint4 (&Vf)[DB]) {
     #pragma unroll
     for (int db = 0; db < DB; ++db) Vf[db] = ldg16(Vb + ((size_t)st * DB + db) * 1024);
-    load_k(st_next, Kn);
+  };
+  // scores of one step for every query block of the wave, scaled, masked where the tree or the end of the cache says so
+  auto scores = [&](int st, const uint4 (&Kf)[NT][DSTEPS], float (&sv)[NQB][PER], float (&mx)[NQB]) {
     const int key0 = st * KSTEP;
     const bool tail = (key0 + KSTEP > L);            // this step touches tree rows or rows past the end
-    float pv_all[NQB][PER], corr_all[NQB];
     #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      // ---- S^T tiles: lane gets keys key0 + g*PER + (t*4 + i), query r16
-      float sv[PER];
+      // lane gets keys key0 + g*PER + (t*4 + i), query r16
       #pragma unroll
       for (int t = 0; t < NT; ++t) {
         f32x4 sacc = (f32x4){0.f, 0.f, 0.f, 0.f};
         #pragma unroll
         for (int ds = 0; ds < DSTEPS; ++ds) sacc = mma16<T>(Kf[t][ds], Qf[qb][ds], sacc);
         #pragma unroll
-        for (int i = 0; i < 4; ++i) sv[t * 4 + i] = sacc[i] * scale;
+        for (int i = 0; i < 4; ++i) sv[qb][t * 4 + i] = sacc[i] * scale;
       }
       if (tail) {
         const int qi = q_base + qb * 16 + r16;
@@ -127,23 +130,16 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
             const int bit = key - L;
             vis = ((bit < 64 ? (mk_lo[qb] >> bit) : (mk_hi[qb] >> (bit - 64))) & 1ull) != 0ull;
           }
-          if (!vis || qi >= Tn) sv[j] = NEG_INF;
+          if (!vis || qi >= Tn) sv[qb][j] = NEG_INF;
         }
       }
-      // ---- online softmax for column (query) r16
-      float mx = sv[0];
       #pragma unroll
-      for (int j = 1; j < PER; ++j) mx = fmaxf(mx, sv[j]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-      const float mn = fmaxf(m_run[qb], mx);
-      corr_all[qb] = fast_exp2(m_run[qb] - mn);
-      float ls = 0.f;
-      #pragma unroll
-      for (int j = 0; j < PER; ++j) { pv_all[qb][j] = fast_exp2(sv[j] - mn); ls += pv_all[qb][j]; }
-      l_run[qb] = l_run[qb] * corr_all[qb] + ls;
-      m_run[qb] = mn;
+      for (int j = 0; j < PER; ++j) mx[qb] = fmaxf(mx[qb], sv[qb][j]);
     }
+  };
+  // probabilities of one step against the group's maximum, and O^T += V^T P^T
+  auto accumulate = [&](int st, uint4 (&Vf)[DB], const float (&sv)[NQB][PER]) {
+    const int key0 = st * KSTEP;
     if (key0 + KSTEP > n_keys) {
       // rows past L+T may hold anything (even NaN): zero their values so that 0 * V stays 0
       #pragma unroll
@@ -157,26 +153,57 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
     }
     #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
-      const uint4 Pf = pack16<T>(pv_all[qb]);
-      // ---- O^T += V^T P^T; on a wave's first step O is still zero and needs no rescaling
+      float pv[PER], ls = 0.f;
       #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        if (!first) O[qb][db] *= corr_all[qb];
-        O[qb][db] = mma16<T>(Vf[db], Pf, O[qb][db]);
-      }
+      for (int j = 0; j < PER; ++j) { pv[j] = fast_exp2(sv[qb][j] - m_run[qb]); ls += pv[j]; }
+      l_run[qb] += ls;
+      const uint4 Pf = pack16<T>(pv);
+      #pragma unroll
+      for (int db = 0; db < DB; ++db) O[qb][db] = mma16<T>(Vf[db], Pf, O[qb][db]);
     }
   };
 
   const int n_w = (st1 - (st0 + wave) + 3) / 4;        // key steps of this wave: st0 + wave, + 4, ...
   if (n_w > 0) {
-    uint4 KA[NT][DSTEPS], KB_[NT][DSTEPS];
     const int first = st0 + wave;
-    load_k(first, KA);
-    // the next step's index is clamped (it re-reads the last step) so that every iteration issues the same loads
-    math_step(first, first + 4 * min(1, n_w - 1), true, KA, KB_);
-    for (int i = 1; i < n_w; i += 2) {
-      math_step(first + 4 * i, first + 4 * min(i + 1, n_w - 1), false, KB_, KA);
-      if (i + 1 < n_w) math_step(first + 4 * (i + 1), first + 4 * min(i + 2, n_w - 1), false, KA, KB_);
+    auto step_of = [&](int i) { return first + 4 * min(i, n_w - 1); };
+    uint4 KA[NT][DSTEPS], KB_[NT][DSTEPS], VA_[DB], VB_[DB];
+    load_k(step_of(0), KA);
+    for (int i0 = 0; i0 < n_w; i0 += GS) {
+      float sv[GS][NQB][PER], mx[NQB];
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) mx[qb] = NEG_INF;
+      // ---- pass 1 (GS is even: step s of a group always finds its K fragments in the same register set)
+      #pragma unroll
+      for (int s = 0; s < GS; ++s) {
+        if (s & 1) load_k(step_of(i0 + s + 1), KA); else load_k(step_of(i0 + s + 1), KB_);
+        if (s == GS - 1) load_v(step_of(i0), VA_);
+        if (i0 + s < n_w) {
+          if (s & 1) scores(step_of(i0 + s), KB_, sv[s], mx); else scores(step_of(i0 + s), KA, sv[s], mx);
+        }
+      }
+      // ---- the group's maximum per query; rescale what earlier groups accumulated
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float m2 = fmaxf(mx[qb], __shfl_xor(mx[qb], 16, WAVE));
+        m2 = fmaxf(m2, __shfl_xor(m2, 32, WAVE));
+        const float mn = fmaxf(m_run[qb], m2);
+        if (i0 > 0) {
+          const float corr = fast_exp2(m_run[qb] - mn);
+          l_run[qb] *= corr;
+          #pragma unroll
+          for (int db = 0; db < DB; ++db) O[qb][db] *= corr;
+        }
+        m_run[qb] = mn;
+      }
+      // ---- pass 2
+      #pragma unroll
+      for (int s = 0; s < GS; ++s) {
+        if (s + 1 < GS) { if (s & 1) load_v(step_of(i0 + s + 1), VA_); else load_v(step_of(i0 + s + 1), VB_); }
+        if (i0 + s < n_w) {
+          if (s & 1) accumulate(step_of(i0 + s), VB_, sv[s]); else accumulate(step_of(i0 + s), VA_, sv[s]);
+        }
+      }
     }
   }
 
