@@ -59,9 +59,11 @@ def test_gemm_matches_oracle(cfg, M, N, Kd, split):
 
 
 # ---------------------------------------------------------------------------- A8 tree-masked attention
-def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None):
+def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None):
     K = len(caps)
     cfgx = si.with_(cfg, batch=B_, K=K, topk=min(16, max(caps)))
+    lens = [L] * B_ if lens is None else list(lens)      # committed rows per batch element (L = the largest)
+    assert max(lens) == L and len(lens) == B_
     max_kv = (L + T + 31) // 32 * 32 + 32
     ctx = make_ctx(cfgx, T=T, batch=B_, max_kv=max_kv)
     paths = si.tree_paths(T, caps)
@@ -75,11 +77,12 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None):
     # caches start as NaN everywhere outside the valid rows: nothing beyond L + T may leak in
     k_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
     v_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
-    k_rows[:, :, :L + T] = cfg_tensor_to_dev(k)
-    v_rows[:, :, :L + T] = cfg_tensor_to_dev(v)
+    for b in range(B_):                                   # element b uses rows [0, lens[b] + T) of its random rows
+        k_rows[b, :, :lens[b] + T] = cfg_tensor_to_dev(k)[b, :, :lens[b] + T]
+        v_rows[b, :, :lens[b] + T] = cfg_tensor_to_dev(v)[b, :, :lens[b] + T]
     kc, vc = D.keys_to_tiled(k_rows), D.values_to_tiled(v_rows)
     out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
-    kv_len = i32_to_dev(np.full(B_, L))
+    kv_len = i32_to_dev(np.asarray(lens))
     ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), kc, vc, kv_len, out)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
@@ -88,7 +91,8 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None):
     worst = 0.0
     for b in range(B_):
         for h in hs:
-            ref = orc.tree_attention(q.f32[b][:, h:h + 1], k.f32[b][h:h + 1], v.f32[b][h:h + 1], L, otree.mask)
+            n = lens[b] + T
+            ref = orc.tree_attention(q.f32[b][:, h:h + 1], k.f32[b][h:h + 1, :n], v.f32[b][h:h + 1, :n], lens[b], otree.mask)
             worst = max(worst, assert_rows_close(got[b][:, h], ref[:, 0], TOL[cfg.dtype], f"verify_attn b={b} h={h}"))
     return worst
 
@@ -110,8 +114,10 @@ def test_verify_attn_matches_oracle(cfg, T, caps, L):
 
 
 def test_verify_attn_batch_independent_lengths_share_a_launch():
-    say("verify_attn batch=3 (same L per element in this case; caches independent)")
-    verify_case(si.MINI, 64, (10,) * 4, 77, B_=3)
+    say("verify_attn batch=3, committed lengths 77 / 5 / 40 in one launch")
+    verify_case(si.MINI, 64, (10,) * 4, 77, B_=3, lens=[77, 5, 40])
+    say("verify_attn batch=2, one element with an empty cache")
+    verify_case(si.MINI, 35, (10,) * 4, 130, B_=2, lens=[0, 130])
 
 
 @pytest.mark.parametrize("cfg,T,caps,L,B_", [
