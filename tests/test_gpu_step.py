@@ -205,10 +205,12 @@ def check_target(cfg, refs, got, tol_scale=1.0):
         say(f"  b={b} nodes with an oracle top-1/top-2 gap below tolerance: {undecided}/{T}")
         # tree K/V rows written by every layer at rows [L, L+T)
         for li, lay in enumerate(r["layers"]):
-            kc = np_of(D.tiled_to_keys(got["k_caches"][li, b])[:, L:L + T])                    # [n_h, T, d_h]
+            # a row = one tree node's whole key (value) vector, i.e. one output row of the projection GEMM
+            per_node = lambda a: np.transpose(a, (1, 0, 2)).reshape(a.shape[1], -1)             # [n_h, T, d_h] -> [T, d]
+            kc = np_of(D.tiled_to_keys(got["k_caches"][li, b])[:, L:L + T])
             vc = np_of(D.tiled_to_values(got["v_caches"][li, b])[:, L:L + T])
-            assert_rows_close(kc, lay["k_new"], tol, f"layer {li} tree keys")
-            assert_rows_close(vc, lay["v_new"], tol, f"layer {li} tree values")
+            assert_rows_close(per_node(kc), per_node(lay["k_new"]), tol, f"layer {li} tree keys")
+            assert_rows_close(per_node(vc), per_node(lay["v_new"]), tol, f"layer {li} tree values")
 
 
 @pytest.mark.parametrize("tiled", [False, True], ids=["rowmajor", "tiled"])
