@@ -125,6 +125,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="vicuna7b", choices=["vicuna7b", "vicuna13b", "vicuna33b", "tiny", "mini_bf16"])
     ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
+    ap.add_argument("--batch", type=int, default=None, help="independent sequences per step (default: the configuration's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
     ap.add_argument("--row-major", action="store_true",
@@ -149,6 +150,8 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     cfg = si.CONFIGS[args.workload]
+    if args.batch is not None:
+        cfg = si.with_(cfg, batch=args.batch)
     n_layers = cfg.n_layers if args.layers is None else args.layers
     n_h, d_h, d, f, V, K, T, L, Ls, Bsz = (cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.d_ffn, cfg.vocab, cfg.K, cfg.T,
                                            cfg.kv_len, cfg.sal_len, cfg.batch)
