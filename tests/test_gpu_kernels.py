@@ -106,6 +106,9 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None):
     (si.MINI, 64, (10,) * 4, 1),
     (si.MINI, 96, (10,) * 5, 333),              # two query groups of three 16-query blocks
     (si.MINI, 35, (10,) * 4, 1000),
+    (si.MINI, 128, (10,) * 8, 64),              # the largest tree (eight 16-query blocks), depth 8
+    (si.MINI, 1, (4, 4, 4, 4), 96),             # the root alone = one-token decoding
+    (si.TINY, 1, (4, 4, 4, 4), 0),              # one query, one key (itself)
 ])
 def test_verify_attn_matches_oracle(cfg, T, caps, L):
     say(f"verify_attn {cfg.name} T={T} L={L}")
@@ -158,7 +161,10 @@ def test_verify_attn_flags_cache_overflow():
 
 
 # ---------------------------------------------------------------------------- A6 / A10 integer work
-@pytest.mark.parametrize("T,caps,B_", [(16, (4, 2, 2, 2), 1), (64, (10,) * 4, 1), (96, (10,) * 5, 4)])
+@pytest.mark.parametrize("T,caps,B_", [(16, (4, 2, 2, 2), 1), (64, (10,) * 4, 1), (96, (10,) * 5, 4),
+                                       (128, (10,) * 8, 2),        # the largest tree and the most heads the library takes
+                                       (1, (4, 4, 4, 4), 1),       # the root alone: nothing to accept
+                                       (5, (1, 1, 1, 1), 1)])      # a chain
 def test_tree_build_and_accept_are_bit_exact(T, caps, B_):
     say(f"tree_build/accept T={T} B={B_}")
     K = len(caps)

@@ -81,6 +81,20 @@ def test_draft_matches_oracle(cfg, sal_len):
     check_draft(cfgx, outs, got)
 
 
+def test_draft_most_heads_and_candidates():
+    """K = 8 heads and top-16 candidates: the largest values the library takes (five heads read the second
+    stage's state with K = 8; with K odd the extra head does, see the next case)."""
+    say("draft mini K=8 top-16")
+    cfgx, ctx, outs, got = run_draft(si.with_(si.MINI, K=8, topk=16))
+    check_draft(cfgx, outs, got)
+    say("draft tiny K=5 (odd: heads 1-2 read the first stage, 3-5 the second)")
+    cfgx, ctx, outs, got = run_draft(si.with_(si.TINY, K=5, topk=4))
+    check_draft(cfgx, outs, got)
+    say("draft tiny K=1")
+    cfgx, ctx, outs, got = run_draft(si.with_(si.TINY, K=1, topk=4))
+    check_draft(cfgx, outs, got)
+
+
 def test_draft_batch_of_two():
     say("draft mini batch=2")
     cfgx, ctx, outs, got = run_draft(si.MINI, Bsz=2)
