@@ -16,8 +16,7 @@ blocking, fusion, online softmax or reordering:
   * tree-attention verification      -- Sec. 2 "Tree Attention", Sec. 3.2 last paragraph
   * greedy acceptance                -- Sec. 2 "Speculative Decoding", Table 1 (Temperature = 0)
 
-Where the paper is silent the readings are (each also listed in the design
-notes): Llama-style decoder layers (pre-RMSNorm, half-split RoPE, SwiGLU, no
+Where the paper is silent the readings are: Llama-style decoder layers (pre-RMSNorm, half-split RoPE, SwiGLU, no
 biases) for both the target and the adaptation layers; h before e in the
 concat; MLP_k(h) = h + SiLU(W_k h); Eq. 5 is a bare multi-head attention
 sublayer (Wq, Wk, Wv, Wo; no mask, no RoPE, no residual, no norm); one LM head
@@ -53,8 +52,8 @@ def _f(a) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
-# Llama-style building blocks (reading of "causal Transformer Decoder layers
-# built upon the target model", Fig. 2 caption)
+# Llama-style building blocks (Fig. 2's caption says the adaptation layers are causal decoder
+# layers of the target's kind; read here as the target's own layer shape)
 # ----------------------------------------------------------------------------
 def rmsnorm(x: np.ndarray, w: np.ndarray, eps: float) -> np.ndarray:
     x = _f(x)

@@ -3,7 +3,7 @@
 The GPU path keeps the residual stream in float32 but hands the matrix cores bf16 activations at five
 points of a decoder layer: the two normalised inputs, q/k/v, the attention output and the SwiGLU
 product.  This test rounds the oracle's float64 values at exactly those points and compares with the
-unrounded oracle.  It pins the statement of the design notes that this inherent noise is a few 1e-3 per
+unrounded oracle.  It pins the fact the bf16 tolerance rests on: this inherent noise is a few 1e-3 per
 layer at small widths (it grows with width: 1.4e-2 at d 6656 / FFN 17920 / 96 rows, measured once with the
 same code), i.e. the same order as the 2e-2 bound the parity tests use."""
 import numpy as np
