@@ -222,18 +222,34 @@ def draft(dw: Dict[str, object], h_t: np.ndarray, tok: int, sal_k: List[np.ndarr
     dw holds float arrays: embed [V,d], fc [2][d,2d], sal [2]{layer}, mlp [K,d,d],
     pe [K,d], aeb_wq/wk/wv/wo [d,d], lm_head [V,d].  sal_k[s], sal_v[s] are the
     committed rows [n_heads, L_s, d_h] of stage s.
+
+    The structural variants of the paper's ablations are read off dw:
+      * one adaptation layer for all heads (Sec. 4.3, variant 4): len(dw["sal"]) == 1, every head reads h^1;
+      * no position encoding (variant 2): dw["pe"] is None;
+      * two self-attention layers in the Auto-embedding Block (Appendix, the "alpha" model): dw["aeb2_wq"]
+        .. dw["aeb2_wo"] present; the second layer reads the first one's output;
+      * LoRA-like LM head (Appendix): dw["lm_a"] [r,d] and dw["lm_b"] [V,r] present; logits = lm_b (lm_a x).
     """
     e = _f(dw["embed"][tok])
     out: Dict[str, object] = {"x": [], "h": [], "k_new": [], "v_new": []}
     u = _f(h_t)
-    for s in range(2):
+    n_stages = len(dw["sal"])
+    for s in range(n_stages):
         x = fc_concat(dw["fc"][s], u, e)
         h, k_new, v_new = sal_stage(x, dw["sal"][s], sal_k[s], sal_v[s], n_heads, eps, theta)
         out["x"].append(x); out["h"].append(h); out["k_new"].append(k_new); out["v_new"].append(v_new)
         u = h
-    Hp = head_inputs(out["h"][0], out["h"][1], dw["mlp"], dw["pe"])
+    K, d = dw["mlp"].shape[0], dw["mlp"].shape[1]
+    pe = dw.get("pe")
+    Hp = head_inputs(out["h"][0], out["h"][-1], dw["mlp"], np.zeros((K, d)) if pe is None else pe)
     attn_o = bi_self_attention(Hp, dw["aeb_wq"], dw["aeb_wk"], dw["aeb_wv"], dw["aeb_wo"], n_heads)
-    logits, idx, val = lm_head_topk(dw["lm_head"], attn_o, topk)
+    if dw.get("aeb2_wq") is not None:
+        attn_o = bi_self_attention(attn_o, dw["aeb2_wq"], dw["aeb2_wk"], dw["aeb2_wv"], dw["aeb2_wo"], n_heads)
+    if dw.get("lm_a") is not None:
+        low = linear(dw["lm_a"], attn_o)                       # [K, r]
+        logits, idx, val = lm_head_topk(dw["lm_b"], low, topk)
+    else:
+        logits, idx, val = lm_head_topk(dw["lm_head"], attn_o, topk)
     out.update(Hp=Hp, attn_o=attn_o, logits=logits, topk_idx=idx, topk_val=val)
     return out
 

@@ -313,6 +313,38 @@ def test_commit_rows_keeps_the_path_in_order():
     assert np.array_equal(out[:, 4], new[:, 2]) and np.array_equal(out[:, 5], new[:, 5])
 
 
+def test_structural_variants_of_the_draft_reduce_to_known_cases():
+    """The ablation variants (Sec. 4.3; Appendix) are switches on the same formulas; each is pinned to a case whose
+    answer is known without running the variant's own code path."""
+    cfg, dw, tw = tiny_setup(seed=4)
+    rng = np.random.default_rng(12)
+    n_h, d_h, d, K = cfg.n_heads, cfg.head_dim, cfg.d_model, 4
+    sal_k = [rng.standard_normal((n_h, 6, d_h)) for _ in range(2)]
+    sal_v = [rng.standard_normal((n_h, 6, d_h)) for _ in range(2)]
+    h, tok = rng.standard_normal(d), 5
+    run = lambda w: orc.draft(w, h, tok, sal_k, sal_v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    base = run(dw)
+    # no position encoding == a zero position encoding
+    a = run({**dw, "pe": None}); b = run({**dw, "pe": np.zeros_like(dw["pe"])})
+    assert np.array_equal(a["logits"], b["logits"]) and not np.allclose(a["logits"], base["logits"])
+    # one adaptation layer: the first stage is the full model's first stage, and every head reads its output
+    one = run({**dw, "sal": dw["sal"][:1], "fc": dw["fc"][:1]})
+    assert np.array_equal(one["h"][0], base["h"][0]) and len(one["h"]) == 1
+    for k in range(K):
+        want = orc.head_mlp(dw["mlp"][k], base["h"][0]) + dw["pe"][k]
+        assert np.allclose(one["Hp"][k], want, rtol=0, atol=1e-12)
+    # second self-attention layer with Wq = Wk = 0 (uniform attention) and Wv = Wo = I: every row becomes the mean
+    I, Z = np.eye(d), np.zeros((d, d))
+    al = run({**dw, "aeb2_wq": Z, "aeb2_wk": Z, "aeb2_wv": I, "aeb2_wo": I})
+    assert np.allclose(al["attn_o"], np.broadcast_to(base["attn_o"].mean(axis=0), (K, d)), rtol=0, atol=1e-12)
+    # low-rank head: with r = d and lm_a = I it is the full head; in general it is the head lm_b @ lm_a
+    lo = run({**dw, "lm_a": I, "lm_b": dw["lm_head"]})
+    assert np.allclose(lo["logits"], base["logits"], rtol=0, atol=1e-10)
+    A, Bm = rng.standard_normal((8, d)), rng.standard_normal((cfg.vocab, 8))
+    lo = run({**dw, "lm_a": A, "lm_b": Bm}); full = run({**dw, "lm_head": Bm @ A})
+    assert np.allclose(lo["logits"], full["logits"], rtol=0, atol=1e-9)
+
+
 def test_draft_step_shapes_and_cache_rows():
     cfg, dw, tw = tiny_setup(seed=2)
     rng = np.random.default_rng(9)
