@@ -130,6 +130,10 @@ def main():
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
     ap.add_argument("--row-major", action="store_true",
                     help="feed the target's GEMMs the row-major matrices instead of their tiled copies (slower; for comparison)")
+    ap.add_argument("--aeb-layers", type=int, default=1, choices=[1, 2], help="self-attention layers in the Auto-embedding Block (2 = the alpha variant)")
+    ap.add_argument("--lm-rank", type=int, default=0, help="rank of the low-rank LM head of the draft (0 = full head)")
+    ap.add_argument("--one-stage", action="store_true", help="one adaptation layer for all heads")
+    ap.add_argument("--no-pe", action="store_true", help="no position encoding")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming copy (read 256 MiB, write 256 MiB) so that a counter run can "
                          "scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -173,6 +177,16 @@ def main():
     dw = dict(embed=randn((V, d), 0.02), fc=[randn((d, 2 * d), 0.02) for _ in range(2)], sal=[layer() for _ in range(2)],
               mlp=randn((K, d, d), 0.02), pe=randn((K, d), 0.02), aeb_wq=randn((d, d), 0.02), aeb_wk=randn((d, d), 0.02),
               aeb_wv=randn((d, d), 0.02), aeb_wo=randn((d, d), 0.02), lm_head=randn((V, d), 0.02))
+    n_stages = 1 if args.one_stage else 2
+    if args.one_stage:
+        dw["sal"], dw["fc"] = dw["sal"][:1], dw["fc"][:1]
+    if args.no_pe:
+        dw["pe"] = None
+    if args.aeb_layers == 2:
+        for k in ("wq", "wk", "wv", "wo"):
+            dw["aeb2_" + k] = randn((d, d), 0.02)
+    if args.lm_rank:
+        dw["lm_a"], dw["lm_b"], dw["lm_head"] = randn((args.lm_rank, d), 0.02), randn((V, args.lm_rank), 0.02), None
     layers = [layer() for _ in range(n_layers)]
     final_norm = torch.ones(d, dtype=tdt, device=dev)
     t_lm_head = randn((V, d), 0.02)
@@ -189,7 +203,8 @@ def main():
     log(f"[bench] {args.workload}: {n_layers} layers, weights on device in {time.time() - t0:.1f}s")
 
     ctx = B.Context(d_model=d, n_heads=n_h, head_dim=d_h, d_ffn=f, vocab=V, K=K, topk=cfg.topk, max_tree=T, max_kv=max_kv,
-                    batch=Bsz, dtype=D.dtype_code(cfg.dtype), rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, device=dev)
+                    batch=Bsz, dtype=D.dtype_code(cfg.dtype), rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, device=dev,
+                    n_stages=n_stages, aeb_layers=args.aeb_layers, lm_rank=args.lm_rank)
     tree = B.Tree(si.tree_paths(T, cfg.tree_caps), K)
     dstruct = B.Context.draft_struct(dw)
     structs = [B.Context.layer_struct(l) for l in layers]
@@ -295,7 +310,9 @@ def main():
         "config": {"workload": f"{args.workload} full step: draft (K={K}, top-{cfg.topk}, SAL cache {Ls}) + {n_layers}-layer "
                                f"tree verification (T={T}, L={L}) + greedy accept, batch {Bsz}",
                    "layers": n_layers, "tree_nodes": T, "kv_len": L, "batch": Bsz,
-                   "target_weight_layout": "row-major" if args.row_major else "tiled"},
+                   "target_weight_layout": "row-major" if args.row_major else "tiled",
+                   "draft_variant": {"adaptation_layers": n_stages, "position_encoding": not args.no_pe,
+                                     "self_attention_layers": args.aeb_layers, "lm_head_rank": args.lm_rank or "full"}},
         "step_algorithmic_GB": sb / 1e9,
         "step_hbm_frac": sb * steps_per_s / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -55,6 +55,10 @@ typedef struct amph_config {
   int32_t dtype;             /* AMPH_F32 | AMPH_BF16                                               */
   float rms_eps;             /* RMSNorm epsilon                                                    */
   float rope_theta;          /* RoPE base; pairs are (i, i + head_dim/2)                           */
+  /* structural variants of the paper's ablations (Sec. 4.3; Appendix); the method itself is 2, 1, 0 */
+  int32_t n_stages;          /* adaptation layers: 2, or 1 = one layer whose output every head reads */
+  int32_t aeb_layers;        /* self-attention layers in the Auto-embedding Block: 1, or 2 ("alpha")  */
+  int32_t lm_rank;           /* 0 = full LM head; r > 0 (multiple of 8) = low-rank pair lm_a, lm_b    */
 } amph_config;
 
 /* One Llama-style decoder layer (pre-RMSNorm, RoPE, SwiGLU, no biases); all T. */
@@ -89,6 +93,10 @@ typedef struct amph_draft_w {
   const void *pe;           /* [K, d]  positional embedding of Eq. 4                                */
   const void *aeb_wq, *aeb_wk, *aeb_wv, *aeb_wo; /* [d, d] self-attention of Eq. 5                  */
   const void *lm_head;      /* [V, d]  LM head of Eq. 6, shared by the K positions                  */
+  /* variants: pe may be NULL (no position encoding); with n_stages = 1 only fc[0] and sal[0] are read;    */
+  const void *aeb2_wq, *aeb2_wk, *aeb2_wv, *aeb2_wo; /* [d, d] second self-attention layer (aeb_layers = 2) */
+  const void *lm_a;         /* [lm_rank, d]  low-rank LM head: logits = lm_b (lm_a x); lm_head is then unused */
+  const void *lm_b;         /* [V, lm_rank]                                                          */
 } amph_draft_w;
 
 typedef struct amph_ctx amph_ctx;

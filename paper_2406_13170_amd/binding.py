@@ -25,7 +25,8 @@ STATUS_NAMES = {0: "AMPH_OK", 1: "AMPH_EINVAL", 2: "AMPH_ESHAPE", 3: "AMPH_ETREE
 
 class amph_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d_model", "n_heads", "head_dim", "d_ffn", "vocab", "K", "topk", "max_tree",
-                                         "max_kv", "batch", "dtype")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)]
+                                         "max_kv", "batch", "dtype")] + [("rms_eps", C.c_float), ("rope_theta", C.c_float)] + \
+               [(n, C.c_int32) for n in ("n_stages", "aeb_layers", "lm_rank")]
 
 
 class amph_layer_w(C.Structure):
@@ -42,7 +43,8 @@ AMPH_PACK_QKV, AMPH_PACK_WO, AMPH_PACK_GATEUP, AMPH_PACK_DOWN, AMPH_PACK_LMHEAD 
 class amph_draft_w(C.Structure):
     _fields_ = [("embed", C.c_void_p), ("fc", C.c_void_p * 2), ("sal", amph_layer_w * 2), ("mlp", C.c_void_p),
                 ("pe", C.c_void_p), ("aeb_wq", C.c_void_p), ("aeb_wk", C.c_void_p), ("aeb_wv", C.c_void_p),
-                ("aeb_wo", C.c_void_p), ("lm_head", C.c_void_p)]
+                ("aeb_wo", C.c_void_p), ("lm_head", C.c_void_p), ("aeb2_wq", C.c_void_p), ("aeb2_wk", C.c_void_p),
+                ("aeb2_wv", C.c_void_p), ("aeb2_wo", C.c_void_p), ("lm_a", C.c_void_p), ("lm_b", C.c_void_p)]
 
 
 EXPORTS = {
@@ -157,9 +159,10 @@ class Context:
     """amph_ctx handle plus the caller-owned workspace (a torch uint8 tensor on the device)."""
 
     def __init__(self, *, d_model, n_heads, head_dim, d_ffn, vocab, K, topk, max_tree, max_kv, batch, dtype,
-                 rms_eps=1e-6, rope_theta=10000.0, device="cuda:0", alloc_workspace=True):
+                 rms_eps=1e-6, rope_theta=10000.0, n_stages=2, aeb_layers=1, lm_rank=0, device="cuda:0",
+                 alloc_workspace=True):
         self.cfg = amph_config(d_model, n_heads, head_dim, d_ffn, vocab, K, topk, max_tree, max_kv, batch, dtype,
-                               rms_eps, rope_theta)
+                               rms_eps, rope_theta, n_stages, aeb_layers, lm_rank)
         h = C.c_void_p()
         st = lib().amph_create(C.byref(self.cfg), C.byref(h))
         if st != AMPH_OK:
@@ -209,11 +212,13 @@ class Context:
     def draft_struct(dw: Dict[str, object]) -> amph_draft_w:
         s = amph_draft_w()
         s.embed = _ptr(dw["embed"])
-        s.fc[0], s.fc[1] = _ptr(dw["fc"][0]), _ptr(dw["fc"][1])
-        s.sal[0], s.sal[1] = Context.layer_struct(dw["sal"][0]), Context.layer_struct(dw["sal"][1])
-        s.mlp, s.pe = _ptr(dw["mlp"]), _ptr(dw["pe"])
+        for i, (fc, sal) in enumerate(zip(dw["fc"], dw["sal"])):      # one entry each for the one-adaptation-layer variant
+            s.fc[i], s.sal[i] = _ptr(fc), Context.layer_struct(sal)
+        s.mlp, s.pe = _ptr(dw["mlp"]), _ptr(dw.get("pe"))
         s.aeb_wq, s.aeb_wk, s.aeb_wv, s.aeb_wo = (_ptr(dw[k]) for k in ("aeb_wq", "aeb_wk", "aeb_wv", "aeb_wo"))
-        s.lm_head = _ptr(dw["lm_head"])
+        s.lm_head = _ptr(dw.get("lm_head"))
+        s.aeb2_wq, s.aeb2_wk, s.aeb2_wv, s.aeb2_wo = (_ptr(dw.get(k)) for k in ("aeb2_wq", "aeb2_wk", "aeb2_wv", "aeb2_wo"))
+        s.lm_a, s.lm_b = _ptr(dw.get("lm_a")), _ptr(dw.get("lm_b"))
         return s
 
     # -- the calls of include/amph.h

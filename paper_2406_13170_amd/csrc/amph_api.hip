@@ -139,7 +139,7 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   float *x = F(ctx->ws.x), *q = F(ctx->ws.q), *att = F(ctx->ws.att), *y = F(ctx->ws.y), *act = F(ctx->ws.act);
   float *h[2] = {F(ctx->ws.h[0]), F(ctx->ws.h[1])};
   const size_t stage_stride = (size_t)B * 2 * n_h * c.max_kv * d_h;      // elements of T
-  for (int s = 0; s < 2; ++s) {
+  for (int s = 0; s < c.n_stages; ++s) {
     const float *u = (s == 0) ? h_new : h[0];
     void *kv_stage = (T *)sal_kv + s * stage_stride;
     PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, M, x, ctx->dev_status));
@@ -150,35 +150,59 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, M, c.rms_eps, act));
     PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, M, y, h[s], nullptr, nullptr, d));
   }
-  // the heads (Eq. 2-6) read the last live position of every batch element
-  const float *h1 = h[0], *h2 = h[1];
+  // the heads (Eq. 2-6) read the last live position of every batch element; with one adaptation layer every
+  // head reads that layer's output
+  const float *h1 = h[0], *h2 = h[c.n_stages - 1];
   if (R > 1) {
     HIP_TRY(ctx, launch_gather_rows(st, h[0], B, R, d, n_valid, x));
-    HIP_TRY(ctx, launch_gather_rows(st, h[1], B, R, d, n_valid, y));
-    h1 = x; h2 = y;
+    h1 = h2 = x;
+    if (c.n_stages == 2) {
+      HIP_TRY(ctx, launch_gather_rows(st, h[1], B, R, d, n_valid, y));
+      h2 = y;
+    }
   }
   float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);
   float *attn_o = F(ctx->ws.attn_o);
   float *lg = logits ? logits : F(ctx->ws.logits);
   PROF_TRY(ctx, AMPH_K_HEAD_MLP, launch_head_mlp<T>(st, w->mlp, w->pe, h1, h2, d, K, B, Hp));
   const int BK = B * K;
-  for (int r0 = 0; r0 < BK; r0 += 8) {
-    const int m = std::min(8, BK - r0);
-    const size_t o = (size_t)r0 * d;
-    PROF_TRY(ctx, AMPH_K_AEB_QKV, launch_linear<T>(st, w->aeb_wq, w->aeb_wk, w->aeb_wv, 3, d, d, Hp + o, d, m, nullptr, Qa + o, Ka + o,
-                                  Va + o, d));
+  // Eq. 5, once or twice: q/k/v projections of the K rows, K x K attention per head, output projection
+  auto self_attention = [&](const void *wq, const void *wk, const void *wv, const void *wo, const float *in,
+                            float *out_rows) -> amph_status {
+    for (int r0 = 0; r0 < BK; r0 += 8) {
+      const int m = std::min(8, BK - r0);
+      const size_t o = (size_t)r0 * d;
+      PROF_TRY(ctx, AMPH_K_AEB_QKV, launch_linear<T>(st, wq, wk, wv, 3, d, d, in + o, d, m, nullptr, Qa + o, Ka + o, Va + o, d));
+    }
+    PROF_TRY(ctx, AMPH_K_AEB_ATTN, launch_aeb_attn(st, Qa, Ka, Va, B, K, n_h, d_h, ctxa));
+    for (int r0 = 0; r0 < BK; r0 += 8) {
+      const int m = std::min(8, BK - r0);
+      const size_t o = (size_t)r0 * d;
+      PROF_TRY(ctx, AMPH_K_AEB_WO, launch_linear<T>(st, wo, nullptr, nullptr, 1, d, d, ctxa + o, d, m, nullptr, out_rows + o,
+                                    nullptr, nullptr, d));
+    }
+    return AMPH_OK;
+  };
+  if (amph_status s1 = self_attention(w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, Hp, attn_o)) return s1;
+  const float *head_in = attn_o;
+  if (c.aeb_layers == 2) {                 // the second layer reads the first one's output; Hp is free by now
+    if (amph_status s2 = self_attention(w->aeb2_wq, w->aeb2_wk, w->aeb2_wv, w->aeb2_wo, attn_o, Hp)) return s2;
+    head_in = Hp;
   }
-  PROF_TRY(ctx, AMPH_K_AEB_ATTN, launch_aeb_attn(st, Qa, Ka, Va, B, K, n_h, d_h, ctxa));
-  for (int r0 = 0; r0 < BK; r0 += 8) {
-    const int m = std::min(8, BK - r0);
-    const size_t o = (size_t)r0 * d;
-    PROF_TRY(ctx, AMPH_K_AEB_WO, launch_linear<T>(st, w->aeb_wo, nullptr, nullptr, 1, d, d, ctxa + o, d, m, nullptr, attn_o + o, nullptr,
-                                  nullptr, d));
+  const void *lm_w = w->lm_head;
+  int lm_k = d;
+  if (c.lm_rank > 0) {                      // low-rank head: [K rows, r] = lm_a x first, then the [V, r] matrix
+    for (int r0 = 0; r0 < BK; r0 += 8) {
+      const int m = std::min(8, BK - r0);
+      PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, w->lm_a, nullptr, nullptr, 1, c.lm_rank, d, head_in + (size_t)r0 * d, d, m,
+                                    nullptr, Qa + (size_t)r0 * c.lm_rank, nullptr, nullptr, c.lm_rank));
+    }
+    head_in = Qa; lm_w = w->lm_b; lm_k = c.lm_rank;
   }
   for (int r0 = 0; r0 < BK; r0 += 8) {
     const int m = std::min(8, BK - r0);
-    PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, w->lm_head, nullptr, nullptr, 1, V, d, attn_o + (size_t)r0 * d, d, m, nullptr,
-                                  lg + (size_t)r0 * V, nullptr, nullptr, V));
+    PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, lm_w, nullptr, nullptr, 1, V, lm_k, head_in + (size_t)r0 * lm_k, lm_k, m,
+                                  nullptr, lg + (size_t)r0 * V, nullptr, nullptr, V));
   }
   PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, R, n_valid, F(ctx->ws.topk_ws)));
   return AMPH_OK;
@@ -284,6 +308,8 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
   if (c.K > AMPH_MAX_HEADS_K || c.topk > AMPH_MAX_TOPK || c.topk > c.vocab || c.max_tree > AMPH_MAX_TREE) return AMPH_ESHAPE;
   if (c.max_kv % 32 || c.max_kv < c.max_tree) return AMPH_ESHAPE;
   if (c.vocab > 65536 || c.batch > 64 || (long long)c.batch * c.n_heads > 1000) return AMPH_ESHAPE;
+  if ((c.n_stages != 1 && c.n_stages != 2) || (c.aeb_layers != 1 && c.aeb_layers != 2)) return AMPH_EINVAL;
+  if (c.lm_rank < 0 || c.lm_rank % 8 || c.lm_rank > c.d_model) return AMPH_ESHAPE;
   amph_ctx *ctx = new (std::nothrow) amph_ctx();
   if (!ctx) return AMPH_EINVAL;
   ctx->cfg = c;
@@ -334,11 +360,20 @@ amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     return fail(ctx, AMPH_EINVAL, "amph_draft: null argument");
   if (n_new < 1 || (long long)n_new * ctx->cfg.batch > 8)
     return fail(ctx, AMPH_ESHAPE, "amph_draft: need 1 <= n_new and batch * n_new <= 8");
-  const void *ptrs[] = {w->embed, w->fc[0], w->fc[1], w->mlp, w->pe, w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, w->lm_head,
-                        h_new, sal_kv, workspace};
+  const amph_config &cf = ctx->cfg;
+  const void *ptrs[] = {w->embed, w->fc[0], w->mlp, w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, h_new, sal_kv, workspace};
   for (const void *p : ptrs)
     if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_draft: null or misaligned (16 B) pointer");
-  for (int s = 0; s < 2; ++s) {
+  if (!aligned16(w->pe)) return fail(ctx, AMPH_EINVAL, "amph_draft: misaligned position encoding");
+  if (cf.n_stages == 2 && (!w->fc[1] || !aligned16(w->fc[1]))) return fail(ctx, AMPH_EINVAL, "amph_draft: fc[1] missing");
+  if (cf.aeb_layers == 2) {
+    const void *p2[] = {w->aeb2_wq, w->aeb2_wk, w->aeb2_wv, w->aeb2_wo};
+    for (const void *p : p2)
+      if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_draft: second self-attention layer missing or misaligned");
+  }
+  if (cf.lm_rank > 0 ? (!w->lm_a || !w->lm_b || !aligned16(w->lm_a) || !aligned16(w->lm_b)) : (!w->lm_head || !aligned16(w->lm_head)))
+    return fail(ctx, AMPH_EINVAL, "amph_draft: LM head (or its low-rank pair) missing or misaligned");
+  for (int s = 0; s < cf.n_stages; ++s) {
     const amph_layer_w &l = w->sal[s];
     const void *lp[] = {l.rms1, l.wq, l.wk, l.wv, l.wo, l.rms2, l.w_gate, l.w_up, l.w_down};
     for (const void *p : lp)

@@ -433,7 +433,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
       for (int r = 0; r < GV_R; ++r) {
         const int n = gl * GV_R + r;
         if (n < d) {
-          const float pek = Elem<T>::to_f32(pe[(size_t)k * d + n]);
+          const float pek = pe ? Elem<T>::to_f32(pe[(size_t)k * d + n]) : 0.f;     // no position encoding: PE = 0
           #pragma unroll
           for (int m = 0; m < M; ++m)
             if (m < m_valid) Hp[((size_t)m * K + k) * d + n] = src[(size_t)m * d + n] + silu_f(acc[r][m]) + pek;

@@ -23,10 +23,11 @@ def say(msg: str):
     sys.stdout.flush()
 
 
-def make_ctx(cfg: si.Config, T: int | None = None, batch: int | None = None, max_kv: int | None = None) -> B.Context:
+def make_ctx(cfg: si.Config, T: int | None = None, batch: int | None = None, max_kv: int | None = None, **variant) -> B.Context:
+    """variant: n_stages, aeb_layers, lm_rank (the structural switches of amph_config)."""
     return B.Context(d_model=cfg.d_model, n_heads=cfg.n_heads, head_dim=cfg.head_dim, d_ffn=cfg.d_ffn, vocab=cfg.vocab,
                      K=cfg.K, topk=cfg.topk, max_tree=T or cfg.T, max_kv=max_kv or cfg.max_kv, batch=batch or cfg.batch,
-                     dtype=D.dtype_code(cfg.dtype), rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, device=DEV)
+                     dtype=D.dtype_code(cfg.dtype), rms_eps=cfg.rms_eps, rope_theta=cfg.rope_theta, device=DEV, **variant)
 
 
 def rowwise_ok(got: np.ndarray, ref: np.ndarray, tol: float):

@@ -16,14 +16,60 @@ pytestmark = pytest.mark.gpu
 
 
 # ---------------------------------------------------------------------------- amph_draft (A1-A5)
-def run_draft(cfg: si.Config, seed=0, Bsz=1, sal_len=None):
+def apply_variant(cfg, dw, seed, variant):
+    """The ablation variants as changes of the weight dictionary (synth_inputs tensors) + amph_config switches."""
+    dw = dict(dw)
+    sw = {}
+    d, V = cfg.d_model, cfg.vocab
+    if variant.get("one_stage"):
+        dw["sal"], dw["fc"] = dw["sal"][:1], dw["fc"][:1]
+        sw["n_stages"] = 1
+    if variant.get("no_pe"):
+        dw["pe"] = None
+    if variant.get("alpha"):
+        for k in ("wq", "wk", "wv", "wo"):
+            dw["aeb2_" + k] = si.normal(cfg, seed, "draft.aeb2." + k, (d, d), si.W_STD)
+        sw["aeb_layers"] = 2
+    if variant.get("lm_rank"):
+        r = variant["lm_rank"]
+        dw["lm_a"] = si.normal(cfg, seed, "draft.lm_a", (r, d), si.W_STD)
+        dw["lm_b"] = si.normal(cfg, seed, "draft.lm_b", (V, r), si.W_STD)
+        dw["lm_head"] = None
+        sw["lm_rank"] = r
+    return dw, sw
+
+
+def variant_to_device(dw):
+    out = {}
+    for k, v in dw.items():
+        if v is None:
+            out[k] = None
+        elif k == "sal":
+            out[k] = [D.layer_to_device(l, DEV) for l in v]
+        elif k == "fc":
+            out[k] = [D.to_device(x, DEV) for x in v]
+        else:
+            out[k] = D.to_device(v, DEV)
+    return out
+
+
+def variant_f32(dw):
+    f = lambda t: None if t is None else t.f32
+    return {k: ([{kk: vv.f32 for kk, vv in l.items()} for l in v] if k == "sal" else [x.f32 for x in v] if k == "fc" else f(v))
+            for k, v in dw.items()}
+
+
+def run_draft(cfg: si.Config, seed=0, Bsz=1, sal_len=None, variant=None):
     cfg = si.with_(cfg, batch=Bsz)
     Ls = cfg.sal_len if sal_len is None else sal_len
     n_h, d_h, d, V, K = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab, cfg.K
     max_kv = (max(Ls + 1, cfg.T) + 31) // 32 * 32
-    ctx = make_ctx(cfg, batch=Bsz, max_kv=max_kv)
     dw = si.draft_weights(cfg, seed)
-    dwd = D.draft_to_device(dw, DEV)
+    sw = {}
+    if variant:
+        dw, sw = apply_variant(cfg, dw, seed, variant)
+    ctx = make_ctx(cfg, batch=Bsz, max_kv=max_kv, **sw)
+    dwd = variant_to_device(dw) if variant else D.draft_to_device(dw, DEV)
     dstruct = B.Context.draft_struct(dwd)
     h = si.as_f32_exact(cfg, seed, "draft.h_t", (Bsz, d), 1.0)
     tok = si.tokens(cfg, seed, "draft.tok", (Bsz,))
@@ -42,7 +88,7 @@ def run_draft(cfg: si.Config, seed=0, Bsz=1, sal_len=None):
     ctx.amph_draft(dstruct, f32_to_dev(h), i32_to_dev(tok), sal_kv, sal_len_d, topk_idx, topk_val, logits)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
-    dwo = draft_f32(dw)
+    dwo = variant_f32(dw) if variant else draft_f32(dw)
     outs = []
     for b in range(Bsz):
         o = orc.draft(dwo, h[b], int(tok[b]), [sal_k[s].f32[b] for s in range(2)], [sal_v[s].f32[b] for s in range(2)],
@@ -52,7 +98,7 @@ def run_draft(cfg: si.Config, seed=0, Bsz=1, sal_len=None):
                                 sal_kv=sal_kv, sal_len=np_of(sal_len_d), Ls=Ls, keep=(dwd, dstruct))
 
 
-def check_draft(cfg, outs, got):
+def check_draft(cfg, outs, got, n_stages=2):
     tol = TOL[cfg.dtype]
     Ls = got["Ls"]
     for b, o in enumerate(outs):
@@ -66,11 +112,13 @@ def check_draft(cfg, outs, got):
             np.testing.assert_allclose(got["topk_val"][b, k], got["logits"][b, k][got["topk_idx"][b, k]], rtol=0, atol=0)
             assert np.all(np.diff(got["topk_val"][b, k]) <= 0)
         # the new cache rows (keys after RoPE at position Ls, values) of both stages
-        for s in range(2):
+        for s in range(n_stages):
             kc = np_of(got["sal_kv"][s, b, 0, :, Ls])
             vc = np_of(got["sal_kv"][s, b, 1, :, Ls])
             assert_rows_close(kc, o["k_new"][s], tol, f"SAL{s + 1} new key row")
             assert_rows_close(vc, o["v_new"][s], tol, f"SAL{s + 1} new value row")
+        if n_stages == 1:                              # the second stage's cache is never touched
+            assert torch.isnan(got["sal_kv"][1, b, :, :, Ls].float()).all()
     assert np.all(got["sal_len"] == Ls + 1)
 
 
@@ -93,6 +141,17 @@ def test_draft_most_heads_and_candidates():
     say("draft tiny K=1")
     cfgx, ctx, outs, got = run_draft(si.with_(si.TINY, K=1, topk=4))
     check_draft(cfgx, outs, got)
+
+
+@pytest.mark.parametrize("cfg", [si.TINY, si.MINI])
+@pytest.mark.parametrize("variant", [dict(one_stage=True), dict(no_pe=True), dict(alpha=True), dict(lm_rank=64),
+                                     dict(one_stage=True, no_pe=True, alpha=True, lm_rank=256)],
+                         ids=["one-adaptation-layer", "no-position-encoding", "two-attention-layers", "low-rank-head", "all-four"])
+def test_draft_structural_variants(cfg, variant):
+    """The ablation variants of Sec. 4.3 and the Appendix as configuration switches."""
+    say(f"draft {cfg.name} variant {variant}")
+    cfgx, ctx, outs, got = run_draft(cfg, variant=variant)
+    check_draft(cfgx, outs, got, n_stages=1 if variant.get("one_stage") else 2)
 
 
 def test_draft_batch_of_two():
