@@ -237,6 +237,14 @@ typedef enum { AMPH_PACK_QKV = 0, AMPH_PACK_WO, AMPH_PACK_GATEUP, AMPH_PACK_DOWN
 amph_status amph_tiled_bytes(const amph_ctx *ctx, int role, size_t *bytes /* host */);
 amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const void *w1, const void *w2, void *dst);
 
+/* ---- choice of the verification-attention kernel, for tests and measurements -----------------------
+ * The tree attention (amph_verify_attn, and inside amph_target_forward) has two kernels with the same
+ * arithmetic: one feeds the matrix cores from registers (lowest fixed cost, short key ranges), one streams
+ * the caches through a ring of LDS stages (long key ranges, many (batch, head) pairs).  kernel = -1 (the
+ * default) chooses by shape; 0 and 1 force the first or the second for every later call on this context.
+ * The workspace is sized for either.  Returns AMPH_EINVAL for any other value. */
+amph_status amph_verify_kernel(amph_ctx *ctx, int kernel);
+
 /* ---- per-kernel timing, for measurement ------------------------------------------------------------
  * Every kernel launch inside amph_draft / amph_target_forward / amph_verify_attn belongs to one kind.
  * amph_profile_kind selects one kind (or -1 for none): from then on one launch in `every` (>= 1; the

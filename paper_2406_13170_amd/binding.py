@@ -67,6 +67,7 @@ EXPORTS = {
                             + [C.c_void_p] * 13),
     "amph_tiled_bytes": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]),
     "amph_pack_weights": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "amph_verify_kernel": (C.c_int, [C.c_void_p, C.c_int]),
     "amph_profile_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int]),
     "amph_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     "amph_gemv": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]),
@@ -268,6 +269,9 @@ class Context:
 
     def amph_pack_weights(self, role: int, w0, w1, w2, dst):
         self._check(lib().amph_pack_weights(self.handle, role, _ptr(w0), _ptr(w1), _ptr(w2), _ptr(dst)), "amph_pack_weights")
+
+    def amph_verify_kernel(self, kernel: int):
+        self._check(lib().amph_verify_kernel(self.handle, kernel), "amph_verify_kernel")
 
     def amph_profile_kind(self, kind: int, max_launches: int = 4096, every: int = 1):
         self._check(lib().amph_profile_kind(self.handle, kind, max_launches, every), "amph_profile_kind")

@@ -40,6 +40,7 @@ struct amph_ctx {
   size_t prof_used = 0;
   int prof_every = 1;                 // one launch in this many is timed
   long long prof_seen = 0;            // launches of prof_kind since it was selected
+  int verify_kernel = -1;             // amph_verify_kernel: -1 by shape, 0 registers, 1 LDS ring
 };
 
 struct amph_tree {
@@ -218,6 +219,7 @@ amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, con
   a.partials = (float *)((char *)workspace + ctx->ws.ver_part);
   a.partials_cap = ctx->ws.ver_part_floats;
   a.dev_status = ctx->dev_status;
+  a.kernel = ctx->verify_kernel;
   PROF_TRY(ctx, AMPH_K_VERIFY, launch_verify_attn<T>(ctx->stream, a));
   return AMPH_OK;
 }
@@ -605,6 +607,13 @@ amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const voi
   a.n_heads = ctx->cfg.n_heads; a.d_h = ctx->cfg.head_dim;
   if (ctx->cfg.dtype == AMPH_BF16) HIP_TRY(ctx, launch_pack_weights<bf16_t>(ctx->stream, epi, a, dst));
   else HIP_TRY(ctx, launch_pack_weights<float>(ctx->stream, epi, a, dst));
+  return AMPH_OK;
+}
+
+amph_status amph_verify_kernel(amph_ctx *ctx, int kernel) {
+  if (!ctx) return AMPH_EINVAL;
+  if (kernel < -1 || kernel > 1) return fail(ctx, AMPH_EINVAL, "amph_verify_kernel: kernel must be -1, 0 or 1");
+  ctx->verify_kernel = kernel;
   return AMPH_OK;
 }
 

@@ -103,8 +103,8 @@ struct VerifyArgs {
   const int32_t *kv_len; const uint64_t *mask_bits;
   int B, T, n_heads, d_h, max_kv;
   float *partials; size_t partials_cap; uint32_t *dev_status;
+  int kernel;       // -1: chosen by shape; 0: operands through registers; 1: operands through an LDS ring
 };
-int verify_splits(int B, int T, int n_heads, int max_kv, int elem_bytes);
 size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes);
 template <typename T> hipError_t launch_verify_attn(hipStream_t st, const VerifyArgs &a);
 

@@ -2,18 +2,32 @@
 // queries of one head against the committed cache rows [0, L) and the tree's own rows [L, L+T),
 // where query i sees tree row j only if node j is i or an ancestor of i.
 //
-// Everything runs on the matrix cores with operands taken straight from global memory:
+// Everything runs on the matrix cores:
 //   S^T[key, q] = K[key, :] . Q[q, :]      A = 16 keys x 64 bytes of K rows, B = 16 queries of Q
 //   O^T[d, q]  += V^T[d, keys] . P^T[keys, q]   A = 16 dims x the step's keys of V
 // Both caches are stored step-tiled (layout in the header of the C ABI): each A fragment is one
-// contiguous 1 KB piece, in the order the loop below asks for them.
+// contiguous 1 KB piece and the fragments of one key step (32 keys in bf16, 16 in float) are adjacent.
 // The 16 keys fed to one S^T tile are chosen so that the accumulator a lane ends up with (4 keys of
 // its lane group per tile) is exactly the contraction-slot layout the second product expects from
-// its B operand, so P never leaves registers.  A wave owns whole key steps (32 keys in bf16, 16 in
-// float) for up to 32 queries; the four waves of a workgroup take different steps and merge their
-// running (max, sum, O) through LDS; workgroups that split the keys of one head merge through global
-// memory: a second small kernel (k_verify_fold) folds them in a fixed order, so no workgroup ever
-// waits for or signals another.
+// its B operand, so P never leaves registers.
+//
+// Two kernels share this arithmetic and differ in how the fragments reach the matrix cores:
+//
+// k_verify_attn_regs (short key ranges: few steps per wave, fixed costs dominate).  Operands go from
+// global memory straight to registers.  A wave owns whole key steps for up to 32 queries; the four waves of a
+// workgroup take different steps and merge their running (max, sum, O) through LDS.
+//
+// k_verify_attn_ring (long key ranges: one workgroup streams all keys of a (batch element, head)).  Two loader
+// waves stream the fragments from global memory straight into a ring of LDS stages (one key step per stage)
+// without passing through registers; each math wave owns 16 or 32 queries for the whole range, reads every
+// fragment of a stage from LDS (lane-linear, free of bank conflicts) and keeps its running (max, sum, O) in
+// registers: the keys are read once per workgroup instead of once per 32 queries, and math waves never
+// exchange anything.  One barrier per stage hands a landed stage to the math waves and a consumed one back to
+// the loaders.  Measured at 52 heads, T = 96, batch 4, L = 4096: 120 us against 167 us; at 32 heads, T = 64,
+// batch 1, L = 1024: 17.0 us against 15.4 us, hence the other kernel there.
+//
+// Workgroups that split the keys of one head merge through global memory: a second small kernel
+// (k_verify_fold) folds them in a fixed order, so no workgroup ever waits for or signals another.
 #include "kernels.h"
 
 namespace amph {
@@ -22,8 +36,11 @@ namespace amph {
 // the library version's rescue of results below the normal range (four more instructions per call) buys nothing.
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// =====================================================================================================
+// operands through registers
+// =====================================================================================================
 template <typename T, int DH, int NQB>
-struct VA {
+struct VAR {
   static constexpr int PER = Elem<T>::PER;
   static constexpr int KSTEP = 4 * PER;            // keys per step
   static constexpr int NT = KSTEP / 16;            // S^T tiles per step
@@ -35,8 +52,8 @@ struct VA {
 };
 
 template <typename T, int DH, int NQB>
-__global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_qg) {
-  using C = VA<T, DH, NQB>;
+__global__ __launch_bounds__(256) void k_verify_attn_regs(const VerifyArgs a, int n_qg) {
+  using C = VAR<T, DH, NQB>;
   constexpr int PER = C::PER, KSTEP = C::KSTEP, NT = C::NT, DSTEPS = C::DSTEPS, DB = C::DB, NQ = C::NQ;
   __shared__ __align__(16) float sm_o[4][NQ][C::OPITCH];
   __shared__ float sm_m[4][NQ], sm_l[4][NQ];
@@ -253,6 +270,268 @@ __global__ __launch_bounds__(256) void k_verify_attn(const VerifyArgs a, int n_q
   }
 }
 
+// =====================================================================================================
+// operands through an LDS ring
+// =====================================================================================================
+template <typename T, int DH>
+struct VA {
+  static constexpr int PER = Elem<T>::PER;
+  static constexpr int KSTEP = 4 * PER;            // keys per step
+  static constexpr int NT = KSTEP / 16;            // S^T tiles per step
+  static constexpr int DSTEPS = DH / (4 * PER);    // 64-byte pieces of a K/Q row
+  static constexpr int DB = DH / 16;               // 16-row blocks of O^T
+  static constexpr int FK = NT * DSTEPS;           // K fragments of a step
+  static constexpr int FR = FK + DB;               // fragments (KB) of a step: its K, then its V
+  static constexpr int STEPB = FR * 1024;          // bytes of a step
+  static constexpr int NS = 1;                     // key steps per ring stage (2 measured slower)
+  static constexpr int STAGE = NS * STEPB;
+  static constexpr int NL = 2;                     // loader waves
+  static constexpr int PERL = NS * FR / NL;        // loads per loader wave and stage
+  static constexpr int R = 4;                      // stages in the ring (8 measured no faster)
+  static_assert(FK % NL == 0 && FR % NL == 0, "a loader wave's j-th fragment must be K or V for both waves alike");
+  static_assert(PERL * (R - 2) <= 63, "outstanding loads of a loader wave must fit the hardware counter");
+};
+constexpr int VA_MAX_MATH = 4;                     // math waves per workgroup
+
+// Waits until at most N vector-memory operations of this wave are outstanding (they complete in order).
+template <int N> __device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+// at most k whole stages of this loader wave's loads may still be in flight
+template <int PERL> __device__ __forceinline__ void wait_stages(int k) {
+  switch (k) {
+    case 0: wait_vm<0>(); break;
+    case 1: wait_vm<PERL>(); break;
+    default: wait_vm<2 * PERL>(); break;
+  }
+}
+template <int N> struct IntTag { static constexpr int value = N; };
+
+// grid = (key splits, heads, batch); block = (math waves + 2 loader waves) * 64; dynamic LDS = R stages
+template <typename T, int DH, int NQB>
+__global__ __launch_bounds__((VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(const VerifyArgs a) {
+  using C = VA<T, DH>;
+  constexpr int PER = C::PER, KSTEP = C::KSTEP, NT = C::NT, DSTEPS = C::DSTEPS, DB = C::DB, FK = C::FK, FR = C::FR;
+  constexpr int STEPB = C::STEPB, NS = C::NS, STAGE = C::STAGE, NL = C::NL, PERL = C::PERL, R = C::R;
+  extern __shared__ __align__(16) unsigned char sm_ring[];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
+  const int nm = (int)(blockDim.x >> 6) - NL;        // math waves
+  const int S = gridDim.x, split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int Tn = a.T, n_h = a.n_heads, max_kv = a.max_kv;
+  const int L = a.kv_len[b];
+  if (L < 0 || L + Tn > max_kv) {                    // whole workgroup leaves before any barrier; nobody else waits for it
+    if (tid == 0 && split == 0 && h == 0) atomicOr(a.dev_status, 2u);
+    return;
+  }
+  const int n_keys = L + Tn;
+  const int n_steps = (n_keys + KSTEP - 1) / KSTEP;
+  const int st0 = (int)((long long)n_steps * split / S), st1 = (int)((long long)n_steps * (split + 1) / S);
+  const int n = st1 - st0;                           // key steps of this workgroup; may be 0
+  const int n_stages = (n + NS - 1) / NS;            // ring stages: NS steps each, the last one possibly ragged
+  const size_t head_bytes = ((size_t)b * n_h + h) * (size_t)max_kv * DH * sizeof(T);
+
+  if (wave >= nm) {
+    // ---------------- loader wave: fragments w, w + 2, ... of every step of every stage ----------------
+    // A lane fetches the 16 bytes its counterpart in a math wave feeds to the matrix core (row r16 of the
+    // fragment, piece g); they land in LDS at lane * 16, where the math lane reads them back.  A ragged last
+    // stage loads its last step again (never used), so every stage counts the same number of loads.
+    const int w = wave - nm;
+    const unsigned char *Kg = (const unsigned char *)a.k_cache + head_bytes + r16 * 64 + g * 16;
+    const unsigned char *Vg = (const unsigned char *)a.v_cache + head_bytes + r16 * 64 + g * 16;
+    auto issue = [&](int p) {
+      #pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const int rel = (p * NS + s < n) ? p * NS + s : n - 1;
+        const size_t st = (size_t)(st0 + rel);
+        unsigned char *lp = sm_ring + (p % R) * STAGE + s * STEPB;
+        #pragma unroll
+        for (int j = 0; j < FR / NL; ++j) {
+          const int f = w + j * NL;
+          const unsigned char *src = (j * NL < FK) ? Kg + (st * FK + f) * 1024 : Vg + (st * DB + (f - FK)) * 1024;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                           (__attribute__((address_space(3))) void *)(lp + f * 1024), 16, 0, 0);
+        }
+      }
+    };
+    const int pro = n_stages < R - 1 ? n_stages : R - 1;
+    for (int p = 0; p < pro; ++p) issue(p);
+    for (int p = 0; p < n_stages; ++p) {
+      const int newest = (p + R - 2 < n_stages - 1) ? p + R - 2 : n_stages - 1;    // newest stage issued so far
+      wait_stages<PERL>(newest - p);                 // stage p has landed
+      __builtin_amdgcn_s_barrier();                  // math waves may read stage p; they are done with stage p - 1
+      if (p + R - 1 < n_stages) issue(p + R - 1);    // into the slot of stage p - 1
+    }
+    return;
+  }
+
+  // ---------------- math wave: queries [q0, q0 + 16 * NQB) against all stages ----------------
+  const float scale = 1.4426950408889634f * rsqrtf((float)DH);
+  const float NEG_INF = -__builtin_huge_valf();
+  const int q0 = wave * NQB * 16;
+
+  // queries as B fragments: lane = query r16 of block qb, 16 bytes of dims per 64-byte piece
+  uint4 Qf[NQB][DSTEPS];
+  uint64_t mk_lo[NQB], mk_hi[NQB];
+  #pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int qi = q0 + qb * 16 + r16;
+    #pragma unroll
+    for (int ds = 0; ds < DSTEPS; ++ds) {      // padding queries re-read query 0; their rows are never stored
+      const int qs = (qi < Tn) ? qi : 0;
+      Qf[qb][ds] = ldg16((const T *)a.q + (((size_t)b * Tn + qs) * n_h + h) * DH + ds * (4 * PER) + g * PER);
+    }
+    mk_lo[qb] = (qi < Tn) ? a.mask_bits[(size_t)qi * 2] : 0ull;
+    mk_hi[qb] = (qi < Tn) ? a.mask_bits[(size_t)qi * 2 + 1] : 0ull;
+  }
+
+  f32x4 O[NQB][DB];
+  float m_run[NQB], l_run[NQB];
+  #pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = NEG_BIG; l_run[qb] = 0.f;
+    #pragma unroll
+    for (int db = 0; db < DB; ++db) O[qb][db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+
+  // NSL consecutive key steps (first key key0) whose fragments start at sb: their scores together, one move of the
+  // running maximum, then their probabilities and values.  Independent steps give the matrix cores and the LDS
+  // reads something to overlap with the exponentials.
+  auto process = [&](auto tag, const unsigned char *sb, int key0) {
+    constexpr int NSL = decltype(tag)::value;
+    // ---- scores: fragment (t, ds) holds keys step0 + (slot >> 2) * (4 * NT) + t * 4 + (slot & 3) at slot = lane & 15,
+    // so the S^T accumulators come out in the contraction-slot order of the second product:
+    // the lane gets keys step0 + g * PER + (t * 4 + c), query r16
+    f32x4 sacc[NSL][NQB][NT];
+    #pragma unroll
+    for (int s = 0; s < NSL; ++s)
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb)
+        #pragma unroll
+        for (int t = 0; t < NT; ++t) sacc[s][qb][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    #pragma unroll
+    for (int s = 0; s < NSL; ++s)
+      #pragma unroll
+      for (int t = 0; t < NT; ++t)
+        #pragma unroll
+        for (int ds = 0; ds < DSTEPS; ++ds) {
+          const uint4 Kf = *reinterpret_cast<const uint4 *>(sb + s * STEPB + (t * DSTEPS + ds) * 1024);
+          #pragma unroll
+          for (int qb = 0; qb < NQB; ++qb) sacc[s][qb][t] = mma16<T>(Kf, Qf[qb][ds], sacc[s][qb][t]);
+        }
+    float sv[NSL][NQB][PER], mn[NQB];
+    bool grow = false;
+    #pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      float mx = NEG_INF;
+      #pragma unroll
+      for (int s = 0; s < NSL; ++s) {
+        #pragma unroll
+        for (int t = 0; t < NT; ++t)
+          #pragma unroll
+          for (int c = 0; c < 4; ++c) sv[s][qb][t * 4 + c] = sacc[s][qb][t][c] * scale;
+        const int k0 = key0 + s * KSTEP;
+        if (k0 + KSTEP > L) {                          // this step touches tree rows or rows past the end
+          const int qi = q0 + qb * 16 + r16;
+          #pragma unroll
+          for (int j = 0; j < PER; ++j) {
+            const int key = k0 + g * PER + j;
+            bool vis = key < L;
+            if (!vis && key < n_keys) {
+              const int bit = key - L;
+              vis = ((bit < 64 ? (mk_lo[qb] >> bit) : (mk_hi[qb] >> (bit - 64))) & 1ull) != 0ull;
+            }
+            if (!vis || qi >= Tn) sv[s][qb][j] = NEG_INF;
+          }
+        }
+        #pragma unroll
+        for (int j = 0; j < PER; ++j) mx = fmaxf(mx, sv[s][qb][j]);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+      mn[qb] = fmaxf(m_run[qb], mx);
+      grow |= (mn[qb] > m_run[qb]);
+    }
+    // ---- the running maximum rarely moves after the first steps: rescale only when some query's did
+    if (__any(grow)) {
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        const float corr = fast_exp2(m_run[qb] - mn[qb]);
+        l_run[qb] *= corr;
+        #pragma unroll
+        for (int db = 0; db < DB; ++db) O[qb][db] *= corr;
+        m_run[qb] = mn[qb];
+      }
+    }
+    // ---- probabilities, and O^T += V^T P^T
+    uint4 Pf[NSL][NQB];
+    #pragma unroll
+    for (int s = 0; s < NSL; ++s)
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        float pv[PER], ls = 0.f;
+        #pragma unroll
+        for (int j = 0; j < PER; ++j) { pv[j] = fast_exp2(sv[s][qb][j] - m_run[qb]); ls += pv[j]; }
+        l_run[qb] += ls;
+        Pf[s][qb] = pack16<T>(pv);
+      }
+    #pragma unroll
+    for (int s = 0; s < NSL; ++s) {
+      const int k0 = key0 + s * KSTEP;
+      const bool ragged = (k0 + KSTEP > n_keys);
+      #pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        uint4 Vf = *reinterpret_cast<const uint4 *>(sb + s * STEPB + (FK + db) * 1024);
+        if (ragged) {
+          // rows past L+T may hold anything (even NaN): zero their values so that 0 * V stays 0
+          float vv[PER];
+          Elem<T>::unpack(Vf, vv);
+          #pragma unroll
+          for (int j = 0; j < PER; ++j) if (k0 + g * PER + j >= n_keys) vv[j] = 0.f;
+          Vf = pack16<T>(vv);
+        }
+        #pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) O[qb][db] = mma16<T>(Vf, Pf[s][qb], O[qb][db]);
+      }
+    }
+  };
+
+  for (int p = 0; p < n_stages; ++p) {
+    __syncthreads();                                   // stage p is in LDS (pairs with the loaders' barrier)
+    const unsigned char *sb = sm_ring + (p % R) * STAGE + lane * 16;
+    const int key0 = (st0 + p * NS) * KSTEP;
+    if (p * NS + NS <= n) process(IntTag<NS>{}, sb, key0);
+    else process(IntTag<1>{}, sb, key0);               // ragged last stage (NS = 2: one live step)
+  }
+
+  // ---- lane groups hold partial sums of l for the same query: fold them; then the lane writes dims
+  // db * 16 + g * 4 .. + 3 of query r16 of each of its blocks
+  const int NQ = nm * NQB * 16;                        // query rows of a partial
+  float *part = a.partials + ((((size_t)b * n_h + h) * S + split) * (size_t)(NQ * DH + 2 * NQ));
+  #pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    float l = l_run[qb];
+    l += __shfl_xor(l, 16, WAVE);
+    l += __shfl_xor(l, 32, WAVE);
+    const int q = q0 + qb * 16 + r16;
+    if (S == 1) {
+      if (q < Tn) {
+        const float inv = (l > 0.f) ? 1.0f / l : 0.f;
+        T *dst = (T *)a.out + (((size_t)b * Tn + q) * n_h + h) * DH + g * 4;
+        #pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const float r[4] = {O[qb][db][0] * inv, O[qb][db][1] * inv, O[qb][db][2] * inv, O[qb][db][3] * inv};
+          store4<T>(dst + db * 16, r);
+        }
+      }
+    } else {
+      #pragma unroll
+      for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4 *>(part + (size_t)q * DH + db * 16 + g * 4) = O[qb][db];
+      if (g == 0) { part[NQ * DH + q] = m_run[qb]; part[NQ * DH + NQ + q] = l; }
+    }
+  }
+}
+
 // Fold the S key-split partials of one (batch, query group, head): out = sum_s O_s 2^(m_s - m) / sum_s l_s 2^(m_s - m),
 // s ascending.  grid = (heads, B * query groups), 256 threads, 4 dims of one query per thread and iteration.
 template <typename T, int DH>
@@ -284,57 +563,107 @@ __global__ __launch_bounds__(256) void k_verify_fold(const VerifyArgs a, int n_q
   for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(r[i]);
 }
 
-// queries per workgroup: as few 16-query blocks per wave as cover T in ceil(T/64) groups
-// Queries per workgroup: at most two 16-query blocks per wave.  Larger blocks per wave would save K/V
-// re-reads (they come from L2) but need more registers than leave room for a second set of K/V fragments.
-constexpr int VA_MAX_QB = 2;
-static inline void va_groups(int T, int *nqb, int *n_qg) {
-  const int blocks = (T + 15) / 16;
-  *n_qg = (blocks + VA_MAX_QB - 1) / VA_MAX_QB;
-  *nqb = (blocks + *n_qg - 1) / *n_qg;
-}
+// =====================================================================================================
+// launch plan
+// =====================================================================================================
+struct VaPlan {
+  bool ring;        // which kernel
+  int S;            // key splits
+  int nqb;          // 16-query blocks per wave
+  int groups;       // regs: query groups (workgroups per head and split); ring: 1
+  int nm;           // ring: math waves
+  int nq;           // query rows of one partial
+};
+constexpr int VA_MAX_QB = 2;       // regs: more blocks per wave would leave no room for a second set of K/V fragments
 
-int verify_splits(int B, int T, int n_heads, int max_kv, int elem_bytes) {
-  int nqb, n_qg;
-  va_groups(T, &nqb, &n_qg);
+// force: -1 chooses by shape, 0 = registers, 1 = LDS ring
+static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int force) {
+  VaPlan p{};
   const int kstep = 4 * (16 / elem_bytes);
   const int max_steps = max_kv / kstep;
+  // regs: at most two blocks per wave, as few query groups as cover T; enough splits for every compute unit,
+  // at least one step per wave
+  const int blocks = (T + 15) / 16;
+  const int n_qg = (blocks + VA_MAX_QB - 1) / VA_MAX_QB;
   int s = 256 / (B * n_qg * n_heads);
-  const int cap = (max_steps + 3) / 4;        // at least one step per wave
+  const int cap = (max_steps + 3) / 4;
   if (s > cap) s = cap;
   if (s > 32) s = 32;
-  return s < 1 ? 1 : s;
+  if (s < 1) s = 1;
+  // ring: when a workgroup walks a whole head anyway (no room for key splits) and the walk is long, or when the
+  // register kernel would need more workgroups than there are compute units (measured: 32 heads, T = 64, L = 1024:
+  // batch 1 15.4 us regs / 17.3 ring, batch 4 21.1 / 23.2, batch 8 40.6 / 31.0; 40 heads, L = 2048, batch 4: 57.8 / 46.4)
+  const bool ring = (force < 0) ? ((B * n_qg * n_heads > 256) || (s == 1 && max_steps >= 64)) : (force == 1);
+  p.ring = ring;
+  if (ring) {
+    p.nqb = (T > 16 * VA_MAX_MATH) ? 2 : 1;
+    p.nm = (T + 16 * p.nqb - 1) / (16 * p.nqb);
+    p.groups = 1;
+    int sr = 256 / (B * n_heads);                      // never more workgroups than compute units: a second round costs more
+    if (sr > max_steps / 2) sr = max_steps / 2;
+    if (sr > 32) sr = 32;
+    p.S = sr < 1 ? 1 : sr;
+    p.nq = p.nm * p.nqb * 16;
+  } else {
+    p.groups = n_qg;
+    p.nqb = (blocks + n_qg - 1) / n_qg;
+    p.S = s;
+    p.nm = 4;
+    p.nq = p.nqb * 16;
+  }
+  return p;
 }
 
+static size_t va_plan_floats(const VaPlan &p, int B, int n_heads, int d_h) {
+  return (size_t)B * p.groups * n_heads * p.S * ((size_t)p.nq * d_h + 2 * p.nq);
+}
+
+// partial results of the larger of the two kernels' plans: the choice may be overridden per call
 size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes) {
-  int nqb, n_qg;
-  va_groups(T, &nqb, &n_qg);
-  const size_t part = (size_t)nqb * 16 * d_h + 2 * nqb * 16;
-  return (size_t)B * n_qg * n_heads * verify_splits(B, T, n_heads, max_kv, elem_bytes) * part;
+  const size_t a = va_plan_floats(va_plan(B, T, n_heads, max_kv, elem_bytes, 0), B, n_heads, d_h);
+  const size_t b = va_plan_floats(va_plan(B, T, n_heads, max_kv, elem_bytes, 1), B, n_heads, d_h);
+  return a > b ? a : b;
+}
+
+template <typename T, int DH, int NQB>
+static hipError_t launch_va_ring(hipStream_t st, const VerifyArgs &a, const VaPlan &p) {
+  using C = VA<T, DH>;
+  constexpr size_t smem = (size_t)C::R * C::STAGE;
+  static bool attr_set = false;                       // once per instantiation and process
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)k_verify_attn_ring<T, DH, NQB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_verify_attn_ring<T, DH, NQB>), dim3(p.S, a.n_heads, a.B), dim3((p.nm + C::NL) * 64), smem, st, a);
+  return hipGetLastError();
 }
 
 template <typename T, int DH>
 static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
-  int nqb, n_qg;
-  va_groups(a.T, &nqb, &n_qg);
-  const int S = verify_splits(a.B, a.T, a.n_heads, a.max_kv, (int)sizeof(T));
-  const dim3 grid(S, a.n_heads, a.B * n_qg), block(256);
-  switch (nqb) {
-    case 1: hipLaunchKernelGGL((k_verify_attn<T, DH, 1>), grid, block, 0, st, a, n_qg); break;
-    case 2: hipLaunchKernelGGL((k_verify_attn<T, DH, 2>), grid, block, 0, st, a, n_qg); break;
-    default: return hipErrorInvalidValue;
+  const VaPlan p = va_plan(a.B, a.T, a.n_heads, a.max_kv, (int)sizeof(T), a.kernel);
+  if (p.nqb < 1 || p.nqb > 2) return hipErrorInvalidValue;
+  if (va_plan_floats(p, a.B, a.n_heads, DH) > a.partials_cap) return hipErrorInvalidValue;
+  if (p.ring) {
+    if (p.nm < 1 || p.nm > VA_MAX_MATH) return hipErrorInvalidValue;
+    hipError_t e = (p.nqb == 1) ? launch_va_ring<T, DH, 1>(st, a, p) : launch_va_ring<T, DH, 2>(st, a, p);
+    if (e != hipSuccess) return e;
+  } else {
+    const dim3 grid(p.S, a.n_heads, a.B * p.groups), block(256);
+    if (p.nqb == 1) hipLaunchKernelGGL((k_verify_attn_regs<T, DH, 1>), grid, block, 0, st, a, p.groups);
+    else hipLaunchKernelGGL((k_verify_attn_regs<T, DH, 2>), grid, block, 0, st, a, p.groups);
   }
-  if (S > 1) {
+  if (p.S > 1) {
     constexpr int QW = 256 / (DH / 4);
-    hipLaunchKernelGGL((k_verify_fold<T, DH>), dim3(a.n_heads, a.B * n_qg, (nqb * 16 + QW - 1) / QW), block, 0, st, a, n_qg, nqb, S);
+    hipLaunchKernelGGL((k_verify_fold<T, DH>), dim3(a.n_heads, a.B * p.groups, (p.nq + QW - 1) / QW), dim3(256), 0, st, a, p.groups,
+                       p.nq / 16, p.S);
   }
   return hipGetLastError();
 }
 
 template <typename T>
 hipError_t launch_verify_attn(hipStream_t st, const VerifyArgs &a) {
-  if (a.T < 1 || a.T > AMPH_MAX_TREE || a.max_kv % 32) return hipErrorInvalidValue;
-  if (verify_ws_floats(a.B, a.T, a.n_heads, a.d_h, a.max_kv, (int)sizeof(T)) > a.partials_cap) return hipErrorInvalidValue;
+  if (a.T < 1 || a.T > AMPH_MAX_TREE || a.max_kv % 32 || a.kernel < -1 || a.kernel > 1) return hipErrorInvalidValue;
   if (a.d_h == 64) return launch_va_dh<T, 64>(st, a);
   if (a.d_h == 128) return launch_va_dh<T, 128>(st, a);
   return hipErrorInvalidValue;

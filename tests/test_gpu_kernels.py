@@ -59,13 +59,18 @@ def test_gemm_matches_oracle(cfg, M, N, Kd, split):
 
 
 # ---------------------------------------------------------------------------- A8 tree-masked attention
-def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None):
+KERNELS = [0, 1]        # amph_verify_kernel: operands through registers / through the LDS ring
+KERNEL_IDS = ["regs", "ring"]
+
+
+def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None, kernel=-1):
     K = len(caps)
     cfgx = si.with_(cfg, batch=B_, K=K, topk=min(16, max(caps)))
     lens = [L] * B_ if lens is None else list(lens)      # committed rows per batch element (L = the largest)
     assert max(lens) == L and len(lens) == B_
     max_kv = (L + T + 31) // 32 * 32 + 32
     ctx = make_ctx(cfgx, T=T, batch=B_, max_kv=max_kv)
+    ctx.amph_verify_kernel(kernel)
     paths = si.tree_paths(T, caps)
     tree = B.Tree(paths, K)
     otree = orc.tree_from_paths(paths, K)
@@ -110,17 +115,19 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None):
     (si.MINI, 1, (4, 4, 4, 4), 96),             # the root alone = one-token decoding
     (si.TINY, 1, (4, 4, 4, 4), 0),              # one query, one key (itself)
 ])
-def test_verify_attn_matches_oracle(cfg, T, caps, L):
-    say(f"verify_attn {cfg.name} T={T} L={L}")
-    worst = verify_case(cfg, T, caps, L)
+@pytest.mark.parametrize("kernel", KERNELS, ids=KERNEL_IDS)
+def test_verify_attn_matches_oracle(cfg, T, caps, L, kernel):
+    say(f"verify_attn {cfg.name} T={T} L={L} kernel={kernel}")
+    worst = verify_case(cfg, T, caps, L, kernel=kernel)
     say(f"  worst row error {worst:.2e}")
 
 
-def test_verify_attn_batch_independent_lengths_share_a_launch():
-    say("verify_attn batch=3, committed lengths 77 / 5 / 40 in one launch")
-    verify_case(si.MINI, 64, (10,) * 4, 77, B_=3, lens=[77, 5, 40])
+@pytest.mark.parametrize("kernel", KERNELS, ids=KERNEL_IDS)
+def test_verify_attn_batch_independent_lengths_share_a_launch(kernel):
+    say(f"verify_attn batch=3, committed lengths 77 / 5 / 40 in one launch, kernel={kernel}")
+    verify_case(si.MINI, 64, (10,) * 4, 77, B_=3, lens=[77, 5, 40], kernel=kernel)
     say("verify_attn batch=2, one element with an empty cache")
-    verify_case(si.MINI, 35, (10,) * 4, 130, B_=2, lens=[0, 130])
+    verify_case(si.MINI, 35, (10,) * 4, 130, B_=2, lens=[0, 130], kernel=kernel)
 
 
 @pytest.mark.parametrize("cfg,T,caps,L,B_", [
@@ -129,20 +136,38 @@ def test_verify_attn_batch_independent_lengths_share_a_launch():
     (si.TINY, 64, (10,) * 4, 130, 4),           # float32 (16-key steps, 64-wide heads)
     (si.MINI, 64, (10,) * 4, 0, 4),             # empty cache
 ])
-def test_verify_attn_many_workgroups(cfg, T, caps, L, B_):
+@pytest.mark.parametrize("kernel", KERNELS, ids=KERNEL_IDS)
+def test_verify_attn_many_workgroups(cfg, T, caps, L, B_, kernel):
     """Batches large enough that (batch, head, query block) alone fill a quarter of the chip: the launch
     heuristics then pick few or no key splits."""
-    say(f"verify_attn {cfg.name} T={T} L={L} B={B_}")
-    worst = verify_case(cfg, T, caps, L, B_=B_)
+    say(f"verify_attn {cfg.name} T={T} L={L} B={B_} kernel={kernel}")
+    worst = verify_case(cfg, T, caps, L, B_=B_, kernel=kernel)
     say(f"  worst row error {worst:.2e}")
 
 
-def test_verify_attn_vicuna7b_shape():
-    """Full 7B layer shape (32 heads x 128, L = 1024, T = 64) in the launch configuration the bench uses;
-    every head checked against the oracle."""
-    say("verify_attn vicuna7b L=1024 T=64")
-    worst = verify_case(si.V7B, 64, (10,) * 4, 1024)
+@pytest.mark.parametrize("kernel", [-1, 1], ids=["auto", "ring"])
+def test_verify_attn_vicuna7b_shape(kernel):
+    """Full 7B layer shape (32 heads x 128, L = 1024, T = 64) in the launch configuration the bench uses
+    (kernel chosen by shape), and with the other kernel; every head checked against the oracle."""
+    say(f"verify_attn vicuna7b L=1024 T=64 kernel={kernel}")
+    worst = verify_case(si.V7B, 64, (10,) * 4, 1024, kernel=kernel)
     say(f"  worst row error {worst:.2e}")
+
+
+def test_verify_attn_long_cache_whole_head_per_workgroup():
+    """Shape for which the choice by shape takes the LDS ring without key splits (batch x heads above the number of
+    compute units) and every workgroup walks a long cache: 9 x 32 heads, L = 2500 (79 key steps, ragged)."""
+    say("verify_attn vicuna7b heads, batch 9, L=2500 T=64, kernel by shape")
+    worst = verify_case(si.V7B, 64, (10,) * 4, 2500, B_=9, heads=[0, 13, 31], lens=[2500, 17, 1200, 2499, 0, 64, 2048, 999, 2500])
+    say(f"  worst row error {worst:.2e}")
+
+
+def test_verify_kernel_selector_rejects_unknown_values():
+    ctx = make_ctx(si.TINY, T=16)
+    for bad in (-2, 2, 7):
+        with pytest.raises(RuntimeError):
+            ctx.amph_verify_kernel(bad)
+    ctx.amph_verify_kernel(-1)
 
 
 def test_verify_attn_flags_cache_overflow():
