@@ -287,6 +287,13 @@ def main():
     t1 = time.perf_counter()
     dom_ms, dom_n = ctx.amph_profile_read()
     ctx.amph_profile_kind(-1, 0)
+    # what a bracket reads with nothing inside: the part of avg_launch_us that is the markers, not the kernel
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+    for e0, e1 in pairs:
+        e0.record()
+        e1.record()
+    torch.cuda.synchronize()
+    empty_us = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / len(pairs) * 1e3
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = 1e3 / ms_per_step
     dom_avg_s = dom_ms * 1e-3 / max(dom_n, 1)
@@ -317,7 +324,8 @@ def main():
         "step_hbm_frac": sb * steps_per_s / 1e9 / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "launches_timed": dom_n, "timed_one_launch_in": PROF_EVERY,
-                     "avg_launch_us": dom_avg_s * 1e6, "algorithmic_bytes_per_launch": dom_bytes},
+                     "avg_launch_us": dom_avg_s * 1e6, "empty_event_pair_us": empty_us,
+                     "algorithmic_bytes_per_launch": dom_bytes},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, n_layers)
