@@ -126,6 +126,9 @@ def main():
     ap.add_argument("--workload", default="vicuna7b", choices=["vicuna7b", "vicuna13b", "vicuna33b", "tiny", "mini_bf16"])
     ap.add_argument("--layers", type=int, default=None, help="target layers (default: the configuration's)")
     ap.add_argument("--batch", type=int, default=None, help="independent sequences per step (default: the configuration's)")
+    ap.add_argument("--tree-nodes", type=int, default=None, help="nodes of the candidate tree (default: the configuration's)")
+    ap.add_argument("--unequal-kv", action="store_true",
+                    help="batch elements get committed lengths spread over [L/4, L] instead of all L")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
     ap.add_argument("--row-major", action="store_true",
@@ -156,6 +159,8 @@ def main():
     cfg = si.CONFIGS[args.workload]
     if args.batch is not None:
         cfg = si.with_(cfg, batch=args.batch)
+    if args.tree_nodes is not None:
+        cfg = si.with_(cfg, T=args.tree_nodes)
     n_layers = cfg.n_layers if args.layers is None else args.layers
     n_h, d_h, d, f, V, K, T, L, Ls, Bsz = (cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.d_ffn, cfg.vocab, cfg.K, cfg.T,
                                            cfg.kv_len, cfg.sal_len, cfg.batch)
@@ -228,7 +233,8 @@ def main():
     topk_idx, topk_val = i32(Bsz, K, cfg.topk), torch.zeros((Bsz, K, cfg.topk), dtype=torch.float32, device=dev)
     tree_tok, tree_pos, tgt = i32(Bsz, T), i32(Bsz, T), i32(Bsz, T)
     a_len, a_path, nxt, best = i32(Bsz), i32(Bsz, K + 1), i32(Bsz), i32(Bsz)
-    kv_len = torch.full((Bsz,), L, dtype=torch.int32, device=dev)
+    kv_lens = [L - (3 * L // 4) * b // max(Bsz - 1, 1) for b in range(Bsz)] if args.unequal_kv else [L] * Bsz
+    kv_len = torch.tensor(kv_lens, dtype=torch.int32, device=dev)
     sal_len0 = torch.full((Bsz,), Ls, dtype=torch.int32, device=dev)
     sal_len = sal_len0.clone()
 
@@ -316,7 +322,7 @@ def main():
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} full step: draft (K={K}, top-{cfg.topk}, SAL cache {Ls}) + {n_layers}-layer "
                                f"tree verification (T={T}, L={L}) + greedy accept, batch {Bsz}",
-                   "layers": n_layers, "tree_nodes": T, "kv_len": L, "batch": Bsz,
+                   "layers": n_layers, "tree_nodes": T, "kv_len": L if not args.unequal_kv else kv_lens, "batch": Bsz,
                    "target_weight_layout": "row-major" if args.row_major else "tiled",
                    "draft_variant": {"adaptation_layers": n_stages, "position_encoding": not args.no_pe,
                                      "self_attention_layers": args.aeb_layers, "lm_head_rank": args.lm_rank or "full"}},
