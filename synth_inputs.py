@@ -213,6 +213,27 @@ def tree_paths(T: int, caps: Sequence[int]) -> List[Tuple[int, ...]]:
     return out
 
 
+def random_tree_paths(T: int, K: int, topk: int, seed: int) -> List[Tuple[int, ...]]:
+    """T-1 rank paths of an irregular tree: every new node hangs under a random existing node of depth < K
+    that still has an unused rank below topk, with a random unused rank (siblings' ranks need not be
+    contiguous).  Order of the list is the order of creation, i.e. not sorted."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, T, K, topk, 0x7ee]))
+    nodes: List[Tuple[int, ...]] = [()]
+    used = {(): set()}
+    while len(nodes) < T:
+        open_nodes = [p for p in nodes if len(p) < K and len(used[p]) < topk]
+        if not open_nodes:
+            raise ValueError("no room left for another node")
+        par = open_nodes[int(rng.integers(0, len(open_nodes)))]
+        free = [r for r in range(topk) if r not in used[par]]
+        r = free[int(rng.integers(0, len(free)))]
+        used[par].add(r)
+        child = par + (r,)
+        nodes.append(child)
+        used[child] = set()
+    return nodes[1:]
+
+
 def dense_tree_paths(widths: Sequence[int]) -> List[Tuple[int, ...]]:
     """Full tree: every node at depth j-1 has widths[j-1] children."""
     level: List[Tuple[int, ...]] = [()]

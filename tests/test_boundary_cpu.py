@@ -77,6 +77,31 @@ def test_tree_tables_equal_the_oracle(T, caps):
     t.close()
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_irregular_tree_tables_equal_the_oracle(seed):
+    """Irregular topologies (random parents, non-contiguous sibling ranks, unsorted input order): the library's
+    host tables against the oracle's, and the invariants any tree must satisfy."""
+    rng = np.random.default_rng(seed)
+    K = int(rng.integers(1, 9))
+    topk = int(rng.integers(1, 17))
+    room = sum(topk ** j for j in range(1, K + 1))
+    T = int(min(rng.integers(1, 129), room + 1))
+    paths = si.random_tree_paths(T, K, topk, seed)
+    t = B.Tree(paths, K)
+    o = orc.tree_from_paths(paths, K)
+    assert t.T == T == o.T and t.n_leaves == len(o.leaves)
+    np.testing.assert_array_equal(t.parent, o.parent)
+    np.testing.assert_array_equal(t.depth, o.depth)
+    np.testing.assert_array_equal(t.rank, o.rank)
+    np.testing.assert_array_equal(t.mask_bool(), o.mask)
+    np.testing.assert_array_equal(t.retrieve, o.retrieve)
+    m = t.mask_bool()
+    assert np.all(np.diag(m)) and np.all(m[:, 0])                       # every node sees itself and the root
+    assert np.array_equal(m.sum(axis=1), t.depth + 1)                   # exactly its ancestors and itself
+    assert np.all(t.parent[1:] < np.arange(1, T))                       # parents come first
+    t.close()
+
+
 def test_tree_caption_example():
     t = B.Tree(si.dense_tree_paths((2, 3)), 2)
     assert (t.T, t.n_leaves) == (9, 6)

@@ -223,6 +223,87 @@ def test_tree_build_and_accept_are_bit_exact(T, caps, B_):
             np.testing.assert_array_equal(np_of(a_path)[b], opath)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_random_irregular_trees_build_accept_and_attention(seed):
+    """Irregular topologies end to end: tree tokens and positions, greedy acceptance with planted accepted paths, and
+    the tree-masked attention of both kernels, each against the oracle."""
+    rng = np.random.default_rng(100 + seed)
+    K = int(rng.integers(2, 9))
+    topk = int(rng.integers(2, 17))
+    T = int(min(rng.integers(2, 129), sum(topk ** j for j in range(1, K + 1)) + 1))
+    B_ = int(rng.integers(1, 4))
+    say(f"random tree seed={seed}: T={T} K={K} topk={topk} B={B_}")
+    cfg = si.with_(si.MINI, K=K, batch=B_, topk=topk)
+    paths = si.random_tree_paths(T, K, topk, seed)
+    tree = B.Tree(paths, K)
+    otree = orc.tree_from_paths(paths, K)
+    ctx = make_ctx(cfg, T=T, batch=B_)
+    vocab = 11
+    for trial in range(4):
+        top = np.stack([[rng.permutation(max(vocab, topk))[:topk] for _ in range(K)] for _ in range(B_)]).astype(np.int32)
+        root = rng.integers(0, vocab, size=B_).astype(np.int32)
+        kvl = rng.integers(0, 500, size=B_).astype(np.int32)
+        tok = torch.empty((B_, T), dtype=torch.int32, device=DEV)
+        pos = torch.empty((B_, T), dtype=torch.int32, device=DEV)
+        ctx.amph_tree_build(tree, i32_to_dev(root), i32_to_dev(top), i32_to_dev(kvl), tok, pos)
+        torch.cuda.synchronize()
+        tgt = rng.integers(0, vocab, size=(B_, T)).astype(np.int32)
+        o_toks = []
+        for b in range(B_):
+            o_tok, o_pos = orc.tree_tokens(otree, int(root[b]), top[b], int(kvl[b]))
+            np.testing.assert_array_equal(np_of(tok)[b], o_tok)
+            np.testing.assert_array_equal(np_of(pos)[b], o_pos)
+            o_toks.append(o_tok)
+            # plant an accepted path down to a random node: the target picks the drafted token at every ancestor
+            node = int(rng.integers(0, T))
+            while node > 0:
+                tgt[b, otree.parent[node]] = o_tok[node]
+                node = int(otree.parent[node])
+        a_len = torch.empty(B_, dtype=torch.int32, device=DEV)
+        a_path = torch.empty((B_, K + 1), dtype=torch.int32, device=DEV)
+        nxt = torch.empty(B_, dtype=torch.int32, device=DEV)
+        best = torch.empty(B_, dtype=torch.int32, device=DEV)
+        ctx.amph_accept(tree, tok, i32_to_dev(tgt), None, a_len, a_path, nxt, best)
+        torch.cuda.synchronize()
+        for b in range(B_):
+            oa, opath, onxt, obest = orc.accept_greedy(otree, o_toks[b], tgt[b])
+            assert int(a_len[b]) == oa and int(best[b]) == obest and int(nxt[b]) == onxt
+            np.testing.assert_array_equal(np_of(a_path)[b], opath)
+    # attention with this tree's mask, both kernels
+    L = int(rng.integers(0, 300))
+    for kernel in KERNELS:
+        verify_case_paths(si.MINI, paths, K, topk, L, B_, kernel)
+
+
+def verify_case_paths(cfg, paths, K, topk, L, B_, kernel, seed=23):
+    T = len(paths) + 1
+    cfgx = si.with_(cfg, batch=B_, K=K, topk=topk)
+    max_kv = (L + T + 31) // 32 * 32 + 32
+    ctx = make_ctx(cfgx, T=T, batch=B_, max_kv=max_kv)
+    ctx.amph_verify_kernel(kernel)
+    tree = B.Tree(paths, K)
+    otree = orc.tree_from_paths(paths, K)
+    n_h, d_h = cfg.n_heads, cfg.head_dim
+    q = si.normal(cfgx, seed, "vr.q", (B_, T, n_h, d_h), 1.0)
+    k = si.normal(cfgx, seed, "vr.k", (B_, n_h, L + T, d_h), 1.0)
+    v = si.normal(cfgx, seed, "vr.v", (B_, n_h, L + T, d_h), 1.0)
+    tdt = D.torch_dtype(cfg.dtype)
+    k_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
+    v_rows = torch.full((B_, n_h, max_kv, d_h), float("nan"), dtype=tdt, device=DEV)
+    k_rows[:, :, :L + T] = cfg_tensor_to_dev(k)
+    v_rows[:, :, :L + T] = cfg_tensor_to_dev(v)
+    out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
+    ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), D.keys_to_tiled(k_rows), D.values_to_tiled(v_rows),
+                         i32_to_dev(np.full(B_, L)), out)
+    torch.cuda.synchronize()
+    assert ctx.device_status() == 0
+    got = np_of(out)
+    for b in range(B_):
+        for h in range(n_h):
+            ref = orc.tree_attention(q.f32[b][:, h:h + 1], k.f32[b][h:h + 1], v.f32[b][h:h + 1], L, otree.mask)
+            assert_rows_close(got[b][:, h], ref[:, 0], TOL[cfg.dtype], f"random-tree verify_attn b={b} h={h} kernel={kernel}")
+
+
 def test_accept_from_logits_takes_argmax_with_lowest_id_on_ties():
     cfg = si.with_(si.TINY, vocab=1024)
     T, K = 16, 4
