@@ -282,8 +282,10 @@ def main():
     dominant = args.profile_kind or max(per_kind, key=lambda k: per_kind[k][0])
     dom_id = kinds.index(dominant)
 
-    # A pair of events costs ~6 us of stream time, so only one launch in PROF_EVERY of the dominant kind is
-    # bracketed inside the timed region (7 is coprime to the launches per step, so samples rotate over layers).
+    # The matrix-core GEMMs carry their two events in the launch itself (the events take the kernel's own begin and
+    # end time stamps); other kinds are bracketed by events on the stream.  Either way a timed launch costs the
+    # stream a few microseconds, so only one launch in PROF_EVERY of the dominant kind is timed inside the timed
+    # region (7 is coprime to the launches per step, so samples rotate over layers).
     ctx.amph_profile_kind(dom_id, min(65536, 64 * args.steps + 64), PROF_EVERY)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

@@ -248,9 +248,11 @@ amph_status amph_verify_kernel(amph_ctx *ctx, int kernel);
 /* ---- per-kernel timing, for measurement ------------------------------------------------------------
  * Every kernel launch inside amph_draft / amph_target_forward / amph_verify_attn belongs to one kind.
  * amph_profile_kind selects one kind (or -1 for none): from then on one launch in `every` (>= 1; the
- * first, the every+1-th, ...) of that kind is bracketed by a pair of HIP events on the context's stream,
- * up to max_launches timed launches.  A pair of events costs a few microseconds of stream time, so a
- * caller that also measures end-to-end time samples sparsely.
+ * first, the every+1-th, ...) of that kind is timed by a pair of HIP events, up to max_launches timed
+ * launches.  The matrix-core GEMM kinds (AMPH_K_T_*) pass the events with the launch, so they hold the
+ * kernel's own begin and end time stamps; the other kinds are bracketed by events recorded on the
+ * context's stream (a kind made of two kernels is bracketed as a whole).  A timed launch costs a few
+ * microseconds of stream time, so a caller that also measures end-to-end time samples sparsely.
  * amph_profile_read SYNCHRONISES the stream, returns the summed elapsed time and the number of launches
  * recorded since the last read, and resets the count.  Not for use under stream capture. */
 typedef enum {

@@ -80,6 +80,21 @@ amph_status hip_fail(amph_ctx *ctx, hipError_t e, const char *where) {
     }                                                                                          \
   } while (0)
 
+// The same for a matrix-core GEMM: the launch carries the two events, which then hold the kernel's own begin and
+// end time stamps (no marker on the stream, nothing but the kernel between them).
+#define PROF_GEMM(ctx, kind, T, st, epi, args)                                                 \
+  do {                                                                                         \
+    const bool p__ = ((ctx)->prof_kind == (kind)) && ((ctx)->prof_seen++ % (ctx)->prof_every == 0) && \
+                     ((ctx)->prof_used < (ctx)->prof_ev.size() / 2);                                   \
+    if (p__) {                                                                                 \
+      HIP_TRY(ctx, launch_gemm<T>(st, epi, args, (ctx)->prof_ev[2 * (ctx)->prof_used],         \
+                                  (ctx)->prof_ev[2 * (ctx)->prof_used + 1]));                  \
+      (ctx)->prof_used++;                                                                      \
+    } else {                                                                                   \
+      HIP_TRY(ctx, launch_gemm<T>(st, epi, args));                                             \
+    }                                                                                          \
+  } while (0)
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 WsLayout make_layout(const amph_config &c) {
@@ -263,19 +278,19 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
     GemmArgs a = g;
     a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.wt = lt.qkv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
-    PROF_TRY(ctx, AMPH_K_T_QKV, launch_gemm<T>(st, EPI_QKV_ROPE, a));
+    PROF_GEMM(ctx, AMPH_K_T_QKV, T, st, EPI_QKV_ROPE, a);
     if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
     a = g;
     a.w0 = lw.wo; a.wt = lt.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
-    PROF_TRY(ctx, AMPH_K_T_WO, launch_gemm<T>(st, EPI_STORE, a));
+    PROF_GEMM(ctx, AMPH_K_T_WO, T, st, EPI_STORE, a);
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, nullptr, nullptr, V, slabs, s_wo, slab, lw.rms2, M, d,
                                                         c.rms_eps, xn, nullptr, ctx->dev_status));
     a = g;
     a.w0 = lw.w_gate; a.w1 = lw.w_up; a.wt = lt.gate_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
-    PROF_TRY(ctx, AMPH_K_T_GATEUP, launch_gemm<T>(st, EPI_SWIGLU, a));
+    PROF_GEMM(ctx, AMPH_K_T_GATEUP, T, st, EPI_SWIGLU, a);
     a = g;
     a.w0 = lw.w_down; a.wt = lt.down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = slabs; a.split_k = s_down;
-    PROF_TRY(ctx, AMPH_K_T_DOWN, launch_gemm<T>(st, EPI_STORE, a));
+    PROF_GEMM(ctx, AMPH_K_T_DOWN, T, st, EPI_STORE, a);
     pending = s_down;
   }
   PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, slabs, pending,
@@ -284,7 +299,7 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   a.w0 = lm_head; a.wt = lm_head_tiled; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
   a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
-  PROF_TRY(ctx, AMPH_K_T_LMHEAD, launch_gemm<T>(st, EPI_ARGMAX, a));
+  PROF_GEMM(ctx, AMPH_K_T_LMHEAD, T, st, EPI_ARGMAX, a);
   HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_plan(EPI_ARGMAX, V, d, (int)sizeof(T), M, 1).tiles, M,
                                   tgt_argmax));
   return AMPH_OK;

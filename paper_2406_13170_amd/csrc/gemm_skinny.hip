@@ -34,6 +34,7 @@
 // fixed order; per-tile argmax candidates are folded by k_argmax_fold.  Fused epilogues: RoPE from a
 // precomputed table + KV-cache write, SwiGLU, per-tile row argmax.
 #include "kernels.h"
+#include <hip/hip_ext.h>
 #include <algorithm>
 
 namespace amph {
@@ -429,7 +430,7 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
 }
 
 template <typename T>
-hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in) {
+hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in, hipEvent_t ev_start, hipEvent_t ev_stop) {
   GemmArgs a = a_in;
   if (a.M < 1 || a.Kd < 1 || (a.Kd * (int)sizeof(T)) % 64) return hipErrorInvalidValue;
   if (a.split_k != 1 && a.split_k != 2 && a.split_k != 4 && a.split_k != 8) return hipErrorInvalidValue;
@@ -442,8 +443,13 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in) {
   const long long wgs = (long long)((tiles * a.split_k + 7) / 8) * mblocks * 8;     // see the index mapping in the kernel
   if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)wgs), block(64 * (a.nb + GM_NLW));
-  #define GM_LAUNCH(E)                                                                        \
-    if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, E, true>), grid, block, 0, st, a, tiles);  \
+  // With a pair of events the launch itself carries them: they take the kernel's own begin and end time stamps,
+  // so reading them costs the stream nothing and includes nothing but the kernel.
+  #define GM_LAUNCH(E)                                                                                           \
+    if (ev_start && ev_stop) {                                                                                   \
+      if (a.wt) hipExtLaunchKernelGGL((k_gemm_skinny<T, E, true>), grid, block, 0, st, ev_start, ev_stop, 0, a, tiles);  \
+      else hipExtLaunchKernelGGL((k_gemm_skinny<T, E, false>), grid, block, 0, st, ev_start, ev_stop, 0, a, tiles);      \
+    } else if (a.wt) hipLaunchKernelGGL((k_gemm_skinny<T, E, true>), grid, block, 0, st, a, tiles);              \
     else hipLaunchKernelGGL((k_gemm_skinny<T, E, false>), grid, block, 0, st, a, tiles)
   switch (epi) {
     case EPI_STORE: GM_LAUNCH(EPI_STORE); break;
@@ -455,7 +461,7 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in) {
   #undef GM_LAUNCH
   return hipGetLastError();
 }
-template hipError_t launch_gemm<float>(hipStream_t, int, const GemmArgs &);
-template hipError_t launch_gemm<bf16_t>(hipStream_t, int, const GemmArgs &);
+template hipError_t launch_gemm<float>(hipStream_t, int, const GemmArgs &, hipEvent_t, hipEvent_t);
+template hipError_t launch_gemm<bf16_t>(hipStream_t, int, const GemmArgs &, hipEvent_t, hipEvent_t);
 
 }  // namespace amph

@@ -88,7 +88,9 @@ struct GemmArgs {
 // whatever depends on the plan (partial slabs: split; per-tile argmax candidates: tiles).
 struct GemmPlan { int nb, split, tiles, blocks; };
 GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req);
-template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a);
+// ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end time stamps
+template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a, hipEvent_t ev_start = nullptr,
+                                             hipEvent_t ev_stop = nullptr);
 // bytes of the tiled copy of the matrices of one GEMM, and the kernel that writes it (w0..w2, seg_rows, Kd, n_heads, d_h of a)
 size_t gemm_tiled_bytes(int epi, int seg_rows, int Kd, int elem_bytes);
 template <typename T> hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst);
