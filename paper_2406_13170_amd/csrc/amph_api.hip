@@ -20,7 +20,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {   // byte offsets into the caller's workspace
   size_t x, q, att, y, act, h[2], Hp, Qa, Ka, Va, ctxa, attn_o, logits, topk_ws;                 // draft
-  size_t xres, xn, qb, attb, actb, slabs, amax_val, amax_idx, ver_part, tgt_tmp, rope_cs;      // target
+  size_t xres, xn, qb, attb, actb, slabs, amax_val, amax_idx, ver_part, tgt_tmp, rope_cs, xt;  // target
   size_t slabs_floats, ver_part_floats;
   size_t total;
 };
@@ -117,6 +117,7 @@ WsLayout make_layout(const amph_config &c) {
   w.slabs = take(w.slabs_floats * 4);
   const size_t tilesV = (V + 31) / 32 + 1;      // upper bound on the LM head's tiles (at least two 16-row blocks each)
   w.amax_val = take(tilesV * M * 4); w.amax_idx = take(tilesV * M * 4);
+  w.xt = take(gemm_xt_bytes((int)M, (int)std::max(d, f), (int)esz));     // fragment-tiled activations of the wide GEMM
   size_t vfl = 0;                                           // any tree size up to max_tree may be used
   for (int t = 1; t <= c.max_tree; ++t) vfl = std::max(vfl, verify_ws_floats(c.batch, t, c.n_heads, c.head_dim, c.max_kv, (int)esz));
   w.ver_part = take(vfl * 4);
@@ -261,18 +262,19 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   g.dev_status = ctx->dev_status;
   g.M = M; g.T_nodes = Tn; g.n_heads = n_h; g.d_h = d_h; g.max_kv = c.max_kv;
   g.rope_cs = rope_cs; g.kv_len = kv_len; g.split_k = 1;
-  auto split_for = [&](int rows, int Kd) {
-    int s = gemm_plan(EPI_STORE, rows, Kd, (int)sizeof(T), M, 0).split;
+  g.xt = ws + ctx->ws.xt;
+  auto split_for = [&](int rows, int Kd, bool has_tiled) {
+    int s = gemm_plan(EPI_STORE, rows, Kd, (int)sizeof(T), M, 0, has_tiled).split;
     while (s > 1 && (size_t)s * slab > ctx->ws.slabs_floats) s /= 2;
     return s;
   };
-  const int s_wo = split_for(d, d), s_down = split_for(d, f);
   if (n_layers > 0) HIP_TRY(ctx, launch_rope_table(st, tree_pos, M, d_h, c.rope_theta, rope_cs));
   int pending = 0;                        // slabs of the previous GEMM still to be added to the residual stream
   for (int li = 0; li < n_layers; ++li) {
     const amph_layer_w &lw = layers[li];
     const amph_layer_tiled lt = tiled ? tiled[li] : amph_layer_tiled{nullptr, nullptr, nullptr, nullptr};
     void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
+    const int s_wo = split_for(d, d, lt.wo != nullptr), s_down = split_for(d, f, lt.down != nullptr);
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, slabs, pending,
                                                         slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status));
     GemmArgs a = g;
@@ -300,7 +302,7 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
   a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
   PROF_GEMM(ctx, AMPH_K_T_LMHEAD, T, st, EPI_ARGMAX, a);
-  HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_plan(EPI_ARGMAX, V, d, (int)sizeof(T), M, 1).tiles, M,
+  HIP_TRY(ctx, launch_argmax_fold(st, a.amax_val, a.amax_idx, gemm_plan(EPI_ARGMAX, V, d, (int)sizeof(T), M, 1, lm_head_tiled != nullptr).tiles, M,
                                   tgt_argmax));
   return AMPH_OK;
 }
@@ -680,7 +682,7 @@ amph_status amph_gemm(amph_ctx *ctx, const void *x, const void *W, float *y, int
   if (!x || !W || !y || !workspace || !aligned16(x) || !aligned16(W) || !aligned16(workspace))
     return fail(ctx, AMPH_EINVAL, "amph_gemm: null or misaligned argument");
   if (M < 1 || N < 1 || Kd < 1 || (Kd * ctx->esz) % 64) return fail(ctx, AMPH_ESHAPE, "amph_gemm: a row of x must be a multiple of 64 bytes");
-  if (split_k == 0) split_k = gemm_plan(EPI_STORE, N, Kd, ctx->esz, M, 0).split;
+  if (split_k == 0) split_k = gemm_plan(EPI_STORE, N, Kd, ctx->esz, M, 0, false).split;
   if (split_k != 1 && split_k != 2 && split_k != 4 && split_k != 8) return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k");
   if (split_k > 1 && (size_t)split_k * M * N > ctx->ws.slabs_floats)
     return fail(ctx, AMPH_ESHAPE, "amph_gemm: split_k * M * N exceeds the workspace's slab area");

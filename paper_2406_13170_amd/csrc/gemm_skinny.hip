@@ -1,6 +1,6 @@
-// Skinny GEMM for the target's forward pass over the tree tokens (Sec. 2 "Tree Attention"): M = B*T
-// activation rows (64 per block) against [N, Kd] weights that stream from HBM once, on the matrix
-// cores.
+// GEMMs of the target's forward pass over the tree tokens (Sec. 2 "Tree Attention"): M = B*T activation rows
+// against [N, Kd] weights that stream from HBM once, on the matrix cores.  Two kernels: the skinny one
+// (described first; up to four blocks of 64 rows) and the wide one (further down; five blocks or more).
 //
 // The unit of work is a ROW BLOCK: 16 weight rows that one wave keeps as matrix-core A fragments and
 // whose outputs need nothing from any other block:
@@ -83,6 +83,104 @@ __device__ __forceinline__ RowMap map_block(const GemmArgs &a, int b, int r16) {
   return o;
 }
 
+// Epilogue of one 64-row block of a workgroup's output tile: Ct[m][r] (float32, pitch CT_PITCH) holds rows
+// m_base .. m_base + 63 of the activations against the tile's nb row blocks (BN = 16 * nb columns).  Every thread
+// of the workgroup (NT of them) takes part.
+template <typename T, int EPI>
+__device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct, int CT_PITCH, int tile, int nb, int m_base,
+                                              int split, int nblk, int tid, int NT) {
+  const int BN = 16 * nb;
+  if (EPI == EPI_STORE) {
+    // out is [split_k][M][N]: slab `split` receives this workgroup's partial sums
+    const int N = a.seg_rows;
+    float *slab = a.out + (size_t)split * a.M * N;
+    for (int idx = tid; idx < GM_BM * BN; idx += NT) {
+      const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
+      if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
+    }
+  } else if (EPI == EPI_SWIGLU) {
+    // block w of the tile: columns 0..7 = gate rows, 8..15 = the same rows of up
+    const int f = a.seg_rows, H = 8 * nb;
+    T *act = (T *)a.act;
+    for (int idx = tid; idx < GM_BM * H; idx += NT) {
+      const int m = idx / H, jj = idx % H, w = jj >> 3, j8 = jj & 7, mg = m_base + m, j = tile * H + jj;
+      if (mg < a.M && j < f)
+        act[(size_t)mg * f + j] =
+            Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + w * 16 + j8]) * Ct[m * CT_PITCH + w * 16 + 8 + j8]);
+    }
+  } else if (EPI == EPI_QKV_ROPE) {
+    // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
+    const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
+    for (int idx = tid; idx < nb * 512; idx += NT) {
+      const int w = idx >> 9, rem = idx & 511, b = tile * nb + w;
+      if (b >= nblk) continue;
+      const int seg = b / bps, bl = b % bps;
+      if (seg < 2) {
+        const int m = rem >> 3, j = rem & 7, mg = m_base + m;
+        if (mg >= a.M) continue;
+        const int head = bl / bph, e = (bl % bph) * 8 + j;
+        const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
+        const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
+        const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
+        if (seg == 0) {
+          T *q = (T *)a.q_out + (size_t)mg * d + head * d_h + e;
+          q[0] = Elem<T>::from_f32(y1);
+          q[half] = Elem<T>::from_f32(y2);
+        } else {
+          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+          if (L < 0 || L + a.T_nodes > a.max_kv) {
+            if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
+            continue;
+          }
+          T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+          kc[k_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(y1);
+          kc[k_tiled_index<T>(L + node, e + half, d_h)] = Elem<T>::from_f32(y2);
+        }
+      } else {
+        // values: consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
+        const int j = rem >> 6, m = rem & 63, mg = m_base + m;
+        if (mg >= a.M) continue;
+        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+        if (L < 0 || L + a.T_nodes > a.max_kv) continue;
+        #pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
+          T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+          vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
+        }
+      }
+    }
+  } else if (EPI == EPI_ARGMAX) {
+    const int N = a.seg_rows;
+    if (a.logits) {
+      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
+        const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
+        if (mg < a.M && n < N) a.logits[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
+      }
+    }
+    // 4 threads per token row, BN/4 columns each, then a 4-lane butterfly (ties -> lower column)
+    for (int t4 = tid; t4 < 4 * GM_BM; t4 += NT) {        // NT is a multiple of 64: the 4 lanes of a row stay in one wave
+      const int m = t4 >> 2, part = t4 & 3, mg = m_base + m;
+      float bv = -__builtin_huge_valf(); int bi = 0x7fffffff;
+      for (int r = part * (BN / 4); r < (part + 1) * (BN / 4); ++r) {
+        const int n = tile * BN + r;
+        const float v = Ct[m * CT_PITCH + r];
+        if (n < N && (v > bv || (v == bv && n < bi))) { bv = v; bi = n; }
+      }
+      #pragma unroll
+      for (int off = 1; off <= 2; off <<= 1) {
+        const float ov = __shfl_xor(bv, off, WAVE);
+        const int oi = __shfl_xor(bi, off, WAVE);
+        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      }
+      if (part == 0 && mg < a.M) {
+        a.amax_val[(size_t)tile * a.M + mg] = bv;
+        a.amax_idx[(size_t)tile * a.M + mg] = bi;
+      }
+    }
+  }
+}
+
 template <typename T, int EPI, bool TILED>
 __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const GemmArgs a, int tiles) {
   __shared__ __align__(16) unsigned char lds[GM_LDS_BYTES];
@@ -133,7 +231,7 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
         // load at the merge).  Steps past the slice re-read its last step: harmless, because the activation
         // tile is zero there and weights are finite; rows past N re-read row 0 and are never stored.
         const int st = min(s0 + c * GM_STEPS + s, s1 - 1);
-        af[s] = ldg16(wrow + (size_t)st * (TILED ? 1024 : 64));
+        af[s] = ldg16_stream(wrow + (size_t)st * (TILED ? 1024 : 64));
       }
     };
     load_w(0, aw[0]);
@@ -205,96 +303,179 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
   }
   __syncthreads();
 
-  // ---------------------------------------------------------------------------------- epilogues
-  if (EPI == EPI_STORE) {
-    // out is [split_k][M][N]: slab `split` receives this workgroup's partial sums
-    const int N = a.seg_rows;
-    float *slab = a.out + (size_t)split * a.M * N;
-    for (int idx = tid; idx < GM_BM * BN; idx += NT) {
-      const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
-      if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
-    }
-  } else if (EPI == EPI_SWIGLU) {
-    // block w of the tile: columns 0..7 = gate rows, 8..15 = the same rows of up
-    const int f = a.seg_rows, H = 8 * nb;
-    T *act = (T *)a.act;
-    for (int idx = tid; idx < GM_BM * H; idx += NT) {
-      const int m = idx / H, jj = idx % H, w = jj >> 3, j8 = jj & 7, mg = m_base + m, j = tile * H + jj;
-      if (mg < a.M && j < f)
-        act[(size_t)mg * f + j] =
-            Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + w * 16 + j8]) * Ct[m * CT_PITCH + w * 16 + 8 + j8]);
-    }
-  } else if (EPI == EPI_QKV_ROPE) {
-    // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
-    const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
-    for (int idx = tid; idx < nb * 512; idx += NT) {
-      const int w = idx >> 9, rem = idx & 511, b = tile * nb + w;
-      if (b >= nblk) continue;
-      const int seg = b / bps, bl = b % bps;
-      if (seg < 2) {
-        const int m = rem >> 3, j = rem & 7, mg = m_base + m;
-        if (mg >= a.M) continue;
-        const int head = bl / bph, e = (bl % bph) * 8 + j;
-        const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
-        const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
-        const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
-        if (seg == 0) {
-          T *q = (T *)a.q_out + (size_t)mg * d + head * d_h + e;
-          q[0] = Elem<T>::from_f32(y1);
-          q[half] = Elem<T>::from_f32(y2);
-        } else {
-          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-          if (L < 0 || L + a.T_nodes > a.max_kv) {
-            if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
-            continue;
-          }
-          T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-          kc[k_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(y1);
-          kc[k_tiled_index<T>(L + node, e + half, d_h)] = Elem<T>::from_f32(y2);
-        }
-      } else {
-        // values: consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
-        const int j = rem >> 6, m = rem & 63, mg = m_base + m;
-        if (mg >= a.M) continue;
-        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-        if (L < 0 || L + a.T_nodes > a.max_kv) continue;
-        #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
-          T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-          vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
-        }
-      }
-    }
-  } else if (EPI == EPI_ARGMAX) {
-    const int N = a.seg_rows;
-    if (a.logits) {
-      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
-        const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
-        if (mg < a.M && n < N) a.logits[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
-      }
-    }
-    // 4 threads per token row (the first four waves), BN/4 columns each, then a 4-lane butterfly
-    // (ties -> lower column)
-    if (tid < 4 * GM_BM) {
-      const int m = tid >> 2, part = tid & 3, mg = m_base + m;
-      float bv = -__builtin_huge_valf(); int bi = 0x7fffffff;
-      for (int r = part * (BN / 4); r < (part + 1) * (BN / 4); ++r) {
-        const int n = tile * BN + r;
-        const float v = Ct[m * CT_PITCH + r];
-        if (n < N && (v > bv || (v == bv && n < bi))) { bv = v; bi = n; }
-      }
+  gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, nb, m_base, split, nblk, tid, NT);
+}
+
+// =====================================================================================================
+// Wide GEMM: 128 or more activation rows (batches of trees).  The skinny kernel above re-reads the weights
+// from L2 once per block of 64 rows, every math wave re-reads the whole activation chunk from LDS, and its
+// 16 x 16 matrix-core instruction runs at half the rate of the 32 x 32 one: with several blocks of rows L2, LDS
+// and the matrix cores, not HBM, set the pace.  Here a workgroup owns ALL activation rows (up to 384) of NB weight
+// row blocks, and the roles of the operands are swapped:
+//   * the weights are the shared operand: two loader waves stream the workgroup's NB blocks from HBM straight
+//     into a ring of LDS stages (global-to-LDS loads, 8 steps of 64 bytes of k per stage), so they cross L2 once;
+//   * each math wave owns 64 activation rows (two 32-row tiles) against all NB blocks, taken in pairs (32 weight
+//     rows): per step and half-step it reads one weight fragment per pair from LDS and 2 activation fragments from
+//     global memory (L2 hits, requested GW_XD steps ahead into registers) and issues 2 matrix-core instructions
+//     of 32 x 32 per pair; one barrier per 8 steps.
+// A 32 x 32 instruction takes, per lane (half, r), 16 bytes of row r: the bytes [half * 16, half * 16 + 16) of
+// 32 bytes of k.  The weight fragments in LDS are the 16-row x 64-byte ones of the tiled layout, piece (g, r16)
+// at (g * 16 + r16) * 16: lane (half, r) of half-step h reads piece (2h + half, r % 16) of block r / 16 of the
+// pair, 16 lanes per 256 contiguous bytes.  The activations must be tiled to match (a fragment gathered from
+// row-major rows is the slow many-half-lines load): k_tile_rows rewrites [M, Kd] as
+// xt[(q * m32_tiles + tile) * 1024 + lane * 16], q = index of 32 bytes of k, lane = half * 32 + row % 32, rows
+// past M as zeros (a few microseconds).
+// =====================================================================================================
+constexpr int GW_STEPS = 8;        // steps (64 bytes of k) per weight stage
+constexpr int GW_R = 3;            // weight stages in the LDS ring
+constexpr int GW_NL = 2;           // loader waves
+constexpr int GW_MAX_NP = 3;       // pairs of weight row blocks per workgroup
+constexpr int GW_MAX_NW = 6;       // math waves = blocks of 64 activation rows per workgroup
+constexpr int GW_XD = 4;           // steps of activations requested ahead
+constexpr int GW_MIN_MBLOCKS = 5;  // blocks of 64 activation rows from which the wide kernel is used
+constexpr int GW_AUX_NT = 2;       // cache-policy bits of the global-to-LDS load: non-temporal (the weights are read once)
+static_assert(GW_STEPS % GW_XD == 0, "the activation ring is indexed statically inside a stage");
+
+template <int N> __device__ __forceinline__ void gw_wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_tile_rows(const unsigned char *x, int M, int row_bytes, int m32_tiles, unsigned char *xt) {
+  const int qn = row_bytes / 32;
+  const size_t pieces = (size_t)qn * m32_tiles * 64;
+  for (size_t p = (size_t)blockIdx.x * 256 + threadIdx.x; p < pieces; p += (size_t)gridDim.x * 256) {
+    const int lane = (int)(p & 63), half = lane >> 5, r32 = lane & 31;
+    const size_t frag = p >> 6;
+    const int mt = (int)(frag % m32_tiles), q = (int)(frag / m32_tiles);
+    const int m = mt * 32 + r32;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (m < M) v = ldg16(x + (size_t)m * row_bytes + (size_t)q * 32 + half * 16);
+    stg16(xt + p * 16, v);
+  }
+}
+
+template <typename T, int EPI, int NP>
+__global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const GemmArgs a, int tiles, int mgroups, int m32_tiles) {
+  extern __shared__ __align__(16) unsigned char gw_lds[];
+  constexpr int NB = 2 * NP, STAGE = NB * GW_STEPS * 1024, PERL = NB * GW_STEPS / GW_NL;
+  static_assert(GW_R == 3 && PERL * (GW_R - 2) <= 63, "loader wave's outstanding loads");
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int NT = blockDim.x, nw = (NT >> 6) - GW_NL;       // math waves
+  const int S = a.split_k;
+  const int id = blockIdx.x, unit = (id / 8 / mgroups) * 8 + (id & 7), mgroup = (id / 8) % mgroups;
+  if (unit >= tiles * S) return;                          // padding of the last group of 8 units (whole workgroup)
+  const int tile = unit / S, split = unit % S;
+  const int m_group = mgroup * nw * GM_BM;
+  const int total_steps = a.Kd * (int)sizeof(T) / 64;
+  const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
+  const int n = s1 - s0;
+  const int P = (n + GW_STEPS - 1) / GW_STEPS;             // weight stages
+  const int nblk = gemm_blocks(EPI, a.seg_rows);
+
+  f32x16 acc[NP][2];
+  #pragma unroll
+  for (int p = 0; p < NP; ++p)
+    #pragma unroll
+    for (int t = 0; t < 2; ++t)
       #pragma unroll
-      for (int off = 1; off <= 2; off <<= 1) {
-        const float ov = __shfl_xor(bv, off, WAVE);
-        const int oi = __shfl_xor(bi, off, WAVE);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+      for (int i = 0; i < 16; ++i) acc[p][t][i] = 0.f;
+
+  if (wave >= nw) {
+    // ---------------------------------------------------------------------------- loader wave
+    // fragments l, l + 2, ... of a stage; fragment f = block (f / 8), step (f % 8).  Lane (g, r16) fetches piece g
+    // of row r16, which lands at (g * 16 + r16) * 16 of the fragment's KB in LDS.  Steps past the slice (last
+    // stage) re-read its last step and are never used.
+    const int l = wave - nw, g = lane >> 4, r16 = lane & 15;
+    const unsigned char *wbase = (const unsigned char *)a.wt + r16 * 64 + g * 16;
+    auto issue = [&](int p) {
+      unsigned char *lp = gw_lds + (p % GW_R) * STAGE;
+      #pragma unroll
+      for (int j = 0; j < PERL; ++j) {
+        const int f = l + j * GW_NL, b = f / GW_STEPS, s = f % GW_STEPS;
+        const int blk = min(tile * NB + b, nblk - 1);
+        const int st = min(s0 + p * GW_STEPS + s, s1 - 1);
+        const unsigned char *src = wbase + ((size_t)blk * total_steps + st) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)(lp + f * 1024), 16, 0, GW_AUX_NT);
       }
-      if (part == 0 && mg < a.M) {
-        a.amax_val[(size_t)tile * a.M + mg] = bv;
-        a.amax_idx[(size_t)tile * a.M + mg] = bi;
+    };
+    const int pro = P < GW_R - 1 ? P : GW_R - 1;
+    for (int p = 0; p < pro; ++p) issue(p);
+    for (int p = 0; p < P; ++p) {
+      if (p + 1 < P) gw_wait_vm<PERL>(); else gw_wait_vm<0>();   // stage p has landed (one younger stage may be in flight)
+      __builtin_amdgcn_s_barrier();                        // math waves may read stage p; they are done with stage p - 1
+      if (p + GW_R - 1 < P) issue(p + GW_R - 1);           // into the slot of stage p - 1
+    }
+  } else {
+    // ------------------------------------------------------------------------------ math wave
+    // activation tiles 2 * wave, 2 * wave + 1 of the group (32 rows each); the 4 fragments of a step (two halves of
+    // the step's 64 bytes, two tiles) are requested GW_XD steps ahead
+    const int half = lane >> 5, r32 = lane & 31;
+    const int mt0 = (m_group >> 5) + 2 * wave;
+    const unsigned char *xb = (const unsigned char *)a.xt + lane * 16;
+    uint4 xq[GW_XD][2][2];
+    auto load_x = [&](int i, uint4 (&xf)[2][2]) {
+      const int st = s0 + max(min(i, n - 1), 0);           // unconditional: steps past the slice re-read the last one
+      #pragma unroll
+      for (int h = 0; h < 2; ++h)
+        #pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const int mt = min(mt0 + t, m32_tiles - 1);      // tiles past the end (last wave) re-read the last tile; never stored
+          xf[h][t] = ldg16(xb + ((size_t)(2 * st + h) * m32_tiles + mt) * 1024);
+        }
+    };
+    // weight piece of this lane inside a pair's two fragments of a step, for half-step h: + h * 512
+    const int woff = (r32 >> 4) * (GW_STEPS * 1024) + (half * 16 + (r32 & 15)) * 16;
+    #pragma unroll
+    for (int i = 0; i < GW_XD; ++i) load_x(i, xq[i]);
+    for (int p = 0; p < P; ++p) {
+      // Stage p is in LDS (pairs with the loaders' barrier).  A bare barrier: __syncthreads() would also wait for this
+      // wave's outstanding activation loads (the fence it carries counts them since the kernel contains global-to-LDS
+      // loads) and drain the prefetch ring at every stage.  The "memory" clobber keeps the LDS reads below it; the
+      // reads of stage p - 1 are complete because the matrix-core instructions that used them have been issued.
+      asm volatile("s_barrier" ::: "memory");
+      const unsigned char *sb = gw_lds + (p % GW_R) * STAGE + woff;
+      #pragma unroll
+      for (int s = 0; s < GW_STEPS; ++s) {
+        const int i = p * GW_STEPS + s;
+        if (i < n) {                                       // wave-uniform
+          #pragma unroll
+          for (int h = 0; h < 2; ++h)
+            #pragma unroll
+            for (int pr = 0; pr < NP; ++pr) {
+              const uint4 wf = *reinterpret_cast<const uint4 *>(sb + (2 * pr * GW_STEPS + s) * 1024 + h * 512);
+              #pragma unroll
+              for (int t = 0; t < 2; ++t) acc[pr][t] = mma32<T>(wf, xq[s % GW_XD][h][t], acc[pr][t]);
+            }
+        }
+        load_x(i + GW_XD, xq[s % GW_XD]);
       }
     }
+  }
+
+  // ---- epilogues: every math wave handles its own 64 activation rows through its own Ct region in LDS (the ring is
+  // free by now), the 64 lanes playing the workgroup of the shared epilogue code.  Lane (half, r32) holds activation
+  // row t * 32 + r32 and weight rows (i / 4) * 8 + half * 4 + (i % 4) of each pair.
+  const int CT_PITCH = 16 * NB + 4;
+  __syncthreads();                                         // every wave has left the ring
+  const int m_base = m_group + wave * GM_BM;
+  if (wave < nw && m_base < a.M) {                         // whole waves
+    float *Ct = reinterpret_cast<float *>(gw_lds) + (size_t)wave * GM_BM * CT_PITCH;
+    const int half = lane >> 5, r32 = lane & 31;
+    #pragma unroll
+    for (int pr = 0; pr < NP; ++pr)
+      #pragma unroll
+      for (int t = 0; t < 2; ++t)
+        #pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 v = {acc[pr][t][4 * q4], acc[pr][t][4 * q4 + 1], acc[pr][t][4 * q4 + 2], acc[pr][t][4 * q4 + 3]};
+          *reinterpret_cast<f32x4 *>(Ct + (t * 32 + r32) * CT_PITCH + pr * 32 + q4 * 8 + half * 4) = v;
+        }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's LDS writes before its lanes read each other's
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, NB, m_base, split, nblk, lane, WAVE);
   }
 }
 
@@ -405,7 +586,7 @@ hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32
 // is that times the number of rounds the grid needs on 256 CUs; every split beyond the first costs the
 // write and the later read of one more float32 slab.  The two constants are fitted to measurements of
 // the 7B shapes (Wo: 4 blocks x 4 splits beats 2 x 2 and 8 x 8; down: 4 x 4 beats 8 x 8).
-GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req) {
+GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req, bool tiled) {
   GemmPlan best{};
   const int blocks = gemm_blocks(epi, seg_rows);
   const int total_steps = Kd * elem_bytes / 64;
@@ -413,6 +594,31 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   const bool fused = epi != EPI_STORE;
   const double slab_units = fused ? 0.0 : (double)M * seg_rows * 1.0e-4 + 2.0;   // per extra split
   double best_cost = 1e300;
+  best.blocks = blocks;
+  // measured at 7B shapes: 2 blocks of 64 rows 7.3 ms per step wide against 5.7 skinny, 4 blocks 8.8 against 8.3,
+  // 8 blocks 13.5 against 14.5; 33B shapes, 6 blocks: 50.0 against 59.1
+  best.wide = tiled && mblocks >= GW_MIN_MBLOCKS;
+  if (best.wide) {
+    // all activation rows in one workgroup (groups of at most GW_MAX_NW blocks of 64): a step costs the math waves
+    // 4 * nb matrix-core instructions and the chip nb weight fragments per workgroup
+    best.mgroups = (mblocks + GW_MAX_NW - 1) / GW_MAX_NW;
+    best.nw = (mblocks + best.mgroups - 1) / best.mgroups;
+    for (int s = 1; s <= 8; s *= 2) {
+      if (split_req > 0 && s != split_req) continue;
+      if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GW_STEPS))) continue;
+      for (int nb = 2; nb <= 2 * GW_MAX_NP; nb += 2) {      // blocks are taken in pairs
+        if (nb > std::max(blocks, 2)) break;
+        const int tiles = (blocks + nb - 1) / nb;
+        const long wgs = (long)tiles * s * best.mgroups;
+        const long rounds = (wgs + 255) / 256;
+        const double cost = (double)rounds * ((total_steps + s - 1) / s) * (nb + 2) + slab_units * (s - 1);
+        if (cost <= best_cost) { best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles; }
+      }
+    }
+    return best;
+  }
+  best.mgroups = mblocks;
+  best.nw = 1;
   for (int s = 1; s <= 8; s *= 2) {
     if (split_req > 0 && s != split_req) continue;
     if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GM_STEPS))) continue;
@@ -425,8 +631,47 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
       if (cost <= best_cost) { best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles; }
     }
   }
-  best.blocks = blocks;
   return best;
+}
+
+size_t gemm_xt_bytes(int M, int Kd, int elem_bytes) { return (size_t)((M + 31) / 32) * 32 * (size_t)Kd * elem_bytes; }
+
+template <typename T, int EPI, int NP>
+static hipError_t launch_wide_np(hipStream_t st, const GemmArgs &a, const GemmPlan &pl, int m32_tiles, dim3 grid, dim3 block,
+                                 hipEvent_t ev_start, hipEvent_t ev_stop) {
+  // the weight ring, or (afterwards, in the same memory) one float32 output tile of 64 rows per math wave
+  constexpr size_t ring = (size_t)GW_R * 2 * NP * GW_STEPS * 1024, ct_wave = (size_t)GM_BM * (32 * NP + 4) * 4;
+  constexpr size_t smem_max = ring > GW_MAX_NW * ct_wave ? ring : GW_MAX_NW * ct_wave;
+  static_assert(smem_max <= 160 * 1024, "LDS of one workgroup");
+  const size_t smem = std::max(ring, (size_t)pl.nw * ct_wave);
+  static bool attr_set = false;                           // once per instantiation and process
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void *)k_gemm_wide<T, EPI, NP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (ev_start && ev_stop)
+    hipExtLaunchKernelGGL((k_gemm_wide<T, EPI, NP>), grid, block, smem, st, ev_start, ev_stop, 0, a, pl.tiles, pl.mgroups, m32_tiles);
+  else
+    hipLaunchKernelGGL((k_gemm_wide<T, EPI, NP>), grid, block, smem, st, a, pl.tiles, pl.mgroups, m32_tiles);
+  return hipGetLastError();
+}
+
+template <typename T, int EPI>
+static hipError_t launch_wide(hipStream_t st, const GemmArgs &a, const GemmPlan &pl, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  if (!a.wt || !a.xt || pl.nw < 1 || pl.nw > GW_MAX_NW || pl.nb < 2 || pl.nb > 2 * GW_MAX_NP || pl.nb % 2) return hipErrorInvalidValue;
+  const int m32_tiles = (a.M + 31) / 32, row_bytes = a.Kd * (int)sizeof(T);
+  const size_t pieces = (size_t)(row_bytes / 32) * m32_tiles * 64;
+  hipLaunchKernelGGL((k_tile_rows<T>), dim3((unsigned)std::min<size_t>((pieces + 255) / 256, 4096)), dim3(256), 0, st,
+                     (const unsigned char *)a.x, a.M, row_bytes, m32_tiles, (unsigned char *)a.xt);
+  const long long wgs = (long long)((pl.tiles * a.split_k + 7) / 8) * pl.mgroups * 8;
+  if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)wgs), block(64 * (pl.nw + GW_NL));
+  switch (pl.nb / 2) {
+    case 1: return launch_wide_np<T, EPI, 1>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    case 2: return launch_wide_np<T, EPI, 2>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    default: return launch_wide_np<T, EPI, 3>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
+  }
 }
 
 template <typename T>
@@ -436,8 +681,17 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in, hipEvent_t
   if (a.split_k != 1 && a.split_k != 2 && a.split_k != 4 && a.split_k != 8) return hipErrorInvalidValue;
   if (epi != EPI_STORE && a.split_k != 1) return hipErrorInvalidValue;     // fused epilogues need complete sums
   if (epi == EPI_QKV_ROPE && (a.d_h % 16 || a.seg_rows != a.n_heads * a.d_h || !a.rope_cs)) return hipErrorInvalidValue;
-  const GemmPlan pl = gemm_plan(epi, a.seg_rows, a.Kd, (int)sizeof(T), a.M, a.split_k);
+  const GemmPlan pl = gemm_plan(epi, a.seg_rows, a.Kd, (int)sizeof(T), a.M, a.split_k, a.wt != nullptr && a.xt != nullptr);
   a.nb = pl.nb;
+  if (pl.wide) {
+    switch (epi) {
+      case EPI_STORE: return launch_wide<T, EPI_STORE>(st, a, pl, ev_start, ev_stop);
+      case EPI_QKV_ROPE: return launch_wide<T, EPI_QKV_ROPE>(st, a, pl, ev_start, ev_stop);
+      case EPI_SWIGLU: return launch_wide<T, EPI_SWIGLU>(st, a, pl, ev_start, ev_stop);
+      case EPI_ARGMAX: return launch_wide<T, EPI_ARGMAX>(st, a, pl, ev_start, ev_stop);
+      default: return hipErrorInvalidValue;
+    }
+  }
   const int tiles = pl.tiles;
   const int mblocks = (a.M + GM_BM - 1) / GM_BM;
   const long long wgs = (long long)((tiles * a.split_k + 7) / 8) * mblocks * 8;     // see the index mapping in the kernel

@@ -46,7 +46,7 @@ __device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const fl
       // Unconditional loads (a predicated load with a zero alternative makes the compiler wait for every
       // load at the merge).  Lanes past the end re-read the row's first fragment; x is zero-padded there
       // and weights are finite, so they add nothing.
-      for (int r = 0; r < GV_R; ++r) w[u][r] = ldg16(rows[r] + (k < Kd ? k : 0));
+      for (int r = 0; r < GV_R; ++r) w[u][r] = ldg16_stream(rows[r] + (k < Kd ? k : 0));
     }
     #pragma unroll
     for (int u = 0; u < GV_U; ++u) {

@@ -65,6 +65,7 @@ struct GemmArgs {
   int n_seg, seg_rows;        // rows per matrix
   int Kd;
   const void *x;              // [M, Kd] T
+  void *xt;                   // scratch of gemm_xt_bytes(M, Kd): fragment-tiled copy of x for the wide kernel, or NULL
   int M;
   int split_k;                // 1, 2, 4, 8 (fused epilogues: 1)
   int nb;                     // row blocks per workgroup: filled in by launch_gemm from gemm_plan
@@ -84,10 +85,12 @@ struct GemmArgs {
   uint32_t *dev_status;
 };
 // Tile height (row blocks per workgroup), reduction split and resulting tile count of one GEMM.  split_req: 0 lets
-// the plan choose (fused epilogues always 1), else the caller's split.  The same call must be used to size
+// the plan choose (fused epilogues always 1), else the caller's split; tiled: the launch will have both GemmArgs::wt
+// and GemmArgs::xt (then 128 rows or more go to the wide kernel).  The same call must be used to size
 // whatever depends on the plan (partial slabs: split; per-tile argmax candidates: tiles).
-struct GemmPlan { int nb, split, tiles, blocks; };
-GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req);
+struct GemmPlan { int nb, split, tiles, blocks; bool wide; int mgroups, nw; };   // wide: all rows in one workgroup (nw blocks of 64)
+GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req, bool tiled);
+size_t gemm_xt_bytes(int M, int Kd, int elem_bytes);
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end time stamps
 template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a, hipEvent_t ev_start = nullptr,
                                              hipEvent_t ev_stop = nullptr);

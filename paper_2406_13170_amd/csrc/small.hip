@@ -47,8 +47,8 @@ __global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, c
     #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = min(jb + u * G + grp, n - 1);     // unconditional loads; rows past the end are skipped below
-      kf[u] = ldg16(kbase + (size_t)j * DH + li * PER);
-      vf[u] = ldg16(vbase + (size_t)j * DH + li * PER);
+      kf[u] = ldg16_stream(kbase + (size_t)j * DH + li * PER);
+      vf[u] = ldg16_stream(vbase + (size_t)j * DH + li * PER);
     }
     #pragma unroll
     for (int u = 0; u < U; ++u) {
