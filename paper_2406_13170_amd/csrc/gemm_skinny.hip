@@ -94,60 +94,93 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
     // out is [split_k][M][N]: slab `split` receives this workgroup's partial sums
     const int N = a.seg_rows;
     float *slab = a.out + (size_t)split * a.M * N;
-    for (int idx = tid; idx < GM_BM * BN; idx += NT) {
-      const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
-      if (mg < a.M && n < N) slab[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
+    const int Q = BN / 4;                                   // 4 adjacent columns per thread (one by one in a ragged last tile)
+    for (int idx = tid; idx < GM_BM * Q; idx += NT) {
+      const int m = idx / Q, r = (idx % Q) * 4, mg = m_base + m, n = tile * BN + r;
+      if (mg >= a.M || n >= N) continue;
+      const f32x4 v = *reinterpret_cast<const f32x4 *>(Ct + m * CT_PITCH + r);
+      float *dst = slab + (size_t)mg * N + n;
+      if (n + 4 <= N && (N & 3) == 0) {
+        *reinterpret_cast<f32x4 *>(dst) = v;
+      } else {
+        for (int c = 0; c < 4 && n + c < N; ++c) dst[c] = v[c];
+      }
     }
   } else if (EPI == EPI_SWIGLU) {
     // block w of the tile: columns 0..7 = gate rows, 8..15 = the same rows of up
     const int f = a.seg_rows, H = 8 * nb;
     T *act = (T *)a.act;
-    for (int idx = tid; idx < GM_BM * H; idx += NT) {
-      const int m = idx / H, jj = idx % H, w = jj >> 3, j8 = jj & 7, mg = m_base + m, j = tile * H + jj;
-      if (mg < a.M && j < f)
-        act[(size_t)mg * f + j] =
-            Elem<T>::from_f32(silu_f(Ct[m * CT_PITCH + w * 16 + j8]) * Ct[m * CT_PITCH + w * 16 + 8 + j8]);
+    // one (token, block) per thread: 8 adjacent outputs leave as one piece (element by element in a ragged last block)
+    for (int idx = tid; idx < GM_BM * nb; idx += NT) {
+      const int m = idx / nb, w = idx % nb, mg = m_base + m, j0 = tile * H + w * 8;
+      if (mg >= a.M || j0 >= f) continue;
+      const float *crow = Ct + m * CT_PITCH + w * 16;
+      float y[8];
+      #pragma unroll
+      for (int j = 0; j < 8; ++j) y[j] = silu_f(crow[j]) * crow[8 + j];
+      T *dst = act + (size_t)mg * f + j0;
+      if (j0 + 8 <= f && (f & 7) == 0) {
+        store4<T>(dst, y); store4<T>(dst + 4, y + 4);
+      } else {
+        for (int j = 0; j < 8 && j0 + j < f; ++j) dst[j] = Elem<T>::from_f32(y[j]);
+      }
     }
   } else if (EPI == EPI_QKV_ROPE) {
-    // 512 items per row block (64 tokens x 8), so a wave's 64 items always belong to one block
     const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
+    // q and k blocks: one (block, token) per thread = 8 rotation pairs.  Everything the item needs from global
+    // memory (64 bytes of the cos/sin table) is requested at once, and the 8 + 8 results leave as 16-byte pieces:
+    // dims e0 .. e0+7 (and their partners at + d_h/2) are adjacent in q and inside a fragment of the tiled K cache.
+    for (int idx = tid; idx < nb * GM_BM; idx += NT) {
+      const int w = idx / GM_BM, m = idx % GM_BM, b = tile * nb + w, mg = m_base + m;
+      if (b >= nblk || mg >= a.M) continue;
+      const int seg = b / bps, bl = b % bps;
+      if (seg >= 2) continue;
+      const int head = bl / bph, e0 = (bl % bph) * 8;
+      const float4 *csp = reinterpret_cast<const float4 *>(a.rope_cs + (size_t)mg * half + e0);   // (cos, sin) x 8
+      const float4 c01 = csp[0], c23 = csp[1], c45 = csp[2], c67 = csp[3];
+      const float cs[8] = {c01.x, c01.z, c23.x, c23.z, c45.x, c45.z, c67.x, c67.z};
+      const float sn[8] = {c01.y, c01.w, c23.y, c23.w, c45.y, c45.w, c67.y, c67.w};
+      const float *crow = Ct + m * CT_PITCH + w * 16;
+      float y1[8], y2[8];
+      #pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float x1 = crow[j], x2 = crow[8 + j];
+        y1[j] = x1 * cs[j] - x2 * sn[j];
+        y2[j] = x2 * cs[j] + x1 * sn[j];
+      }
+      T *dst1, *dst2;
+      if (seg == 0) {
+        dst1 = (T *)a.q_out + (size_t)mg * d + head * d_h + e0;
+        dst2 = dst1 + half;
+      } else {
+        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+        if (L < 0 || L + a.T_nodes > a.max_kv) {
+          if (node == 0 && e0 == 0) atomicOr(a.dev_status, 2u);
+          continue;
+        }
+        T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+        dst1 = kc + k_tiled_index<T>(L + node, e0, d_h);
+        dst2 = kc + k_tiled_index<T>(L + node, e0 + half, d_h);
+      }
+      store4<T>(dst1, y1); store4<T>(dst1 + 4, y1 + 4);
+      store4<T>(dst2, y2); store4<T>(dst2 + 4, y2 + 4);
+    }
+    // v blocks: 512 items per row block (8 dims x 64 tokens), so a wave's 64 items always belong to one block
     for (int idx = tid; idx < nb * 512; idx += NT) {
       const int w = idx >> 9, rem = idx & 511, b = tile * nb + w;
       if (b >= nblk) continue;
       const int seg = b / bps, bl = b % bps;
-      if (seg < 2) {
-        const int m = rem >> 3, j = rem & 7, mg = m_base + m;
-        if (mg >= a.M) continue;
-        const int head = bl / bph, e = (bl % bph) * 8 + j;
-        const float2 cs = a.rope_cs[(size_t)mg * half + e];          // (cos, sin) of tree_pos[mg] * theta^(-2e/d_h)
-        const float x1 = Ct[m * CT_PITCH + w * 16 + j], x2 = Ct[m * CT_PITCH + w * 16 + 8 + j];
-        const float y1 = x1 * cs.x - x2 * cs.y, y2 = x2 * cs.x + x1 * cs.y;
-        if (seg == 0) {
-          T *q = (T *)a.q_out + (size_t)mg * d + head * d_h + e;
-          q[0] = Elem<T>::from_f32(y1);
-          q[half] = Elem<T>::from_f32(y2);
-        } else {
-          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-          if (L < 0 || L + a.T_nodes > a.max_kv) {
-            if (j == 0 && node == 0) atomicOr(a.dev_status, 2u);
-            continue;
-          }
-          T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-          kc[k_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(y1);
-          kc[k_tiled_index<T>(L + node, e + half, d_h)] = Elem<T>::from_f32(y2);
-        }
-      } else {
-        // values: consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
-        const int j = rem >> 6, m = rem & 63, mg = m_base + m;
-        if (mg >= a.M) continue;
-        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-        if (L < 0 || L + a.T_nodes > a.max_kv) continue;
-        #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
-          T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-          vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
-        }
+      if (seg < 2) continue;
+      // consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
+      const int j = rem >> 6, m = rem & 63, mg = m_base + m;
+      if (mg >= a.M) continue;
+      const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
+      if (L < 0 || L + a.T_nodes > a.max_kv) continue;
+      #pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
+        T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+        vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
       }
     }
   } else if (EPI == EPI_ARGMAX) {
@@ -292,6 +325,20 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
     }
   }
 
+  // Partial slabs need no regrouping: a math lane holds 4 adjacent outputs (weight rows wave*16 + g*4 .. +3) of
+  // activation row mb*16 + r16, which are 16 adjacent bytes of out[split][m][n].
+  if (EPI == EPI_STORE && (a.seg_rows & 3) == 0) {
+    if (wave < nb) {
+      const int N = a.seg_rows, n0 = tile * BN + wave * 16 + g * 4;
+      float *slab = a.out + (size_t)split * a.M * N + n0;
+      #pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        const int mg = m_base + mb * 16 + r16;
+        if (mg < a.M && n0 < N) *reinterpret_cast<f32x4 *>(slab + (size_t)mg * N) = acc[mb];
+      }
+    }
+    return;
+  }
   // accumulators -> Ct[m][r] (float32): a math lane holds rows r = wave*16 + g*4 .. +4 of column m.
   // The last barrier of the loop has passed, so nobody reads the stages any more; the one write still
   // outstanding (the loaders' zero chunk nch2) went to stage nch2 % 2 before that barrier.
