@@ -339,6 +339,26 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
     }
     return;
   }
+  // SwiGLU needs no regrouping either: lane groups 0, 1 hold the block's 8 gate rows, groups 2, 3 the same rows of
+  // W_up, 32 lanes further on; after one exchange a lane of group 0 or 1 owns 4 adjacent outputs of its token.
+  if (EPI == EPI_SWIGLU && (a.seg_rows & 3) == 0) {
+    if (wave < nb) {
+      const int f = a.seg_rows, j0 = tile * 8 * nb + wave * 8 + g * 4;
+      T *act = (T *)a.act;
+      #pragma unroll
+      for (int mb = 0; mb < 4; ++mb) {
+        float y[4];
+        #pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const float up = __shfl_down(acc[mb][c], 32, WAVE);
+          y[c] = silu_f(acc[mb][c]) * up;
+        }
+        const int mg = m_base + mb * 16 + r16;
+        if (g < 2 && mg < a.M && j0 < f) store4<T>(act + (size_t)mg * f + j0, y);
+      }
+    }
+    return;
+  }
   // accumulators -> Ct[m][r] (float32): a math lane holds rows r = wave*16 + g*4 .. +4 of column m.
   // The last barrier of the loop has passed, so nobody reads the stages any more; the one write still
   // outstanding (the loaders' zero chunk nch2) went to stage nch2 % 2 before that barrier.
