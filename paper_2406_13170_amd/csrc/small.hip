@@ -267,6 +267,70 @@ __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const in
     for (int i = lane; i < n_advance; i += WAVE) advance[i] += advance_each ? advance_each[i] : advance_by;
 }
 
+// One workgroup of 1024 threads per row for vocabularies up to 65536: every thread keeps NPT logits (element
+// j * 1024 + tid in slot j) and its own best; k rounds of (wave butterfly, 16 wave winners through LDS, every wave
+// folds them again) pick the winners, and only the thread that owned a winner rescans its slots.  Same order and
+// tie rule as the two-pass version, one launch instead of two.
+template <int NPT>
+__global__ __launch_bounds__(1024) void k_topk_row(const float *logits, int V, int k, int32_t *idx, float *val,
+                                                   int32_t *advance, int n_advance, int advance_by,
+                                                   const int32_t *advance_each) {
+  __shared__ float sm_v[16];
+  __shared__ int sm_i[16];
+  const float NEG_INF = -__builtin_huge_valf();
+  const int NONE = 0x7fffffff;
+  const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float *src = logits + (size_t)row * V;
+  float x[NPT];
+  unsigned long long alive = 0ull;
+  #pragma unroll
+  for (int j = 0; j < NPT; ++j) {
+    const int e = j * 1024 + tid;
+    x[j] = src[min(e, V - 1)];                            // unconditional loads from clamped addresses
+    if (e < V) alive |= 1ull << j;
+  }
+  float bv; int bi;
+  auto rescan = [&]() {
+    bv = NEG_INF; bi = NONE;
+    #pragma unroll
+    for (int j = 0; j < NPT; ++j)
+      if (((alive >> j) & 1ull) && better(x[j], j * 1024 + tid, bv, bi)) { bv = x[j]; bi = j * 1024 + tid; }
+  };
+  rescan();
+  for (int r = 0; r < k; ++r) {
+    float wv = bv; int wi = bi;
+    #pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(wv, off, WAVE);
+      const int oi = __shfl_xor(wi, off, WAVE);
+      if (better(ov, oi, wv, wi)) { wv = ov; wi = oi; }
+    }
+    if (lane == 0) { sm_v[wave] = wv; sm_i[wave] = wi; }
+    __syncthreads();
+    float gv = (lane < 16) ? sm_v[lane] : NEG_INF;
+    int gi = (lane < 16) ? sm_i[lane] : NONE;
+    #pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+      const float ov = __shfl_xor(gv, off, WAVE);
+      const int oi = __shfl_xor(gi, off, WAVE);
+      if (better(ov, oi, gv, gi)) { gv = ov; gi = oi; }
+    }
+    gv = __shfl(gv, 0, WAVE);
+    gi = __shfl(gi, 0, WAVE);
+    if (tid == 0) {
+      if (idx) idx[(size_t)row * k + r] = (gi == NONE) ? -1 : gi;
+      if (val) val[(size_t)row * k + r] = gv;
+    }
+    if (gi != NONE && gi == bi) {                          // this thread owned the winner: retire it and rescan
+      alive &= ~(1ull << (gi >> 10));
+      rescan();
+    }
+    __syncthreads();                                       // the wave winners are rewritten in the next round
+  }
+  if (row == 0 && advance)
+    for (int i = tid; i < n_advance; i += 1024) advance[i] += advance_each ? advance_each[i] : advance_by;
+}
+
 size_t topk_ws_floats(int rows, int V, int k) {
   const int chunks = (V + TK_CHUNK - 1) / TK_CHUNK;
   return 2 * (size_t)rows * chunks * k;
@@ -275,9 +339,16 @@ size_t topk_ws_floats(int rows, int V, int k) {
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
                             int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, float *ws) {
   if (rows < 1 || V < 1 || k < 1 || k > V || k > AMPH_MAX_TOPK) return hipErrorInvalidValue;
+  if (V <= 65536) {
+    #define TK_ROW(N) hipLaunchKernelGGL((k_topk_row<N>), dim3(rows), dim3(1024), 0, st, logits, V, k, idx, val, advance, \
+                                         n_advance, advance_by, advance_each)
+    if (V <= 8192) TK_ROW(8); else if (V <= 16384) TK_ROW(16); else if (V <= 32768) TK_ROW(32); else TK_ROW(64);
+    #undef TK_ROW
+    return hipGetLastError();
+  }
   const int chunks = (V + TK_CHUNK - 1) / TK_CHUNK;
   const int n_cand = chunks * k;
-  if (n_cand > TK_MAXC * WAVE) return hipErrorInvalidValue;          // V <= 65536 with k <= 16
+  if (n_cand > TK_MAXC * WAVE) return hipErrorInvalidValue;
   float *cand_v = ws;
   int *cand_i = reinterpret_cast<int *>(ws + (size_t)rows * n_cand);
   hipLaunchKernelGGL(k_topk_pass1, dim3((chunks + 3) / 4, rows), dim3(256), 0, st, logits, V, k, chunks, cand_v, cand_i);
