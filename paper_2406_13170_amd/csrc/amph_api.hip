@@ -110,8 +110,9 @@ WsLayout make_layout(const amph_config &c) {
   w.Hp = take(BK * d * 4); w.Qa = take(BK * d * 4); w.Ka = take(BK * d * 4); w.Va = take(BK * d * 4);
   w.ctxa = take(BK * d * 4); w.attn_o = take(BK * d * 4); w.logits = take(BK * V * 4);
   w.topk_ws = take(std::max(topk_ws_floats((int)BK, c.vocab, c.topk), topk_ws_floats((int)M, c.vocab, 1)) * 4);
-  w.xres = take(M * d * 4); w.xn = take(M * d * esz); w.qb = take(M * d * esz); w.attb = take(M * d * esz);
-  w.actb = take(M * f * esz);
+  const size_t Mp = (M + 31) / 32 * 32;         // activations may be kept in 32-row tiles for the wide GEMM
+  w.xres = take(M * d * 4); w.xn = take(Mp * d * esz); w.qb = take(M * d * esz); w.attb = take(Mp * d * esz);
+  w.actb = take(Mp * f * esz);
   // partial slabs of the split-K GEMMs (Wo, W_down: up to 8 slabs of [M, d]); amph_gemm may use the same area
   w.slabs_floats = std::max((size_t)8 * M * d, (size_t)8 * 1024 * 1024);
   w.slabs = take(w.slabs_floats * 4);
@@ -227,7 +228,7 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
 
 template <typename T>
 amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache, const void *v_cache,
-                        const int32_t *kv_len, void *out, void *workspace) {
+                        const int32_t *kv_len, void *out, void *workspace, int out_tiles = 0) {
   const amph_config &c = ctx->cfg;
   VerifyArgs a{};
   a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out; a.kv_len = kv_len; a.mask_bits = tree->d_mask;
@@ -236,6 +237,7 @@ amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, con
   a.partials_cap = ctx->ws.ver_part_floats;
   a.dev_status = ctx->dev_status;
   a.kernel = ctx->verify_kernel;
+  a.out_tiles = out_tiles;
   PROF_TRY(ctx, AMPH_K_VERIFY, launch_verify_attn<T>(ctx->stream, a));
   return AMPH_OK;
 }
@@ -275,30 +277,44 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
     const amph_layer_tiled lt = tiled ? tiled[li] : amph_layer_tiled{nullptr, nullptr, nullptr, nullptr};
     void *kc = (T *)k_caches + (size_t)li * cache_layer, *vc = (T *)v_caches + (size_t)li * cache_layer;
     const int s_wo = split_for(d, d, lt.wo != nullptr), s_down = split_for(d, f, lt.down != nullptr);
+    // Where the consumer of an activation tensor is the wide GEMM (enough rows, tiled weights), its producer writes
+    // it in that kernel's tiled layout straight away instead of leaving a copy to be made.
+    const int xt_tiles = (M + 31) / 32;
+    const bool w_qkv = gemm_is_wide(M, lt.qkv != nullptr), w_wo = gemm_is_wide(M, lt.wo != nullptr);
+    const bool w_gu = gemm_is_wide(M, lt.gate_up != nullptr), w_down = gemm_is_wide(M, lt.down != nullptr);
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, slabs, pending,
-                                                        slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status));
+                                                        slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status,
+                                                        w_qkv ? xt_tiles : 0));
     GemmArgs a = g;
     a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.wt = lt.qkv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
+    a.x_tiled = w_qkv;
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
     PROF_GEMM(ctx, AMPH_K_T_QKV, T, st, EPI_QKV_ROPE, a);
-    if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace)) return s;
+    if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace, w_wo ? xt_tiles : 0)) return s;
     a = g;
     a.w0 = lw.wo; a.wt = lt.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
+    a.x_tiled = w_wo;
     PROF_GEMM(ctx, AMPH_K_T_WO, T, st, EPI_STORE, a);
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, nullptr, nullptr, V, slabs, s_wo, slab, lw.rms2, M, d,
-                                                        c.rms_eps, xn, nullptr, ctx->dev_status));
+                                                        c.rms_eps, xn, nullptr, ctx->dev_status, w_gu ? xt_tiles : 0));
     a = g;
     a.w0 = lw.w_gate; a.w1 = lw.w_up; a.wt = lt.gate_up; a.n_seg = 2; a.seg_rows = f; a.Kd = d; a.x = xn; a.act = actb;
+    a.x_tiled = w_gu;
+    a.act_tiles = (w_gu && w_down) ? xt_tiles : 0;         // only the wide kernel's epilogue can write the tiled form
     PROF_GEMM(ctx, AMPH_K_T_GATEUP, T, st, EPI_SWIGLU, a);
     a = g;
     a.w0 = lw.w_down; a.wt = lt.down; a.n_seg = 1; a.seg_rows = d; a.Kd = f; a.x = actb; a.out = slabs; a.split_k = s_down;
+    a.x_tiled = w_gu && w_down;
     PROF_GEMM(ctx, AMPH_K_T_DOWN, T, st, EPI_STORE, a);
     pending = s_down;
   }
+  const bool w_lm = gemm_is_wide(M, lm_head_tiled != nullptr);
   PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, n_layers == 0 ? tree_tok : nullptr, V, slabs, pending,
-                                                      slab, final_norm, M, d, c.rms_eps, xn, hidden_out, ctx->dev_status));
+                                                      slab, final_norm, M, d, c.rms_eps, xn, hidden_out, ctx->dev_status,
+                                                      w_lm ? (M + 31) / 32 : 0));
   GemmArgs a = g;
   a.w0 = lm_head; a.wt = lm_head_tiled; a.n_seg = 1; a.seg_rows = V; a.Kd = d; a.x = xn;
+  a.x_tiled = w_lm;
   a.logits = logits_out;
   a.amax_val = (float *)(ws + ctx->ws.amax_val); a.amax_idx = (int32_t *)(ws + ctx->ws.amax_idx);
   PROF_GEMM(ctx, AMPH_K_T_LMHEAD, T, st, EPI_ARGMAX, a);

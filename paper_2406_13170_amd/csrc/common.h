@@ -129,6 +129,15 @@ template <typename T> __device__ __forceinline__ size_t v_tiled_index(int row, i
   return ((size_t)(row / KSTEP) * (d_h / 16) + c / 16) * (16 * PIECE) + (c % 16) * PIECE + row % KSTEP;
 }
 
+// Element index of (row m, element k) in the fragment-tiled activation layout the wide GEMM reads: 32 rows x 32 bytes
+// of k per KB, lane-linear (lane = half * 32 + m % 32 holds the 16 bytes at half * 16).  4 elements starting at a
+// multiple of 4 stay inside one 16-byte piece.
+template <typename T> __device__ __forceinline__ size_t xt_index(int m, int k, int m32_tiles) {
+  const int kb = k * (int)sizeof(T);
+  const size_t byte = ((size_t)(kb >> 5) * m32_tiles + (m >> 5)) * 1024 + (size_t)((((kb >> 4) & 1) * 32 + (m & 31)) << 4) + (kb & 15);
+  return byte / sizeof(T);
+}
+
 // ---- wave-level reductions ---------------------------------------------------------------------------
 __device__ __forceinline__ float wave_sum(float v) {
   #pragma unroll

@@ -119,7 +119,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
       #pragma unroll
       for (int j = 0; j < 8; ++j) y[j] = silu_f(crow[j]) * crow[8 + j];
       T *dst = act + (size_t)mg * f + j0;
-      if (j0 + 8 <= f && (f & 7) == 0) {
+      if (a.act_tiles) {                                   // tiled for the wide GEMM that follows (f is a multiple of 16)
+        store4<T>(act + xt_index<T>(mg, j0, a.act_tiles), y);
+        store4<T>(act + xt_index<T>(mg, j0 + 4, a.act_tiles), y + 4);
+      } else if (j0 + 8 <= f && (f & 7) == 0) {
         store4<T>(dst, y); store4<T>(dst + 4, y + 4);
       } else {
         for (int j = 0; j < 8 && j0 + j < f; ++j) dst[j] = Elem<T>::from_f32(y[j]);
@@ -664,7 +667,7 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   best.blocks = blocks;
   // measured at 7B shapes: 2 blocks of 64 rows 7.3 ms per step wide against 5.7 skinny, 4 blocks 8.8 against 8.3,
   // 8 blocks 13.5 against 14.5; 33B shapes, 6 blocks: 50.0 against 59.1
-  best.wide = tiled && mblocks >= GW_MIN_MBLOCKS;
+  best.wide = gemm_is_wide(M, tiled);
   if (best.wide) {
     // all activation rows in one workgroup (groups of at most GW_MAX_NW blocks of 64): a step costs the math waves
     // 4 * nb matrix-core instructions and the chip nb weight fragments per workgroup
@@ -701,6 +704,8 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   return best;
 }
 
+bool gemm_is_wide(int M, bool tiled) { return tiled && (M + GM_BM - 1) / GM_BM >= GW_MIN_MBLOCKS; }
+
 size_t gemm_xt_bytes(int M, int Kd, int elem_bytes) { return (size_t)((M + 31) / 32) * 32 * (size_t)Kd * elem_bytes; }
 
 template <typename T, int EPI, int NP>
@@ -729,15 +734,17 @@ static hipError_t launch_wide(hipStream_t st, const GemmArgs &a, const GemmPlan 
   if (!a.wt || !a.xt || pl.nw < 1 || pl.nw > GW_MAX_NW || pl.nb < 2 || pl.nb > 2 * GW_MAX_NP || pl.nb % 2) return hipErrorInvalidValue;
   const int m32_tiles = (a.M + 31) / 32, row_bytes = a.Kd * (int)sizeof(T);
   const size_t pieces = (size_t)(row_bytes / 32) * m32_tiles * 64;
-  hipLaunchKernelGGL((k_tile_rows<T>), dim3((unsigned)std::min<size_t>((pieces + 255) / 256, 4096)), dim3(256), 0, st,
-                     (const unsigned char *)a.x, a.M, row_bytes, m32_tiles, (unsigned char *)a.xt);
+  GemmArgs aw = a;
+  if (a.x_tiled) aw.xt = const_cast<void *>(a.x);         // the producer of x wrote it tiled
+  else hipLaunchKernelGGL((k_tile_rows<T>), dim3((unsigned)std::min<size_t>((pieces + 255) / 256, 4096)), dim3(256), 0, st,
+                          (const unsigned char *)a.x, a.M, row_bytes, m32_tiles, (unsigned char *)a.xt);
   const long long wgs = (long long)((pl.tiles * a.split_k + 7) / 8) * pl.mgroups * 8;
   if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)wgs), block(64 * (pl.nw + GW_NL));
   switch (pl.nb / 2) {
-    case 1: return launch_wide_np<T, EPI, 1>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
-    case 2: return launch_wide_np<T, EPI, 2>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
-    default: return launch_wide_np<T, EPI, 3>(st, a, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    case 1: return launch_wide_np<T, EPI, 1>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    case 2: return launch_wide_np<T, EPI, 2>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    default: return launch_wide_np<T, EPI, 3>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
   }
 }
 
@@ -750,6 +757,7 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in, hipEvent_t
   if (epi == EPI_QKV_ROPE && (a.d_h % 16 || a.seg_rows != a.n_heads * a.d_h || !a.rope_cs)) return hipErrorInvalidValue;
   const GemmPlan pl = gemm_plan(epi, a.seg_rows, a.Kd, (int)sizeof(T), a.M, a.split_k, a.wt != nullptr && a.xt != nullptr);
   a.nb = pl.nb;
+  if (!pl.wide && (a.x_tiled || a.act_tiles)) return hipErrorInvalidValue;   // only the wide kernel knows the tiled activations
   if (pl.wide) {
     switch (epi) {
       case EPI_STORE: return launch_wide<T, EPI_STORE>(st, a, pl, ev_start, ev_stop);

@@ -51,11 +51,12 @@ hipError_t launch_commit(hipStream_t st, void *k_caches, void *v_caches, int n_l
                          int32_t *n_new);
 hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, int d, const int32_t *n_valid, float *out);
 // x[m] (+)= sum_s slabs[s][m] (or x[m] = embed[tok[m]] when tok != NULL); xn[m] = RMSNorm(x[m]) * g as T;
-// hidden_out (float32, optional) receives the same normalised rows.
+// hidden_out (float32, optional) receives the same normalised rows.  xn_tiles != 0: xn is written in the tiled
+// activation layout of the wide GEMM (xn_tiles = number of 32-row tiles).
 template <typename T>
 hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
                             const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
-                            void *xn, float *hidden_out, uint32_t *dev_status);
+                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles = 0);
 
 // ---- gemm_skinny.hip (target path, rows on the matrix cores) ----
 enum GemmEpi { EPI_STORE = 0, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
@@ -66,6 +67,8 @@ struct GemmArgs {
   int Kd;
   const void *x;              // [M, Kd] T
   void *xt;                   // scratch of gemm_xt_bytes(M, Kd): fragment-tiled copy of x for the wide kernel, or NULL
+  bool x_tiled;               // x itself is already in that tiled layout (its producer wrote it so): no copy is made
+  int act_tiles;              // EPI_SWIGLU: 0 = act is row-major [M, f]; else its 32-row tile count, act is written tiled
   int M;
   int split_k;                // 1, 2, 4, 8 (fused epilogues: 1)
   int nb;                     // row blocks per workgroup: filled in by launch_gemm from gemm_plan
@@ -91,6 +94,7 @@ struct GemmArgs {
 struct GemmPlan { int nb, split, tiles, blocks; bool wide; int mgroups, nw; };   // wide: all rows in one workgroup (nw blocks of 64)
 GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req, bool tiled);
 size_t gemm_xt_bytes(int M, int Kd, int elem_bytes);
+bool gemm_is_wide(int M, bool tiled);       // whether gemm_plan sends this many rows to the wide kernel
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end time stamps
 template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a, hipEvent_t ev_start = nullptr,
                                              hipEvent_t ev_stop = nullptr);
@@ -108,6 +112,7 @@ struct VerifyArgs {
   const int32_t *kv_len; const uint64_t *mask_bits;
   int B, T, n_heads, d_h, max_kv;
   float *partials; size_t partials_cap; uint32_t *dev_status;
+  int out_tiles;    // 0: out is row-major [B*T, n_heads*d_h]; else the 32-row tile count of the tiled activation layout
   int kernel;       // -1: chosen by shape; 0: operands through registers; 1: operands through an LDS ring
 };
 size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes);

@@ -555,7 +555,7 @@ hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, i
 template <typename T, int S, bool EMB, int NP>
 __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, const int32_t *tok, int vocab,
                                                     const float *slabs, size_t slab_stride, const T *g, int d,
-                                                    float eps, T *xn, float *hidden_out, uint32_t *dev_status) {
+                                                    float eps, T *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles) {
   __shared__ float red[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   float *xr = x + (size_t)row * d;
@@ -603,7 +603,7 @@ __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, co
       float o[4];
       #pragma unroll
       for (int j = 0; j < 4; ++j) o[j] = v[i][j] * rs * gk[i][j];
-      store4<T>(xn + (size_t)row * d + k, o);
+      store4<T>(xn_tiles ? xn + xt_index<T>(row, k, xn_tiles) : xn + (size_t)row * d + k, o);
       if (hidden_out) store4<float>(hidden_out + (size_t)row * d + k, o);
     }
   }
@@ -612,13 +612,13 @@ __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, co
 template <typename T>
 hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
                             const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
-                            void *xn, float *hidden_out, uint32_t *dev_status) {
+                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles) {
   if (d % 4 || d > 8192) return hipErrorInvalidValue;
   if (tok && S != 0) return hipErrorInvalidValue;                  // the embedding gather starts a fresh residual stream
   const int np = d > 4096 ? 2 : 1;
   #define NF_LAUNCH(S_, EMB_, NP_)                                                                                  \
     hipLaunchKernelGGL((k_norm_fold<T, S_, EMB_, NP_>), dim3(rows), dim3(1024), 0, st, x, (const T *)embed, tok,    \
-                       vocab, slabs, slab_stride, (const T *)g, d, eps, (T *)xn, hidden_out, dev_status)
+                       vocab, slabs, slab_stride, (const T *)g, d, eps, (T *)xn, hidden_out, dev_status, xn_tiles)
   #define NF_CASE(S_)                                                                                               \
     case S_: if (np == 1) NF_LAUNCH(S_, false, 1); else NF_LAUNCH(S_, false, 2); break
   if (tok) {
@@ -634,8 +634,8 @@ hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const i
   return hipGetLastError();
 }
 template hipError_t launch_norm_fold<float>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
-                                            size_t, const void *, int, int, float, void *, float *, uint32_t *);
+                                            size_t, const void *, int, int, float, void *, float *, uint32_t *, int);
 template hipError_t launch_norm_fold<bf16_t>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
-                                             size_t, const void *, int, int, float, void *, float *, uint32_t *);
+                                             size_t, const void *, int, int, float, void *, float *, uint32_t *, int);
 
 }  // namespace amph

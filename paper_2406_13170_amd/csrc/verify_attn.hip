@@ -259,7 +259,8 @@ __global__ __launch_bounds__(256) void k_verify_attn_regs(const VerifyArgs a, in
     if (S == 1) {
       if (qi < Tn) {
         const float inv = (l > 0.f) ? 1.0f / l : 0.f;
-        T *dst = outp + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
+        T *dst = a.out_tiles ? outp + xt_index<T>(b * Tn + qi, h * DH + d4, a.out_tiles)
+                             : outp + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
         #pragma unroll
         for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(o[i] * inv);
       }
@@ -517,11 +518,12 @@ __global__ __launch_bounds__((VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(con
     if (S == 1) {
       if (q < Tn) {
         const float inv = (l > 0.f) ? 1.0f / l : 0.f;
-        T *dst = (T *)a.out + (((size_t)b * Tn + q) * n_h + h) * DH + g * 4;
         #pragma unroll
         for (int db = 0; db < DB; ++db) {
           const float r[4] = {O[qb][db][0] * inv, O[qb][db][1] * inv, O[qb][db][2] * inv, O[qb][db][3] * inv};
-          store4<T>(dst + db * 16, r);
+          T *dst = a.out_tiles ? (T *)a.out + xt_index<T>(b * Tn + q, h * DH + db * 16 + g * 4, a.out_tiles)
+                               : (T *)a.out + (((size_t)b * Tn + q) * n_h + h) * DH + db * 16 + g * 4;
+          store4<T>(dst, r);
         }
       }
     } else {
@@ -558,7 +560,8 @@ __global__ __launch_bounds__(256) void k_verify_fold(const VerifyArgs a, int n_q
   }
   const float inv = (l > 0.f) ? 1.0f / l : 0.f;
   float r[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
-  T *dst = (T *)a.out + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
+  T *dst = a.out_tiles ? (T *)a.out + xt_index<T>(b * Tn + qi, h * DH + d4, a.out_tiles)
+                       : (T *)a.out + (((size_t)b * Tn + qi) * n_h + h) * DH + d4;
   #pragma unroll
   for (int i = 0; i < 4; ++i) dst[i] = Elem<T>::from_f32(r[i]);
 }
@@ -663,7 +666,7 @@ static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
 
 template <typename T>
 hipError_t launch_verify_attn(hipStream_t st, const VerifyArgs &a) {
-  if (a.T < 1 || a.T > AMPH_MAX_TREE || a.max_kv % 32 || a.kernel < -1 || a.kernel > 1) return hipErrorInvalidValue;
+  if (a.T < 1 || a.T > AMPH_MAX_TREE || a.max_kv % 32 || a.kernel < -1 || a.kernel > 1 || a.out_tiles < 0) return hipErrorInvalidValue;
   if (a.d_h == 64) return launch_va_dh<T, 64>(st, a);
   if (a.d_h == 128) return launch_va_dh<T, 128>(st, a);
   return hipErrorInvalidValue;
