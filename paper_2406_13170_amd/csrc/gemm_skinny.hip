@@ -402,7 +402,7 @@ constexpr int GW_NL = 2;           // loader waves
 constexpr int GW_MAX_NP = 3;       // pairs of weight row blocks per workgroup
 constexpr int GW_MAX_NW = 6;       // math waves = blocks of 64 activation rows per workgroup
 constexpr int GW_XD = 4;           // steps of activations requested ahead
-constexpr int GW_MIN_MBLOCKS = 5;  // blocks of 64 activation rows from which the wide kernel is used
+constexpr int GW_MIN_MBLOCKS = 3;  // blocks of 64 activation rows from which the wide kernel is used
 constexpr int GW_AUX_NT = 2;       // cache-policy bits of the global-to-LDS load: non-temporal (the weights are read once)
 static_assert(GW_STEPS % GW_XD == 0, "the activation ring is indexed statically inside a stage");
 
@@ -665,8 +665,8 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   const double slab_units = fused ? 0.0 : (double)M * seg_rows * 1.0e-4 + 2.0;   // per extra split
   double best_cost = 1e300;
   best.blocks = blocks;
-  // measured at 7B shapes: 2 blocks of 64 rows 7.3 ms per step wide against 5.7 skinny, 4 blocks 8.8 against 8.3,
-  // 8 blocks 13.5 against 14.5; 33B shapes, 6 blocks: 50.0 against 59.1
+  // measured at 7B shapes, ms per step skinny / wide: 2 blocks of 64 rows 5.60 / 6.49, 3 blocks 7.37 / 7.02, 4 blocks
+  // 8.23 / 7.86, 6 blocks 12.44 / 11.07, 8 blocks 14.46 / 12.40; 33B shapes, 6 blocks: 59.1 / 47.4
   best.wide = gemm_is_wide(M, tiled);
   if (best.wide) {
     // all activation rows in one workgroup (groups of at most GW_MAX_NW blocks of 64): a step costs the math waves

@@ -308,13 +308,14 @@ def test_target_forward_batch_two():
 
 @pytest.mark.parametrize("cfg,n_layers,T,caps,L,Bsz", [
     (si.MINI, 2, 64, (10,) * 4, 100, 2),           # M = 128: two blocks of 64 rows, still the skinny kernel
+    (si.MINI, 2, 64, (10,) * 4, 90, 3),            # M = 192: three blocks, the smallest case of the wide kernel
     (si.MINI, 2, 64, (10,) * 4, 77, 5),            # M = 320: five blocks in one workgroup of the wide kernel
     (si.MINI, 1, 35, (10,) * 4, 61, 10),           # M = 350: ragged last block and last 32-row tile
     (si.MINI, 1, 64, (10,) * 4, 40, 7),            # M = 448: two groups of rows (4 + 3 blocks)
     (si.TINY, 2, 64, (10,) * 4, 5, 6),             # float32, M = 384: six blocks
 ])
 def test_target_forward_batches_on_tiled_weights(cfg, n_layers, T, caps, L, Bsz):
-    """Five blocks of 64 activation rows or more with tiled weights take the wide GEMM (all rows of a weight tile in
+    """Three blocks of 64 activation rows or more with tiled weights take the wide GEMM (all rows of a weight tile in
     one workgroup, 32 x 32 matrix-core tiles); the same inputs with row-major weights take the skinny one.  Both
     against the oracle."""
     say(f"target_forward {cfg.name} layers={n_layers} T={T} L={L} batch={Bsz} (M = {T * Bsz}), tiled weights")
