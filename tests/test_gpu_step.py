@@ -204,7 +204,7 @@ def test_draft_is_deterministic_and_flags_overflow():
 
 
 # ---------------------------------------------------------------------------- amph_target_forward (A7-A9)
-def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False, oracle=True):
+def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False, oracle=True, tiled_keys=None):
     cfg = si.with_(cfg, batch=Bsz, K=len(caps), topk=min(16, max(caps)))
     n_h, d_h, d, V = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab
     max_kv = (L + T + 31) // 32 * 32
@@ -236,7 +236,14 @@ def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False,
         packed = [D.pack_layer(ctx, l) for l in layers_d]
         tiled_structs, keep = [p[0] for p in packed], [p[1] for p in packed]
         lm_t = D.pack_lm_head(ctx, lm_d)
-        structs = [B.amph_layer_w(rms1=l["rms1"].data_ptr(), rms2=l["rms2"].data_ptr()) for l in layers_d]
+        if tiled_keys is None:
+            structs = [B.amph_layer_w(rms1=l["rms1"].data_ptr(), rms2=l["rms2"].data_ptr()) for l in layers_d]
+        else:
+            # only the matrices named in tiled_keys get their tiled copy; the others stay row-major
+            for ts in tiled_structs:
+                for name in ("qkv", "wo", "gate_up", "down"):
+                    if name not in tiled_keys:
+                        setattr(ts, name, None)
     ctx.amph_target_forward(tree, structs, embed_d, fn_d, None if tiled else lm_d, i32_to_dev(tok), i32_to_dev(pos),
                             k_caches, v_caches, i32_to_dev(np.full(Bsz, L)), hidden, logits, tgt,
                             tiled_structs=tiled_structs, lm_head_tiled=lm_t)
@@ -323,6 +330,15 @@ def test_target_forward_batches_on_tiled_weights(cfg, n_layers, T, caps, L, Bsz)
     check_target(cfgx, refs, got)
     say("  row-major weights")
     cfgx, refs, got, _ = run_target(cfg, n_layers, T, caps, L, Bsz=Bsz, tiled=False)
+    check_target(cfgx, refs, got)
+
+
+@pytest.mark.parametrize("tiled_keys", [("qkv",), ("wo", "down"), ("gate_up",), ("qkv", "gate_up", "down")])
+def test_target_forward_partially_tiled_weights(tiled_keys):
+    """Some matrices tiled, the others row-major, with enough rows (M = 256) that the tiled ones take the wide GEMM: its
+    input then comes either from a producer that wrote the tiled activation layout or from the fallback copy."""
+    say(f"target_forward mini batch=4, tiled copies only of {tiled_keys}")
+    cfgx, refs, got, _ = run_target(si.MINI, 2, 64, (10,) * 4, 50, Bsz=4, tiled=True, tiled_keys=tiled_keys)
     check_target(cfgx, refs, got)
 
 
