@@ -19,11 +19,11 @@
 //
 // k_verify_attn_ring (long key ranges: one workgroup streams all keys of a (batch element, head)).  Two loader
 // waves stream the fragments from global memory straight into a ring of LDS stages (one key step per stage)
-// without passing through registers; each math wave owns 16 or 32 queries for the whole range, reads every
+// without passing through registers; each math wave owns 16 queries (up to eight waves) for the whole range, reads every
 // fragment of a stage from LDS (lane-linear, free of bank conflicts) and keeps its running (max, sum, O) in
 // registers: the keys are read once per workgroup instead of once per 32 queries, and math waves never
 // exchange anything.  One barrier per stage hands a landed stage to the math waves and a consumed one back to
-// the loaders.  Measured at 52 heads, T = 96, batch 4, L = 4096: 120 us against 167 us; at 32 heads, T = 64,
+// the loaders.  Measured at 52 heads, T = 96, batch 4, L = 4096: 107 us against 167 us; at 32 heads, T = 64,
 // batch 1, L = 1024: 17.0 us against 15.4 us, hence the other kernel there.
 //
 // Workgroups that split the keys of one head merge through global memory: a second small kernel
@@ -292,7 +292,7 @@ struct VA {
   static_assert(FK % NL == 0 && FR % NL == 0, "a loader wave's j-th fragment must be K or V for both waves alike");
   static_assert(PERL * (R - 2) <= 63, "outstanding loads of a loader wave must fit the hardware counter");
 };
-constexpr int VA_MAX_MATH = 4;                     // math waves per workgroup
+constexpr int VA_MAX_MATH = 8;                     // math waves per workgroup: 16 queries each covers the largest tree
 
 // Waits until at most N vector-memory operations of this wave are outstanding (they complete in order).
 template <int N> __device__ __forceinline__ void wait_vm() {
