@@ -18,12 +18,13 @@
 // workgroup take different steps and merge their running (max, sum, O) through LDS.
 //
 // k_verify_attn_ring (long key ranges: one workgroup streams all keys of a (batch element, head)).  Two loader
-// waves stream the fragments from global memory straight into a ring of LDS stages (one key step per stage)
-// without passing through registers; each math wave owns 16 queries (up to eight waves) for the whole range, reads every
-// fragment of a stage from LDS (lane-linear, free of bank conflicts) and keeps its running (max, sum, O) in
-// registers: the keys are read once per workgroup instead of once per 32 queries, and math waves never
-// exchange anything.  One barrier per stage hands a landed stage to the math waves and a consumed one back to
-// the loaders.  Measured at 52 heads, T = 96, batch 4, L = 4096: 107 us against 167 us; at 32 heads, T = 64,
+// waves stream the fragments from global memory straight into a ring of LDS stages without passing through
+// registers; each math wave owns 16 queries (up to eight waves) for the whole range, reads the fragments of its
+// key steps from LDS (lane-linear, free of bank conflicts) and keeps its running (max, sum, O) in registers: the
+// keys are read once per workgroup instead of once per 32 queries.  One barrier per stage hands a landed stage to
+// the math waves and a consumed one back to the loaders.  On long walks two groups of math waves share every
+// query block (a stage then holds one key step for each group) and merge their states through LDS once at the
+// end.  Measured at 52 heads, T = 96, batch 4, L = 4096: 89 us against 167 us; at 32 heads, T = 64,
 // batch 1, L = 1024: 17.0 us against 15.4 us, hence the other kernel there.
 //
 // Workgroups that split the keys of one head merge through global memory: a second small kernel
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(256) void k_verify_attn_regs(const VerifyArgs a, in
 // =====================================================================================================
 // operands through an LDS ring
 // =====================================================================================================
-template <typename T, int DH>
+template <typename T, int DH, int KG = 1>
 struct VA {
   static constexpr int PER = Elem<T>::PER;
   static constexpr int KSTEP = 4 * PER;            // keys per step
@@ -284,7 +285,7 @@ struct VA {
   static constexpr int FK = NT * DSTEPS;           // K fragments of a step
   static constexpr int FR = FK + DB;               // fragments (KB) of a step: its K, then its V
   static constexpr int STEPB = FR * 1024;          // bytes of a step
-  static constexpr int NS = 1;                     // key steps per ring stage (2 measured slower)
+  static constexpr int NS = KG;                    // key steps per ring stage: one per key group of math waves
   static constexpr int STAGE = NS * STEPB;
   static constexpr int NL = 2;                     // loader waves
   static constexpr int PERL = NS * FR / NL;        // loads per loader wave and stage
@@ -308,16 +309,20 @@ template <int PERL> __device__ __forceinline__ void wait_stages(int k) {
 }
 template <int N> struct IntTag { static constexpr int value = N; };
 
-// grid = (key splits, heads, batch); block = (math waves + 2 loader waves) * 64; dynamic LDS = R stages
-template <typename T, int DH, int NQB>
-__global__ __launch_bounds__((VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(const VerifyArgs a) {
-  using C = VA<T, DH>;
+// grid = (key splits, heads, batch); block = (math waves + 2 loader waves) * 64; dynamic LDS = R stages.
+// KG = 2: two groups of math waves share every query block, one taking the even key steps and one the odd ones
+// (a stage holds one step for each), and merge their running states through LDS at the end; this doubles the
+// waves that hide each other's exponentials and LDS reads when one workgroup walks a long cache on its own.
+template <typename T, int DH, int NQB, int KG>
+__global__ __launch_bounds__(KG == 2 ? 1024 : (VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(const VerifyArgs a) {
+  using C = VA<T, DH, KG>;
   constexpr int PER = C::PER, KSTEP = C::KSTEP, NT = C::NT, DSTEPS = C::DSTEPS, DB = C::DB, FK = C::FK, FR = C::FR;
   constexpr int STEPB = C::STEPB, NS = C::NS, STAGE = C::STAGE, NL = C::NL, PERL = C::PERL, R = C::R;
   extern __shared__ __align__(16) unsigned char sm_ring[];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, g = lane >> 4, r16 = lane & 15;
-  const int nm = (int)(blockDim.x >> 6) - NL;        // math waves
+  const int nm = (int)(blockDim.x >> 6) - NL;        // math waves: KG key groups of nmq waves
+  const int nmq = nm / KG;
   const int S = gridDim.x, split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int Tn = a.T, n_h = a.n_heads, max_kv = a.max_kv;
   const int L = a.kv_len[b];
@@ -363,13 +368,18 @@ __global__ __launch_bounds__((VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(con
       __builtin_amdgcn_s_barrier();                  // math waves may read stage p; they are done with stage p - 1
       if (p + R - 1 < n_stages) issue(p + R - 1);    // into the slot of stage p - 1
     }
+    if (KG == 2) {                                   // the two barriers of the key groups' merge
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
+    }
     return;
   }
 
   // ---------------- math wave: queries [q0, q0 + 16 * NQB) against all stages ----------------
   const float scale = 1.4426950408889634f * rsqrtf((float)DH);
   const float NEG_INF = -__builtin_huge_valf();
-  const int q0 = wave * NQB * 16;
+  const int kg = wave / nmq;                         // this wave's key group: step kg of every stage
+  const int q0 = (wave - kg * nmq) * NQB * 16;
 
   // queries as B fragments: lane = query r16 of block qb, 16 bytes of dims per 64-byte piece
   uint4 Qf[NQB][DSTEPS];
@@ -500,14 +510,42 @@ __global__ __launch_bounds__((VA_MAX_MATH + 2) * 64) void k_verify_attn_ring(con
   for (int p = 0; p < n_stages; ++p) {
     __syncthreads();                                   // stage p is in LDS (pairs with the loaders' barrier)
     const unsigned char *sb = sm_ring + (p % R) * STAGE + lane * 16;
-    const int key0 = (st0 + p * NS) * KSTEP;
-    if (p * NS + NS <= n) process(IntTag<NS>{}, sb, key0);
-    else process(IntTag<1>{}, sb, key0);               // ragged last stage (NS = 2: one live step)
+    if (p * KG + kg < n) process(IntTag<1>{}, sb + kg * STEPB, (st0 + p * KG + kg) * KSTEP);   // a ragged last stage has one live step
+  }
+
+  if (KG == 2) {
+    static_assert(KG == 1 || 7 * NQB * (DB * 256 + 128) * 4 <= R * STAGE, "merge area of seven query waves must fit the ring");
+    // ---- the second key group hands its state over through LDS (the ring is free once everyone has passed the
+    // first barrier), the first one merges it into its own and writes the result
+    float *mo = reinterpret_cast<float *>(sm_ring) + (size_t)(wave - kg * nmq) * NQB * (DB * 256 + 128);
+    __syncthreads();
+    if (kg == 1) {
+      #pragma unroll
+      for (int qb = 0; qb < NQB; ++qb) {
+        #pragma unroll
+        for (int db = 0; db < DB; ++db) *reinterpret_cast<f32x4 *>(mo + (qb * DB + db) * 256 + lane * 4) = O[qb][db];
+        mo[NQB * DB * 256 + qb * 128 + lane] = m_run[qb];
+        mo[NQB * DB * 256 + qb * 128 + 64 + lane] = l_run[qb];
+      }
+    }
+    __syncthreads();
+    if (kg == 1) return;
+    #pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const float m1 = mo[NQB * DB * 256 + qb * 128 + lane], l1 = mo[NQB * DB * 256 + qb * 128 + 64 + lane];
+      const float mn = fmaxf(m_run[qb], m1);
+      const float c0 = fast_exp2(m_run[qb] - mn), c1 = fast_exp2(m1 - mn);
+      #pragma unroll
+      for (int db = 0; db < DB; ++db)
+        O[qb][db] = O[qb][db] * c0 + *reinterpret_cast<const f32x4 *>(mo + (qb * DB + db) * 256 + lane * 4) * c1;
+      l_run[qb] = l_run[qb] * c0 + l1 * c1;
+      m_run[qb] = mn;
+    }
   }
 
   // ---- lane groups hold partial sums of l for the same query: fold them; then the lane writes dims
   // db * 16 + g * 4 .. + 3 of query r16 of each of its blocks
-  const int NQ = nm * NQB * 16;                        // query rows of a partial
+  const int NQ = nmq * NQB * 16;                       // query rows of a partial
   float *part = a.partials + ((((size_t)b * n_h + h) * S + split) * (size_t)(NQ * DH + 2 * NQ));
   #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
@@ -574,7 +612,8 @@ struct VaPlan {
   int S;            // key splits
   int nqb;          // 16-query blocks per wave
   int groups;       // regs: query groups (workgroups per head and split); ring: 1
-  int nm;           // ring: math waves
+  int nm;           // ring: math waves per key group
+  int kg;           // ring: key groups of math waves (1 or 2)
   int nq;           // query rows of one partial
 };
 constexpr int VA_MAX_QB = 2;       // regs: more blocks per wave would leave no room for a second set of K/V fragments
@@ -599,7 +638,7 @@ static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int
   const bool ring = (force < 0) ? ((B * n_qg * n_heads > 256) || (s == 1 && max_steps >= 64)) : (force == 1);
   p.ring = ring;
   if (ring) {
-    p.nqb = (T > 16 * VA_MAX_MATH) ? 2 : 1;
+    p.nqb = 1;                                         // 16 queries per math wave cover the largest tree
     p.nm = (T + 16 * p.nqb - 1) / (16 * p.nqb);
     p.groups = 1;
     int sr = 256 / (B * n_heads);                      // never more workgroups than compute units: a second round costs more
@@ -607,6 +646,11 @@ static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int
     if (sr > 32) sr = 32;
     p.S = sr < 1 ? 1 : sr;
     p.nq = p.nm * p.nqb * 16;
+    // two key groups pay when a workgroup walks many steps (measured, ring kernel alone, one / two groups:
+    // 52 heads, T = 96, L = 4096: batch 4 109.3 / 89.4 us, batch 1 37.3 / 33.4; 40 heads, T = 64, L = 2048, batch 4:
+    // 47.5 / 35.4; 32 heads, T = 64, L = 4096: batch 8 102.2 / 96.7, batch 1 (16 steps per workgroup) 25.7 / 26.5)
+    const bool fits = p.nqb == 1 && (2 * p.nm + 2) * 64 <= 1024;
+    p.kg = (fits && (p.S == 1 || max_steps / p.S >= 32)) ? 2 : 1;
   } else {
     p.groups = n_qg;
     p.nqb = (blocks + n_qg - 1) / n_qg;
@@ -628,17 +672,17 @@ size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem
   return a > b ? a : b;
 }
 
-template <typename T, int DH, int NQB>
+template <typename T, int DH, int NQB, int KG>
 static hipError_t launch_va_ring(hipStream_t st, const VerifyArgs &a, const VaPlan &p) {
-  using C = VA<T, DH>;
+  using C = VA<T, DH, KG>;
   constexpr size_t smem = (size_t)C::R * C::STAGE;
   static bool attr_set = false;                       // once per instantiation and process
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_verify_attn_ring<T, DH, NQB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    hipError_t e = hipFuncSetAttribute((const void *)k_verify_attn_ring<T, DH, NQB, KG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_verify_attn_ring<T, DH, NQB>), dim3(p.S, a.n_heads, a.B), dim3((p.nm + C::NL) * 64), smem, st, a);
+  hipLaunchKernelGGL((k_verify_attn_ring<T, DH, NQB, KG>), dim3(p.S, a.n_heads, a.B), dim3((p.nm * KG + C::NL) * 64), smem, st, a);
   return hipGetLastError();
 }
 
@@ -649,7 +693,8 @@ static hipError_t launch_va_dh(hipStream_t st, const VerifyArgs &a) {
   if (va_plan_floats(p, a.B, a.n_heads, DH) > a.partials_cap) return hipErrorInvalidValue;
   if (p.ring) {
     if (p.nm < 1 || p.nm > VA_MAX_MATH) return hipErrorInvalidValue;
-    hipError_t e = (p.nqb == 1) ? launch_va_ring<T, DH, 1>(st, a, p) : launch_va_ring<T, DH, 2>(st, a, p);
+    if (p.nqb != 1 || (p.kg == 2 && (2 * p.nm + 2) * 64 > 1024)) return hipErrorInvalidValue;
+    hipError_t e = (p.kg == 2) ? launch_va_ring<T, DH, 1, 2>(st, a, p) : launch_va_ring<T, DH, 1, 1>(st, a, p);
     if (e != hipSuccess) return e;
   } else {
     const dim3 grid(p.S, a.n_heads, a.B * p.groups), block(256);

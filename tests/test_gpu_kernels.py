@@ -162,6 +162,27 @@ def test_verify_attn_long_cache_whole_head_per_workgroup():
     say(f"  worst row error {worst:.2e}")
 
 
+@pytest.mark.parametrize("cfg,T,caps,heads", [
+    (si.TINY, 22, (10,) * 4, [0, 3]),           # float32, 64-wide heads, two query waves per key group
+    (si.TINY, 1, (4, 4, 4, 4), [1]),            # one query
+    (si.MINI, 112, (10,) * 7, [2]),             # bf16, 128-wide heads, seven query waves per key group: 1024 threads
+    (si.MINI, 96, (10,) * 5, [0]),              # the 33B tree size
+])
+def test_verify_attn_ring_two_key_groups(cfg, T, caps, heads):
+    """Batch x heads above the number of compute units: the LDS ring runs without key splits and with two groups of
+    math waves that take alternate key steps and merge through LDS.  The committed lengths give every count of key
+    steps from 1 upwards (odd counts leave the second group without a step in the last stage; one step leaves it
+    with none at all), full and ragged last steps, and an empty cache."""
+    B_ = 33
+    kstep = 16 if cfg.dtype == si.F32 else 32
+    lens = [0, 1, kstep - 1, kstep, kstep + 1, 2 * kstep, 3 * kstep - T % kstep, 5 * kstep + 3, 8 * kstep, 9 * kstep + 7, 301]
+    lens = [max(0, x) for x in lens]
+    lens = (lens * 3)[:B_]
+    say(f"verify_attn ring, two key groups: {cfg.name} T={T} batch={B_}")
+    worst = verify_case(cfg, T, caps, max(lens), B_=B_, heads=heads, lens=lens, kernel=1)
+    say(f"  worst row error {worst:.2e}")
+
+
 def test_verify_kernel_selector_rejects_unknown_values():
     ctx = make_ctx(si.TINY, T=16)
     for bad in (-2, 2, 7):
