@@ -15,6 +15,8 @@ blocking, fusion, online softmax or reordering:
   * draft tree + tree mask           -- Sec. 2 "Tree Attention", Appendix "Draft Tree"
   * tree-attention verification      -- Sec. 2 "Tree Attention", Sec. 3.2 last paragraph
   * greedy acceptance                -- Sec. 2 "Speculative Decoding", Table 1 (Temperature = 0)
+  * acceptance under random sampling -- Table 2 (Temperature = 0.7); PARITY UNPINNED by the paper, which
+                                        names no rule: see accept_typical for the reading taken
 
 Where the paper is silent the readings are: Llama-style decoder layers (pre-RMSNorm, half-split RoPE, SwiGLU, no
 biases) for both the target and the adaptation layers; h before e in the
@@ -390,6 +392,60 @@ def accept_greedy(tree: Tree, tree_tok: np.ndarray, tgt: np.ndarray):
     chain.reverse()
     path[:len(chain)] = chain
     return int(tree.depth[best]), path, int(tgt[best]), int(best)
+
+
+def accept_typical(tree: Tree, tree_tok: np.ndarray, logits: np.ndarray, temperature: float, eps: float,
+                   delta: float, u: float):
+    """Acceptance under random sampling (Table 2, Temperature = 0.7).
+
+    PARITY UNPINNED BY THE PAPER: it reports results at this temperature but states no acceptance rule.  The
+    reading taken is the typical-acceptance criterion of the multi-head decoding framework whose tree and
+    settings the paper adopts (its reference cai2024medusa): with p_j = softmax(logits_j / temperature) the
+    target's distribution after node j and H(p_j) its entropy in nats, a child i of j is accepted iff j is and
+
+        p_j(tree_tok[i]) > min(eps, delta * exp(-H(p_j))).
+
+    The result is the deepest accepted node (the lowest id among equals, as in the greedy rule).  The token
+    that follows it is drawn from p_best by inverting its cumulative distribution, taken in vocabulary order,
+    at the caller's uniform number u in [0, 1): the first v with sum_{w <= v} p_best(w) > u (the last token of
+    non-zero probability if rounding leaves none).
+
+    Returns (accept_len, path [K+1] -1 padded, next_tok, best_node, margin) where margin[i] = p - threshold of
+    node i (margin[0] = +inf): a test that compares a float32 implementation can see which decisions are
+    near ties."""
+    T = tree.T
+    lg = _f(logits) / float(temperature)
+    p = np.stack([softmax(lg[j]) for j in range(T)])
+    H = np.array([-np.sum(p[j][p[j] > 0] * np.log(p[j][p[j] > 0])) for j in range(T)])
+    thr = np.minimum(float(eps), float(delta) * np.exp(-H))
+    margin = np.full(T, np.inf)
+    ok = np.zeros(T, dtype=bool)
+    ok[0] = True
+    for i in range(1, T):                     # parents precede children in node order
+        j = tree.parent[i]
+        margin[i] = p[j][int(tree_tok[i])] - thr[j]
+        ok[i] = ok[j] and margin[i] > 0.0
+    best = 0
+    for i in range(1, T):
+        if ok[i] and tree.depth[i] > tree.depth[best]:
+            best = i
+    path = np.full(tree.K + 1, -1, dtype=np.int32)
+    chain = []
+    j = best
+    while j >= 0:
+        chain.append(j)
+        j = tree.parent[j]
+    chain.reverse()
+    path[:len(chain)] = chain
+    acc, nxt = 0.0, -1
+    for v in range(p.shape[1]):
+        acc += p[best][v]
+        if acc > u:
+            nxt = v
+            break
+    if nxt < 0:
+        nxt = int(np.nonzero(p[best] > 0)[0][-1])
+    return int(tree.depth[best]), path, int(nxt), int(best), margin
 
 
 # ----------------------------------------------------------------------------
