@@ -137,6 +137,9 @@ def main():
     ap.add_argument("--lm-rank", type=int, default=0, help="rank of the low-rank LM head of the draft (0 = full head)")
     ap.add_argument("--one-stage", action="store_true", help="one adaptation layer for all heads")
     ap.add_argument("--no-pe", action="store_true", help="no position encoding")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="0: greedy acceptance (the headline); above 0: acceptance under random sampling (typical acceptance, "
+                         "eps 0.09, delta 0.3) on the target's logits")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain streaming copy (read 256 MiB, write 256 MiB) so that a counter run can "
                          "scale FETCH_SIZE / WRITE_SIZE by what they read for a kernel of known traffic")
@@ -238,13 +241,20 @@ def main():
     sal_len0 = torch.full((Bsz,), Ls, dtype=torch.int32, device=dev)
     sal_len = sal_len0.clone()
 
+    sampling = args.temperature > 0.0
+    t_logits = torch.zeros((Bsz, T, cfg.vocab), dtype=torch.float32, device=dev) if sampling else None
+    u_draws = torch.rand((Bsz,), generator=torch.Generator(device=dev).manual_seed(1), device=dev) if sampling else None
+
     def step():
         sal_len.copy_(sal_len0)          # every step repeats the same work: the SAL cache does not grow across steps
         ctx.amph_draft(dstruct, h, tok, sal_kv, sal_len, topk_idx, topk_val, None)
         ctx.amph_tree_build(tree, tok, topk_idx, kv_len, tree_tok, tree_pos)
         ctx.amph_target_forward(tree, structs, dw["embed"], final_norm, t_lm_head, tree_tok, tree_pos, k_caches, v_caches,
-                                kv_len, None, None, tgt, tiled_structs=tiled_structs, lm_head_tiled=lm_tiled)
-        ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
+                                kv_len, None, t_logits, tgt, tiled_structs=tiled_structs, lm_head_tiled=lm_tiled)
+        if sampling:
+            ctx.amph_accept_typical(tree, tree_tok, t_logits, args.temperature, 0.09, 0.3, u_draws, a_len, a_path, nxt, best)
+        else:
+            ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
 
     if args.calibrate_copy:
         n_cal = 64 * 2 ** 20                                   # float32 elements: 256 MiB in, 256 MiB out
@@ -323,7 +333,9 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload} full step: draft (K={K}, top-{cfg.topk}, SAL cache {Ls}) + {n_layers}-layer "
-                               f"tree verification (T={T}, L={L}) + greedy accept, batch {Bsz}",
+                               f"tree verification (T={T}, L={L}) + "
+                               + (f"typical acceptance at temperature {args.temperature}" if sampling else "greedy accept")
+                               + f", batch {Bsz}",
                    "layers": n_layers, "tree_nodes": T, "kv_len": L if not args.unequal_kv else kv_lens, "batch": Bsz,
                    "target_weight_layout": "row-major" if args.row_major else "tiled",
                    "draft_variant": {"adaptation_layers": n_stages, "position_encoding": not args.no_pe,

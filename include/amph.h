@@ -190,6 +190,24 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
                         const int32_t *tgt_argmax, const float *tgt_logits, int32_t *accept_len,
                         int32_t *accept_path, int32_t *next_tok, int32_t *best_node, void *workspace);
 
+/* ---- next: acceptance under random sampling (Table 2, Temperature = 0.7) -------------------------------
+ * The paper reports results at this temperature but states no acceptance rule.  The rule built here is a
+ * reading: typical acceptance as defined by the multi-head decoding framework whose tree and settings the
+ * paper adopts (its reference cai2024medusa).  With p_j = softmax(tgt_logits[b, j, :] / temperature) and
+ * H(p_j) its entropy in nats,
+ *   pass[root] = 1;  pass[i] = pass[parent_i] and p_parent_i(tree_tok[i]) > min(eps, delta * exp(-H(p_parent_i)));
+ *   best = deepest passing node (lowest node id among equals); accept_len, accept_path as in amph_accept;
+ *   next_tok = the first v with sum_{w <= v} p_best(w) > u[b] (vocabulary order; the last token of non-zero
+ *   probability if rounding leaves none).
+ * All arithmetic is float32; sums run in a fixed order, so equal inputs give equal outputs.
+ *   tgt_logits [B, T, V] float32 (amph_target_forward's logits_out); every row needs a finite maximum
+ *   u [B] float32, uniform in [0, 1), drawn by the caller      outputs as in amph_accept
+ * AMPH_EINVAL unless temperature > 0, eps >= 0 and delta >= 0.  A tree token outside [0, V) never passes. */
+amph_status amph_accept_typical(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok,
+                                const float *tgt_logits, float temperature, float eps, float delta,
+                                const float *u, int32_t *accept_len, int32_t *accept_path, int32_t *next_tok,
+                                int32_t *best_node, void *workspace);
+
 /* ---- between two steps: commit the accepted path (Sec. 2 "Speculative Decoding") ---------------------
  * After amph_accept, for every batch element b with a = accept_len[b] and path nodes p_0 = root .. p_a:
  *   * in every layer the K/V rows of p_1 .. p_a move from tree slots kv_len[b] + p_j to rows kv_len[b] + j

@@ -410,19 +410,21 @@ def accept_typical(tree: Tree, tree_tok: np.ndarray, logits: np.ndarray, tempera
     at the caller's uniform number u in [0, 1): the first v with sum_{w <= v} p_best(w) > u (the last token of
     non-zero probability if rounding leaves none).
 
-    Returns (accept_len, path [K+1] -1 padded, next_tok, best_node, margin) where margin[i] = p - threshold of
-    node i (margin[0] = +inf): a test that compares a float32 implementation can see which decisions are
-    near ties."""
+    Returns (accept_len, path [K+1] -1 padded, next_tok, best_node, margin, threshold) where margin[i] = p -
+    threshold of node i (margin[0] = +inf) and threshold[i] the threshold it was held against: a test that
+    compares a float32 implementation can see which decisions are near ties."""
     T = tree.T
     lg = _f(logits) / float(temperature)
     p = np.stack([softmax(lg[j]) for j in range(T)])
     H = np.array([-np.sum(p[j][p[j] > 0] * np.log(p[j][p[j] > 0])) for j in range(T)])
     thr = np.minimum(float(eps), float(delta) * np.exp(-H))
     margin = np.full(T, np.inf)
+    held = np.zeros(T)
     ok = np.zeros(T, dtype=bool)
     ok[0] = True
     for i in range(1, T):                     # parents precede children in node order
         j = tree.parent[i]
+        held[i] = thr[j]
         margin[i] = p[j][int(tree_tok[i])] - thr[j]
         ok[i] = ok[j] and margin[i] > 0.0
     best = 0
@@ -445,7 +447,7 @@ def accept_typical(tree: Tree, tree_tok: np.ndarray, logits: np.ndarray, tempera
             break
     if nxt < 0:
         nxt = int(np.nonzero(p[best] > 0)[0][-1])
-    return int(tree.depth[best]), path, int(nxt), int(best), margin
+    return int(tree.depth[best]), path, int(nxt), int(best), margin, held
 
 
 # ----------------------------------------------------------------------------

@@ -63,6 +63,7 @@ EXPORTS = {
     "amph_tree_build": (C.c_int, [C.c_void_p] * 7),
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
+    "amph_accept_typical": (C.c_int, [C.c_void_p] * 4 + [C.c_float] * 3 + [C.c_void_p] * 6),
     "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.POINTER(amph_layer_tiled), C.c_int]
                             + [C.c_void_p] * 13),
     "amph_tiled_bytes": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_size_t)]),
@@ -247,6 +248,13 @@ class Context:
         self._check(lib().amph_accept(self.handle, tree.handle, _ptr(tree_tok), _ptr(tgt_argmax), _ptr(tgt_logits),
                                       _ptr(accept_len), _ptr(accept_path), _ptr(next_tok), _ptr(best_node),
                                       _ptr(self.workspace)), "amph_accept")
+
+    def amph_accept_typical(self, tree: Tree, tree_tok, tgt_logits, temperature, eps, delta, u, accept_len, accept_path,
+                            next_tok, best_node):
+        self._check(lib().amph_accept_typical(self.handle, tree.handle, _ptr(tree_tok), _ptr(tgt_logits),
+                                              float(temperature), float(eps), float(delta), _ptr(u), _ptr(accept_len),
+                                              _ptr(accept_path), _ptr(next_tok), _ptr(best_node), _ptr(self.workspace)),
+                    "amph_accept_typical")
 
     def amph_target_forward(self, tree: Tree, layer_structs, embed, final_norm, lm_head, tree_tok, tree_pos, k_caches,
                             v_caches, kv_len, hidden_out, logits_out, tgt_argmax, tiled_structs=None, lm_head_tiled=None):

@@ -20,7 +20,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {   // byte offsets into the caller's workspace
   size_t x, q, att, y, act, h[2], Hp, Qa, Ka, Va, ctxa, attn_o, logits, topk_ws;                 // draft
-  size_t xres, xn, qb, attb, actb, slabs, amax_val, amax_idx, ver_part, tgt_tmp, rope_cs, xt;  // target
+  size_t xres, xn, qb, attb, actb, slabs, amax_val, amax_idx, ver_part, tgt_tmp, row_stats, rope_cs, xt;  // target
   size_t slabs_floats, ver_part_floats;
   size_t total;
 };
@@ -124,6 +124,7 @@ WsLayout make_layout(const amph_config &c) {
   w.ver_part = take(vfl * 4);
   w.ver_part_floats = vfl;
   w.tgt_tmp = take(M * 4);
+  w.row_stats = take(M * 16);
   w.rope_cs = take(M * (size_t)(c.head_dim / 2) * 8);
   w.total = at;
   return w;
@@ -549,6 +550,22 @@ amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tre
   }
   HIP_TRY(ctx, launch_accept(ctx->stream, tree->d_parent, tree->d_depth, tree->T, ctx->cfg.batch, ctx->cfg.K, tree_tok, tgt,
                              accept_len, accept_path, next_tok, best_node));
+  return AMPH_OK;
+}
+
+amph_status amph_accept_typical(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok, const float *tgt_logits,
+                                float temperature, float eps, float delta, const float *u, int32_t *accept_len,
+                                int32_t *accept_path, int32_t *next_tok, int32_t *best_node, void *workspace) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!tree_tok || !tgt_logits || !u || !accept_len || !accept_path || !next_tok || !best_node || !workspace)
+    return fail(ctx, AMPH_EINVAL, "amph_accept_typical: null argument");
+  if (!(temperature > 0.f) || !(eps >= 0.f) || !(delta >= 0.f))      // (also rejects NaN)
+    return fail(ctx, AMPH_EINVAL, "amph_accept_typical: temperature must be positive, eps and delta non-negative");
+  if (!aligned16(workspace)) return fail(ctx, AMPH_EINVAL, "amph_accept_typical: workspace must be 16-byte aligned");
+  if (amph_status s = check_tree(ctx, tree, "amph_accept_typical")) return s;
+  HIP_TRY(ctx, launch_accept_typical(ctx->stream, tree->d_parent, tree->d_depth, tree->T, ctx->cfg.batch, ctx->cfg.K,
+                                     ctx->cfg.vocab, tree_tok, tgt_logits, temperature, eps, delta, u, accept_len, accept_path,
+                                     next_tok, best_node, (float *)((char *)workspace + ctx->ws.row_stats)));
   return AMPH_OK;
 }
 

@@ -39,6 +39,11 @@ hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int 
 hipError_t launch_tree_build(hipStream_t st, const int32_t *depth, const int32_t *rank, int T, int B, int K, int topk,
                              const int32_t *root_tok, const int32_t *topk_idx, const int32_t *kv_len, int32_t *tree_tok,
                              int32_t *tree_pos);
+// stats_ws: B * T * 4 floats (16-byte aligned)
+hipError_t launch_accept_typical(hipStream_t st, const int32_t *parent, const int32_t *depth, int T, int B, int K, int V,
+                                 const int32_t *tree_tok, const float *logits, float temperature, float eps, float delta,
+                                 const float *u, int32_t *accept_len, int32_t *accept_path, int32_t *next_tok,
+                                 int32_t *best_node, float *stats_ws);
 hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *depth, int T, int B, int K,
                          const int32_t *tree_tok, const int32_t *tgt, int32_t *accept_len, int32_t *accept_path,
                          int32_t *next_tok, int32_t *best_node);

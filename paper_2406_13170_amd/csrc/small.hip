@@ -433,6 +433,179 @@ hipError_t launch_accept(hipStream_t st, const int32_t *parent, const int32_t *d
 }
 
 // =====================================================================================================
+// Acceptance under random sampling (Table 2, Temperature = 0.7).  The paper states no rule; the one built is
+// typical acceptance as the multi-head framework the paper adopts its tree from defines it: with
+// p_j = softmax(logits_j / temperature) and H its entropy in nats, child i of j passes iff
+// p_j(tok_i) > min(eps, delta * exp(-H(p_j))); the deepest node whose whole chain passes wins (lowest id among
+// equals) and the following token is drawn from p_best by inverting its cumulative distribution (vocabulary
+// order) at the caller's uniform number.
+//   k_row_softmax_stats: one workgroup per tree node: m = max l, Z = sum exp((l - m) / t),
+//     H = ln Z - sum(e x) / Z with x = (l - m) / t, e = exp(x)            -> stats[row] = (m, Z, H, 0)
+//   k_accept_typical: one workgroup per batch element: the pass flags, the winner as in k_accept, then the draw:
+//     thread t sums its run of consecutive tokens, a scan over the threads finds the run where the cumulative
+//     sum first exceeds u * Z, and that thread walks its run.  If rounding leaves no such token (u * Z at or
+//     above the total), the last token of non-zero probability is taken.
+// =====================================================================================================
+constexpr int AT_THREADS = 1024, AT_WAVES = AT_THREADS / WAVE;
+
+__device__ __forceinline__ float at_block_max(float v, float *sm) {
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
+  __syncthreads();                                        // sm may still be read from an earlier reduction
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+  for (int w = 1; w < AT_WAVES; ++w) r = fmaxf(r, sm[w]);
+  return r;
+}
+__device__ __forceinline__ float at_block_sum(float v, float *sm) {      // fixed order: lanes by butterfly, waves ascending
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, WAVE);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = sm[0];
+  for (int w = 1; w < AT_WAVES; ++w) r += sm[w];
+  return r;
+}
+
+__global__ __launch_bounds__(AT_THREADS) void k_row_softmax_stats(const float *logits, int V, float inv_temp, float4 *stats) {
+  __shared__ float sm[AT_WAVES];
+  const float *l = logits + (size_t)blockIdx.x * V;
+  const int t = threadIdx.x;
+  float m = -__builtin_huge_valf();
+  for (int v = t; v < V; v += AT_THREADS) m = fmaxf(m, l[v]);
+  m = at_block_max(m, sm);
+  float z = 0.f, sx = 0.f;
+  for (int v = t; v < V; v += AT_THREADS) {
+    const float x = (l[v] - m) * inv_temp, e = expf(x);
+    z += e;
+    if (e > 0.f) sx += e * x;                             // a token of probability zero adds nothing (0 * -inf)
+  }
+  z = at_block_sum(z, sm);
+  sx = at_block_sum(sx, sm);
+  if (t == 0) stats[blockIdx.x] = make_float4(m, z, logf(z) - sx / z, 0.f);
+}
+
+__global__ __launch_bounds__(AT_THREADS) void k_accept_typical(const int32_t *parent, const int32_t *depth, int T, int K, int V,
+                                                               const int32_t *tree_tok, const float *logits, const float4 *stats,
+                                                               float inv_temp, float eps, float delta, const float *u,
+                                                               int32_t *accept_len, int32_t *accept_path, int32_t *next_tok,
+                                                               int32_t *best_node) {
+  __shared__ float sm[AT_WAVES];
+  __shared__ int s_pass[AMPH_MAX_TREE];
+  __shared__ int s_key[AT_WAVES];
+  __shared__ int s_best, s_found;
+  const int b = blockIdx.x, t = threadIdx.x;
+  const int32_t *tok = tree_tok + (size_t)b * T;
+  if (t < T) {
+    int pass = 1;                                          // the root
+    if (t > 0) {
+      const int j = parent[t], tk = tok[t];
+      const size_t row = (size_t)b * T + j;
+      const float4 st = stats[row];
+      pass = 0;
+      if (tk >= 0 && tk < V) {
+        const float p = expf((logits[row * V + tk] - st.x) * inv_temp) / st.y;
+        pass = p > fminf(eps, delta * expf(-st.z));
+      }
+    }
+    s_pass[t] = pass;
+  }
+  if (t == 0) s_found = -1;
+  __syncthreads();
+  int key = -1;
+  if (t < T) {
+    bool ok = true;
+    int j = t;
+    for (int hop = 0; hop <= AMPH_MAX_HEADS_K && j > 0; ++hop) {
+      if (!s_pass[j]) { ok = false; break; }
+      j = parent[j];
+    }
+    if (ok) key = depth[t] * 256 + (255 - t);
+  }
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) key = max(key, __shfl_xor(key, off, WAVE));
+  if ((t & 63) == 0) s_key[t >> 6] = key;
+  __syncthreads();
+  if (t == 0) {
+    int best_key = s_key[0];
+    for (int w = 1; w < AT_WAVES; ++w) best_key = max(best_key, s_key[w]);
+    const int a = best_key >> 8, best = 255 - (best_key & 255);     // the root always qualifies
+    accept_len[b] = a;
+    best_node[b] = best;
+    s_best = best;
+    for (int dd = 0; dd <= K; ++dd) accept_path[(size_t)b * (K + 1) + dd] = -1;
+    int j = best;
+    for (int dd = a; dd >= 0 && j >= 0; --dd) { accept_path[(size_t)b * (K + 1) + dd] = j; j = parent[j]; }
+  }
+  __syncthreads();
+  // ---- the draw from p_best
+  const size_t row = (size_t)b * T + s_best;
+  const float *l = logits + row * V;
+  const float4 st = stats[row];
+  const float target = u[b] * st.y;
+  const int C = (V + AT_THREADS - 1) / AT_THREADS, v0 = min(t * C, V), v1 = min(v0 + C, V);
+  float run = 0.f;
+  int last_live = -1;
+  for (int v = v0; v < v1; ++v) {
+    const float e = expf((l[v] - st.x) * inv_temp);
+    run += e;
+    if (e > 0.f) last_live = v;
+  }
+  // inclusive scan of the runs: inside a wave, then over the wave totals (ascending)
+  float inc = run;
+  #pragma unroll
+  for (int off = 1; off < WAVE; off <<= 1) {
+    const float o = __shfl_up(inc, off, WAVE);
+    if ((t & 63) >= off) inc += o;
+  }
+  if ((t & 63) == 63) sm[t >> 6] = inc;
+  __syncthreads();
+  float base = 0.f;
+  for (int w = 0; w < (t >> 6); ++w) base += sm[w];
+  inc += base;
+  const float prev = __shfl_up(inc, 1, WAVE);
+  const float exc = (t & 63) ? prev : base;               // exactly the thread before's inclusive sum
+  // the sums never decrease with t and exc(t + 1) = inc(t): at most one thread sees the crossing inside its run
+  if (exc <= target && inc > target) {
+    float acc = exc;
+    int pick = -1;
+    for (int v = v0; v < v1; ++v) {
+      acc += expf((l[v] - st.x) * inv_temp);
+      if (acc > target) { pick = v; break; }
+    }
+    if (pick < 0) pick = max(last_live, v0);              // (acc and inc differ by rounding order only)
+    s_found = pick;
+  }
+  #pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) last_live = max(last_live, __shfl_xor(last_live, off, WAVE));
+  __syncthreads();
+  if ((t & 63) == 0) s_key[t >> 6] = last_live;
+  __syncthreads();
+  if (t == 0) {
+    int pick = s_found;
+    if (pick < 0) {
+      pick = s_key[0];
+      for (int w = 1; w < AT_WAVES; ++w) pick = max(pick, s_key[w]);
+    }
+    next_tok[b] = min(max(pick, 0), V - 1);
+  }
+}
+
+hipError_t launch_accept_typical(hipStream_t st, const int32_t *parent, const int32_t *depth, int T, int B, int K, int V,
+                                 const int32_t *tree_tok, const float *logits, float temperature, float eps, float delta,
+                                 const float *u, int32_t *accept_len, int32_t *accept_path, int32_t *next_tok,
+                                 int32_t *best_node, float *stats_ws) {
+  if (T < 1 || T > AMPH_MAX_TREE || V < 1 || !(temperature > 0.f)) return hipErrorInvalidValue;
+  const float inv_temp = 1.0f / temperature;
+  hipLaunchKernelGGL(k_row_softmax_stats, dim3(B * T), dim3(AT_THREADS), 0, st, logits, V, inv_temp, (float4 *)stats_ws);
+  hipLaunchKernelGGL(k_accept_typical, dim3(B), dim3(AT_THREADS), 0, st, parent, depth, T, K, V, tree_tok, logits,
+                     (const float4 *)stats_ws, inv_temp, eps, delta, u, accept_len, accept_path, next_tok, best_node);
+  return hipGetLastError();
+}
+
+// =====================================================================================================
 // The loop around the step (Sec. 2 "Speculative Decoding"; Eq. 1 keeps one adaptation-layer cache row per
 // committed position).
 //   k_kv_commit: for one (layer, batch element, head), the K/V rows of the accepted path's nodes 1..a move

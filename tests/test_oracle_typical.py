@@ -49,7 +49,7 @@ def test_uniform_distribution_closed_form(delta, expect_all):
     tree = small_tree()
     tok = np.arange(tree.T, dtype=np.int32) % V
     logits = np.full((tree.T, V), 1.7)
-    a, path, nxt, best, margin = orc.accept_typical(tree, tok, logits, 0.7, 0.5, delta, 0.0)
+    a, path, nxt, best, margin, _ = orc.accept_typical(tree, tok, logits, 0.7, 0.5, delta, 0.0)
     if expect_all:
         deepest = int(np.max(tree.depth))
         assert a == deepest and best == int(np.nonzero(tree.depth == deepest)[0][0])
@@ -115,7 +115,7 @@ def test_a_rejected_parent_rejects_its_descendants():
     logits = np.zeros((5, V))
     logits[:, 1] = 5.0                                  # token 1 is typical everywhere
     tok = np.array([0, 1, 9, 1, 1], dtype=np.int32)     # node 2 carries an improbable token
-    a, path, nxt, best, margin = orc.accept_typical(tree, tok, logits, 1.0, 0.09, 0.3, 0.0)
+    a, path, nxt, best, margin, _ = orc.accept_typical(tree, tok, logits, 1.0, 0.09, 0.3, 0.0)
     assert a == 1 and best == 1 and list(path) == [0, 1, -1, -1, -1]
     assert margin[3] > 0 and margin[4] > 0              # they would pass on their own
 
