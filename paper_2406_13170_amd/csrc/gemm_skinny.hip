@@ -88,14 +88,14 @@ __device__ __forceinline__ RowMap map_block(const GemmArgs &a, int b, int r16) {
 // of the workgroup (NT of them) takes part.
 template <typename T, int EPI>
 __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct, int CT_PITCH, int tile, int nb, int m_base,
-                                              int split, int nblk, int tid, int NT) {
+                                              int split, int nblk, int tid, int NT, int rows = GM_BM) {   // rows of Ct that are live
   const int BN = 16 * nb;
   if (EPI == EPI_STORE) {
     // out is [split_k][M][N]: slab `split` receives this workgroup's partial sums
     const int N = a.seg_rows;
     float *slab = a.out + (size_t)split * a.M * N;
     const int Q = BN / 4;                                   // 4 adjacent columns per thread (one by one in a ragged last tile)
-    for (int idx = tid; idx < GM_BM * Q; idx += NT) {
+    for (int idx = tid; idx < rows * Q; idx += NT) {
       const int m = idx / Q, r = (idx % Q) * 4, mg = m_base + m, n = tile * BN + r;
       if (mg >= a.M || n >= N) continue;
       const f32x4 v = *reinterpret_cast<const f32x4 *>(Ct + m * CT_PITCH + r);
@@ -111,7 +111,7 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
     const int f = a.seg_rows, H = 8 * nb;
     T *act = (T *)a.act;
     // one (token, block) per thread: 8 adjacent outputs leave as one piece (element by element in a ragged last block)
-    for (int idx = tid; idx < GM_BM * nb; idx += NT) {
+    for (int idx = tid; idx < rows * nb; idx += NT) {
       const int m = idx / nb, w = idx % nb, mg = m_base + m, j0 = tile * H + w * 8;
       if (mg >= a.M || j0 >= f) continue;
       const float *crow = Ct + m * CT_PITCH + w * 16;
@@ -131,71 +131,94 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
   } else if (EPI == EPI_QKV_ROPE) {
     const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
     // q and k blocks: one (block, token) per thread = 8 rotation pairs.  Everything the item needs from global
-    // memory (64 bytes of the cos/sin table) is requested at once, and the 8 + 8 results leave as 16-byte pieces:
-    // dims e0 .. e0+7 (and their partners at + d_h/2) are adjacent in q and inside a fragment of the tiled K cache.
-    for (int idx = tid; idx < nb * GM_BM; idx += NT) {
-      const int w = idx / GM_BM, m = idx % GM_BM, b = tile * nb + w, mg = m_base + m;
-      if (b >= nblk || mg >= a.M) continue;
-      const int seg = b / bps, bl = b % bps;
-      if (seg >= 2) continue;
-      const int head = bl / bph, e0 = (bl % bph) * 8;
-      const float4 *csp = reinterpret_cast<const float4 *>(a.rope_cs + (size_t)mg * half + e0);   // (cos, sin) x 8
-      const float4 c01 = csp[0], c23 = csp[1], c45 = csp[2], c67 = csp[3];
-      const float cs[8] = {c01.x, c01.z, c23.x, c23.z, c45.x, c45.z, c67.x, c67.z};
-      const float sn[8] = {c01.y, c01.w, c23.y, c23.w, c45.y, c45.w, c67.y, c67.w};
-      const float *crow = Ct + m * CT_PITCH + w * 16;
-      float y1[8], y2[8];
+    // memory (64 bytes of the cos/sin table, the committed length) is requested first, for up to QK_U items of the
+    // thread at once: a wave of the wide kernel walks several items, and stores in between would keep the next item's
+    // loads from starting early.  The 8 + 8 results leave as 16-byte pieces: dims e0 .. e0+7 (and their partners at
+    // + d_h/2) are adjacent in q and inside a fragment of the tiled K cache.
+    constexpr int QK_U = 3;
+    for (int base = tid; base < nb * rows; base += QK_U * NT) {
+      float4 tab[QK_U][4];
+      int Lb[QK_U];
       #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float x1 = crow[j], x2 = crow[8 + j];
-        y1[j] = x1 * cs[j] - x2 * sn[j];
-        y2[j] = x2 * cs[j] + x1 * sn[j];
+      for (int u = 0; u < QK_U; ++u) {
+        const int idx = base + u * NT, w = idx / rows, m = idx % rows, b = tile * nb + w, mg = m_base + m;
+        const bool live = idx < nb * rows && b < nblk && mg < a.M && b / bps < 2;
+        const int e0 = ((b % bps) % bph) * 8;
+        // (unconditional loads from clamped addresses: dead items read the table's first entry and element 0's length)
+        const float4 *csp = reinterpret_cast<const float4 *>(a.rope_cs + (live ? (size_t)mg * half + e0 : (size_t)0));
+        #pragma unroll
+        for (int k = 0; k < 4; ++k) tab[u][k] = csp[k];
+        Lb[u] = a.kv_len[live ? mg / a.T_nodes : 0];
       }
-      T *dst1, *dst2;
-      if (seg == 0) {
-        dst1 = (T *)a.q_out + (size_t)mg * d + head * d_h + e0;
-        dst2 = dst1 + half;
-      } else {
-        const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-        if (L < 0 || L + a.T_nodes > a.max_kv) {
-          if (node == 0 && e0 == 0) atomicOr(a.dev_status, 2u);
-          continue;
+      #pragma unroll
+      for (int u = 0; u < QK_U; ++u) {
+        const int idx = base + u * NT, w = idx / rows, m = idx % rows, b = tile * nb + w, mg = m_base + m;
+        if (idx >= nb * rows || b >= nblk || mg >= a.M) continue;
+        const int seg = b / bps, bl = b % bps;
+        if (seg >= 2) continue;
+        const int head = bl / bph, e0 = (bl % bph) * 8;
+        const float4 c01 = tab[u][0], c23 = tab[u][1], c45 = tab[u][2], c67 = tab[u][3];
+        const float cs[8] = {c01.x, c01.z, c23.x, c23.z, c45.x, c45.z, c67.x, c67.z};
+        const float sn[8] = {c01.y, c01.w, c23.y, c23.w, c45.y, c45.w, c67.y, c67.w};
+        const float *crow = Ct + m * CT_PITCH + w * 16;
+        float y1[8], y2[8];
+        #pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float x1 = crow[j], x2 = crow[8 + j];
+          y1[j] = x1 * cs[j] - x2 * sn[j];
+          y2[j] = x2 * cs[j] + x1 * sn[j];
         }
-        T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-        dst1 = kc + k_tiled_index<T>(L + node, e0, d_h);
-        dst2 = kc + k_tiled_index<T>(L + node, e0 + half, d_h);
+        T *dst1, *dst2;
+        if (seg == 0) {
+          dst1 = (T *)a.q_out + (size_t)mg * d + head * d_h + e0;
+          dst2 = dst1 + half;
+        } else {
+          const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = Lb[u];
+          if (L < 0 || L + a.T_nodes > a.max_kv) {
+            if (node == 0 && e0 == 0) atomicOr(a.dev_status, 2u);
+            continue;
+          }
+          T *kc = (T *)a.k_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+          dst1 = kc + k_tiled_index<T>(L + node, e0, d_h);
+          dst2 = kc + k_tiled_index<T>(L + node, e0 + half, d_h);
+        }
+        store4<T>(dst1, y1); store4<T>(dst1 + 4, y1 + 4);
+        store4<T>(dst2, y2); store4<T>(dst2 + 4, y2 + 4);
       }
-      store4<T>(dst1, y1); store4<T>(dst1 + 4, y1 + 4);
-      store4<T>(dst2, y2); store4<T>(dst2 + 4, y2 + 4);
     }
-    // v blocks: 512 items per row block (8 dims x 64 tokens), so a wave's 64 items always belong to one block
-    for (int idx = tid; idx < nb * 512; idx += NT) {
-      const int w = idx >> 9, rem = idx & 511, b = tile * nb + w;
-      if (b >= nblk) continue;
-      const int seg = b / bps, bl = b % bps;
-      if (seg < 2) continue;
-      // consecutive threads -> consecutive tree rows, which are adjacent inside a step-tiled piece
-      const int j = rem >> 6, m = rem & 63, mg = m_base + m;
-      if (mg >= a.M) continue;
-      const int bb = mg / a.T_nodes, node = mg % a.T_nodes, L = a.kv_len[bb];
-      if (L < 0 || L + a.T_nodes > a.max_kv) continue;
-      #pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
-        T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
-        vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
+    // v blocks: 8 * rows items per row block (8 dims x the live tokens).  rows (32 or 64) divides the number of
+    // threads, so a thread keeps its token through the loop: its committed length is read once, ahead of the stores,
+    // and consecutive threads write consecutive tree rows, which are adjacent inside a step-tiled piece.
+    {
+      const int m = tid % rows, mg = m_base + m;
+      const bool row_ok = mg < a.M;
+      const int bb = row_ok ? mg / a.T_nodes : 0, node = row_ok ? mg % a.T_nodes : 0;
+      const int L = a.kv_len[bb];
+      if (row_ok && L >= 0 && L + a.T_nodes <= a.max_kv) {
+        for (int q = tid / rows; q < nb * 8; q += NT / rows) {
+          const int w = q >> 3, j = q & 7, b = tile * nb + w;
+          if (b >= nblk) continue;
+          const int seg = b / bps, bl = b % bps;
+          if (seg < 2) continue;
+          #pragma unroll
+          for (int hh = 0; hh < 2; ++hh) {
+            const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
+            T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
+            vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
+          }
+        }
       }
     }
   } else if (EPI == EPI_ARGMAX) {
     const int N = a.seg_rows;
     if (a.logits) {
-      for (int idx = tid; idx < GM_BM * BN; idx += NT) {
+      for (int idx = tid; idx < rows * BN; idx += NT) {
         const int m = idx / BN, r = idx % BN, mg = m_base + m, n = tile * BN + r;
         if (mg < a.M && n < N) a.logits[(size_t)mg * N + n] = Ct[m * CT_PITCH + r];
       }
     }
     // 4 threads per token row, BN/4 columns each, then a 4-lane butterfly (ties -> lower column)
-    for (int t4 = tid; t4 < 4 * GM_BM; t4 += NT) {        // NT is a multiple of 64: the 4 lanes of a row stay in one wave
+    for (int t4 = tid; t4 < 4 * rows; t4 += NT) {         // NT and 4 * rows are multiples of 64: the 4 lanes of a row stay in one wave
       const int m = t4 >> 2, part = t4 & 3, mg = m_base + m;
       float bv = -__builtin_huge_valf(); int bi = 0x7fffffff;
       for (int r = part * (BN / 4); r < (part + 1) * (BN / 4); ++r) {
@@ -400,7 +423,9 @@ constexpr int GW_STEPS = 8;        // steps (64 bytes of k) per weight stage
 constexpr int GW_R = 3;            // weight stages in the LDS ring
 constexpr int GW_NL = 2;           // loader waves
 constexpr int GW_MAX_NP = 3;       // pairs of weight row blocks per workgroup
-constexpr int GW_MAX_NW = 6;       // math waves = blocks of 64 activation rows per workgroup
+constexpr int GW_MAX_NW = 8;       // math waves per workgroup with 2 tiles of 32 activation rows each (two waves per SIMD)
+constexpr int GW_MAX_NW3 = 4;      // ... with 3 tiles each: one wave per SIMD (three tiles of accumulators need 222 registers)
+constexpr int GW_MAX_TW = 3;
 constexpr int GW_XD = 4;           // steps of activations requested ahead
 constexpr int GW_MIN_MBLOCKS = 3;  // blocks of 64 activation rows from which the wide kernel is used
 constexpr int GW_AUX_NT = 2;       // cache-policy bits of the global-to-LDS load: non-temporal (the weights are read once)
@@ -425,8 +450,8 @@ __global__ __launch_bounds__(256) void k_tile_rows(const unsigned char *x, int M
   }
 }
 
-template <typename T, int EPI, int NP>
-__global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const GemmArgs a, int tiles, int mgroups, int m32_tiles) {
+template <typename T, int EPI, int NP, int TW, int NWMAX>      // NWMAX = 4: one math wave per SIMD (256 registers each); 8: two (168)
+__global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmArgs a, int tiles, int mgroups, int m32_tiles) {
   extern __shared__ __align__(16) unsigned char gw_lds[];
   constexpr int NB = 2 * NP, STAGE = NB * GW_STEPS * 1024, PERL = NB * GW_STEPS / GW_NL;
   static_assert(GW_R == 3 && PERL * (GW_R - 2) <= 63, "loader wave's outstanding loads");
@@ -436,38 +461,64 @@ __global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const Ge
   const int id = blockIdx.x, unit = (id / 8 / mgroups) * 8 + (id & 7), mgroup = (id / 8) % mgroups;
   if (unit >= tiles * S) return;                          // padding of the last group of 8 units (whole workgroup)
   const int tile = unit / S, split = unit % S;
-  const int m_group = mgroup * nw * GM_BM;
+  constexpr int XD = (TW == 3 || NWMAX == 8) ? 2 : GW_XD; // steps of activations requested ahead (registers)
+  static_assert(GW_STEPS % XD == 0, "the activation ring is indexed statically inside a stage");
+  const int m_group = mgroup * nw * (TW * 32);
   const int total_steps = a.Kd * (int)sizeof(T) / 64;
   const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
   const int n = s1 - s0;
   const int P = (n + GW_STEPS - 1) / GW_STEPS;             // weight stages
   const int nblk = gemm_blocks(EPI, a.seg_rows);
 
-  f32x16 acc[NP][2];
+  f32x16 acc[NP][TW];
   #pragma unroll
   for (int p = 0; p < NP; ++p)
     #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < TW; ++t)
       #pragma unroll
       for (int i = 0; i < 16; ++i) acc[p][t][i] = 0.f;
 
   if (wave >= nw) {
     // ---------------------------------------------------------------------------- loader wave
-    // fragments l, l + 2, ... of a stage; fragment f = block (f / 8), step (f % 8).  Lane (g, r16) fetches piece g
-    // of row r16, which lands at (g * 16 + r16) * 16 of the fragment's KB in LDS.  Steps past the slice (last
-    // stage) re-read its last step and are never used.
+    // Loader l takes steps l * HS .. + HS - 1 of every block of a stage (fragment f = block * GW_STEPS + step lies at
+    // f * 1024 of the stage).  Lane (g, r16) fetches piece g of row r16, which lands at (g * 16 + r16) * 16 of the
+    // fragment's KB in LDS.  Those HS fragments are adjacent both in memory and in LDS, so they share one address and
+    // one LDS base and differ in the instruction's immediate offset (applied to both sides): a load costs the wave one
+    // instruction instead of a dozen.  That matters because the loader shares its SIMD's issue port with a math wave
+    // whose matrix-core instructions keep it busy (measured before: 233 clocks per load, the weight ring the
+    // bottleneck).  A ragged last stage takes the general path: steps past the slice re-read its last step and are
+    // never used.
+    constexpr int HS = GW_STEPS / GW_NL;
+    static_assert(GW_STEPS % GW_NL == 0 && HS == 4, "four immediate offsets per block, written out below");
     const int l = wave - nw, g = lane >> 4, r16 = lane & 15;
     const unsigned char *wbase = (const unsigned char *)a.wt + r16 * 64 + g * 16;
+    const unsigned char *bsrc[NB];
+    #pragma unroll
+    for (int b = 0; b < NB; ++b) bsrc[b] = wbase + ((size_t)min(tile * NB + b, nblk - 1) * total_steps + s0 + l * HS) * 1024;
     auto issue = [&](int p) {
       unsigned char *lp = gw_lds + (p % GW_R) * STAGE;
-      #pragma unroll
-      for (int j = 0; j < PERL; ++j) {
-        const int f = l + j * GW_NL, b = f / GW_STEPS, s = f % GW_STEPS;
-        const int blk = min(tile * NB + b, nblk - 1);
-        const int st = min(s0 + p * GW_STEPS + s, s1 - 1);
-        const unsigned char *src = wbase + ((size_t)blk * total_steps + st) * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(lp + f * 1024), 16, 0, GW_AUX_NT);
+      if ((p + 1) * GW_STEPS <= n) {                       // a whole stage (wave-uniform)
+        #pragma unroll
+        for (int b = 0; b < NB; ++b) {
+          const unsigned char *src = bsrc[b] + (size_t)p * (GW_STEPS * 1024);
+          unsigned char *dst = lp + (b * GW_STEPS + l * HS) * 1024;
+          const auto *gs = (const __attribute__((address_space(1))) void *)src;
+          auto *ld = (__attribute__((address_space(3))) void *)dst;
+          __builtin_amdgcn_global_load_lds(gs, ld, 16, 0, GW_AUX_NT);       // (the offset must be a literal)
+          __builtin_amdgcn_global_load_lds(gs, ld, 16, 1024, GW_AUX_NT);
+          __builtin_amdgcn_global_load_lds(gs, ld, 16, 2048, GW_AUX_NT);
+          __builtin_amdgcn_global_load_lds(gs, ld, 16, 3072, GW_AUX_NT);
+        }
+      } else {
+        #pragma unroll
+        for (int j = 0; j < PERL; ++j) {
+          const int b = j / HS, s = l * HS + j % HS, f = b * GW_STEPS + s;
+          const int blk = min(tile * NB + b, nblk - 1);
+          const int st = min(s0 + p * GW_STEPS + s, s1 - 1);
+          const unsigned char *src = wbase + ((size_t)blk * total_steps + st) * 1024;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                           (__attribute__((address_space(3))) void *)(lp + f * 1024), 16, 0, GW_AUX_NT);
+        }
       }
     };
     const int pro = P < GW_R - 1 ? P : GW_R - 1;
@@ -479,18 +530,18 @@ __global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const Ge
     }
   } else {
     // ------------------------------------------------------------------------------ math wave
-    // activation tiles 2 * wave, 2 * wave + 1 of the group (32 rows each); the 4 fragments of a step (two halves of
-    // the step's 64 bytes, two tiles) are requested GW_XD steps ahead
+    // activation tiles TW * wave .. + TW - 1 of the group (32 rows each); the 2 * TW fragments of a step (two halves
+    // of the step's 64 bytes for every tile) are requested XD steps ahead
     const int half = lane >> 5, r32 = lane & 31;
-    const int mt0 = (m_group >> 5) + 2 * wave;
+    const int mt0 = (m_group >> 5) + TW * wave;
     const unsigned char *xb = (const unsigned char *)a.xt + lane * 16;
-    uint4 xq[GW_XD][2][2];
-    auto load_x = [&](int i, uint4 (&xf)[2][2]) {
+    uint4 xq[XD][2][TW];
+    auto load_x = [&](int i, uint4 (&xf)[2][TW]) {
       const int st = s0 + max(min(i, n - 1), 0);           // unconditional: steps past the slice re-read the last one
       #pragma unroll
       for (int h = 0; h < 2; ++h)
         #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < TW; ++t) {
           const int mt = min(mt0 + t, m32_tiles - 1);      // tiles past the end (last wave) re-read the last tile; never stored
           xf[h][t] = ldg16(xb + ((size_t)(2 * st + h) * m32_tiles + mt) * 1024);
         }
@@ -498,7 +549,7 @@ __global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const Ge
     // weight piece of this lane inside a pair's two fragments of a step, for half-step h: + h * 512
     const int woff = (r32 >> 4) * (GW_STEPS * 1024) + (half * 16 + (r32 & 15)) * 16;
     #pragma unroll
-    for (int i = 0; i < GW_XD; ++i) load_x(i, xq[i]);
+    for (int i = 0; i < XD; ++i) load_x(i, xq[i]);
     for (int p = 0; p < P; ++p) {
       // Stage p is in LDS (pairs with the loaders' barrier).  A bare barrier: __syncthreads() would also wait for this
       // wave's outstanding activation loads (the fence it carries counts them since the kernel contains global-to-LDS
@@ -516,36 +567,42 @@ __global__ __launch_bounds__(64 * (GW_MAX_NW + GW_NL)) void k_gemm_wide(const Ge
             for (int pr = 0; pr < NP; ++pr) {
               const uint4 wf = *reinterpret_cast<const uint4 *>(sb + (2 * pr * GW_STEPS + s) * 1024 + h * 512);
               #pragma unroll
-              for (int t = 0; t < 2; ++t) acc[pr][t] = mma32<T>(wf, xq[s % GW_XD][h][t], acc[pr][t]);
+              for (int t = 0; t < TW; ++t) acc[pr][t] = mma32<T>(wf, xq[s % XD][h][t], acc[pr][t]);
             }
         }
-        load_x(i + GW_XD, xq[s % GW_XD]);
+        load_x(i + XD, xq[s % XD]);
       }
     }
   }
 
-  // ---- epilogues: every math wave handles its own 64 activation rows through its own Ct region in LDS (the ring is
-  // free by now), the 64 lanes playing the workgroup of the shared epilogue code.  Lane (half, r32) holds activation
-  // row t * 32 + r32 and weight rows (i / 4) * 8 + half * 4 + (i % 4) of each pair.
+  // ---- epilogues: every math wave handles its own activation rows through its own Ct region in LDS (the ring is
+  // free by now), one tile of 32 rows at a time, the 64 lanes playing the workgroup of the shared epilogue code.
+  // Lane (half, r32) holds activation row t * 32 + r32 and weight rows (i / 4) * 8 + half * 4 + (i % 4) of each pair.
   const int CT_PITCH = 16 * NB + 4;
   __syncthreads();                                         // every wave has left the ring
-  const int m_base = m_group + wave * GM_BM;
-  if (wave < nw && m_base < a.M) {                         // whole waves
-    float *Ct = reinterpret_cast<float *>(gw_lds) + (size_t)wave * GM_BM * CT_PITCH;
+  const int m_wave = m_group + wave * (TW * 32);
+  if (wave < nw && m_wave < a.M) {                         // whole waves
+    float *Ct = reinterpret_cast<float *>(gw_lds) + (size_t)wave * 32 * CT_PITCH;
     const int half = lane >> 5, r32 = lane & 31;
     #pragma unroll
-    for (int pr = 0; pr < NP; ++pr)
+    for (int t = 0; t < TW; ++t) {
+      if (t > 0) {                                         // the lanes are done reading the tile before
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      }
       #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int pr = 0; pr < NP; ++pr)
         #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
           const f32x4 v = {acc[pr][t][4 * q4], acc[pr][t][4 * q4 + 1], acc[pr][t][4 * q4 + 2], acc[pr][t][4 * q4 + 3]};
-          *reinterpret_cast<f32x4 *>(Ct + (t * 32 + r32) * CT_PITCH + pr * 32 + q4 * 8 + half * 4) = v;
+          *reinterpret_cast<f32x4 *>(Ct + r32 * CT_PITCH + pr * 32 + q4 * 8 + half * 4) = v;
         }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's LDS writes before its lanes read each other's
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, NB, m_base, split, nblk, lane, WAVE);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's LDS writes before its lanes read each other's
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      if (m_wave + t * 32 < a.M) gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, NB, m_wave + t * 32, split, nblk, lane, WAVE, 32);
+    }
   }
 }
 
@@ -669,26 +726,41 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   // 8.23 / 7.86, 6 blocks 12.44 / 11.07, 8 blocks 14.46 / 12.40; 33B shapes, 6 blocks: 59.1 / 47.4
   best.wide = gemm_is_wide(M, tiled);
   if (best.wide) {
-    // all activation rows in one workgroup (groups of at most GW_MAX_NW blocks of 64): a step costs the math waves
-    // 4 * nb matrix-core instructions and the chip nb weight fragments per workgroup
-    best.mgroups = (mblocks + GW_MAX_NW - 1) / GW_MAX_NW;
-    best.nw = (mblocks + best.mgroups - 1) / best.mgroups;
-    for (int s = 1; s <= 8; s *= 2) {
-      if (split_req > 0 && s != split_req) continue;
-      if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GW_STEPS))) continue;
-      for (int nb = 2; nb <= 2 * GW_MAX_NP; nb += 2) {      // blocks are taken in pairs
-        if (nb > std::max(blocks, 2)) break;
-        const int tiles = (blocks + nb - 1) / nb;
-        const long wgs = (long)tiles * s * best.mgroups;
-        const long rounds = (wgs + 255) / 256;
-        const double cost = (double)rounds * ((total_steps + s - 1) / s) * (nb + 2) + slab_units * (s - 1);
-        if (cost <= best_cost) { best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles; }
+    // A workgroup owns a group of tiles of 32 activation rows against nb weight row blocks.  Inside a group the
+    // tiles are dealt to math waves so that the four SIMDs carry the same matrix-core load: 2 tiles per wave, or 3
+    // per wave for 9 to 12 tiles (one wave per SIMD; six waves of two tiles kept two SIMDs twice as busy as the
+    // others), up to 8 waves of 2.  Two ways to form the groups are priced: as few groups as possible (up to 16
+    // tiles: the weights cross LDS once) or groups of at most 8 tiles (twice the workgroups: pays when the weight
+    // matrix has too few row blocks to fill the chip).  A workgroup's time goes with its steps, its nb + 2
+    // fragments per step and the tiles its busiest SIMD carries; ties go to the fewer groups.
+    const int mt = (M + 31) / 32;
+    for (int max_tiles = 8; max_tiles <= 16; max_tiles += 8) {          // (the later candidate wins ties)
+      const int mg = (mt + max_tiles - 1) / max_tiles;
+      const int gt = (mt + mg - 1) / mg;                                // tiles per group
+      const int tw = (gt > 2 * GW_MAX_NW3 && gt <= 3 * GW_MAX_NW3) ? 3 : 2;
+      const int nw = (gt + tw - 1) / tw;
+      const double simd_tiles = (double)((nw + 3) / 4) * tw;
+      for (int s = 1; s <= 8; s *= 2) {
+        if (split_req > 0 && s != split_req) continue;
+        if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GW_STEPS))) continue;
+        for (int nb = 2; nb <= 2 * GW_MAX_NP; nb += 2) {      // blocks are taken in pairs
+          if (nb > std::max(blocks, 2)) break;
+          const int tiles = (blocks + nb - 1) / nb;
+          const long wgs = (long)tiles * s * mg;
+          const long rounds = (wgs + 255) / 256;
+          const double cost = (double)rounds * ((total_steps + s - 1) / s) * (nb + 2) * (simd_tiles / 2) + slab_units * (s - 1);
+          if (cost <= best_cost) {
+            best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles;
+            best.mgroups = mg; best.nw = nw; best.tw = tw;
+          }
+        }
       }
     }
     return best;
   }
   best.mgroups = mblocks;
   best.nw = 1;
+  best.tw = 2;
   for (int s = 1; s <= 8; s *= 2) {
     if (split_req > 0 && s != split_req) continue;
     if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GM_STEPS))) continue;
@@ -708,30 +780,33 @@ bool gemm_is_wide(int M, bool tiled) { return tiled && (M + GM_BM - 1) / GM_BM >
 
 size_t gemm_xt_bytes(int M, int Kd, int elem_bytes) { return (size_t)((M + 31) / 32) * 32 * (size_t)Kd * elem_bytes; }
 
-template <typename T, int EPI, int NP>
+template <typename T, int EPI, int NP, int TW, int NWMAX>
 static hipError_t launch_wide_np(hipStream_t st, const GemmArgs &a, const GemmPlan &pl, int m32_tiles, dim3 grid, dim3 block,
                                  hipEvent_t ev_start, hipEvent_t ev_stop) {
   // the weight ring, or (afterwards, in the same memory) one float32 output tile of 64 rows per math wave
-  constexpr size_t ring = (size_t)GW_R * 2 * NP * GW_STEPS * 1024, ct_wave = (size_t)GM_BM * (32 * NP + 4) * 4;
-  constexpr size_t smem_max = ring > GW_MAX_NW * ct_wave ? ring : GW_MAX_NW * ct_wave;
+  constexpr size_t ring = (size_t)GW_R * 2 * NP * GW_STEPS * 1024, ct_wave = (size_t)32 * (32 * NP + 4) * 4;
+  constexpr size_t smem_max = ring > NWMAX * ct_wave ? ring : NWMAX * ct_wave;
   static_assert(smem_max <= 160 * 1024, "LDS of one workgroup");
   const size_t smem = std::max(ring, (size_t)pl.nw * ct_wave);
   static bool attr_set = false;                           // once per instantiation and process
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void *)k_gemm_wide<T, EPI, NP>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
+    hipError_t e = hipFuncSetAttribute((const void *)k_gemm_wide<T, EPI, NP, TW, NWMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_gemm_wide<T, EPI, NP>), grid, block, smem, st, ev_start, ev_stop, 0, a, pl.tiles, pl.mgroups, m32_tiles);
+    hipExtLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, ev_start, ev_stop, 0, a, pl.tiles, pl.mgroups, m32_tiles);
   else
-    hipLaunchKernelGGL((k_gemm_wide<T, EPI, NP>), grid, block, smem, st, a, pl.tiles, pl.mgroups, m32_tiles);
+    hipLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, a, pl.tiles, pl.mgroups, m32_tiles);
   return hipGetLastError();
 }
 
 template <typename T, int EPI>
 static hipError_t launch_wide(hipStream_t st, const GemmArgs &a, const GemmPlan &pl, hipEvent_t ev_start, hipEvent_t ev_stop) {
-  if (!a.wt || !a.xt || pl.nw < 1 || pl.nw > GW_MAX_NW || pl.nb < 2 || pl.nb > 2 * GW_MAX_NP || pl.nb % 2) return hipErrorInvalidValue;
+  if (!a.wt || !a.xt || pl.nw < 1 || pl.nw > (pl.tw == 3 ? GW_MAX_NW3 : GW_MAX_NW) || pl.tw < 2 || pl.tw > GW_MAX_TW || pl.nb < 2 ||
+      pl.nb > 2 * GW_MAX_NP || pl.nb % 2)
+    return hipErrorInvalidValue;
+  if ((long long)pl.mgroups * pl.nw * pl.tw * 32 < a.M) return hipErrorInvalidValue;     // the groups must cover every row
   const int m32_tiles = (a.M + 31) / 32, row_bytes = a.Kd * (int)sizeof(T);
   const size_t pieces = (size_t)(row_bytes / 32) * m32_tiles * 64;
   GemmArgs aw = a;
@@ -741,11 +816,16 @@ static hipError_t launch_wide(hipStream_t st, const GemmArgs &a, const GemmPlan 
   const long long wgs = (long long)((pl.tiles * a.split_k + 7) / 8) * pl.mgroups * 8;
   if (wgs > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)wgs), block(64 * (pl.nw + GW_NL));
+  #define GW_LAUNCH(NP_)                                                                                            \
+    return pl.tw == 3 ? launch_wide_np<T, EPI, NP_, 3, 4>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop)   \
+         : pl.nw > 4  ? launch_wide_np<T, EPI, NP_, 2, 8>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop)   \
+                      : launch_wide_np<T, EPI, NP_, 2, 4>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop)
   switch (pl.nb / 2) {
-    case 1: return launch_wide_np<T, EPI, 1>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
-    case 2: return launch_wide_np<T, EPI, 2>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
-    default: return launch_wide_np<T, EPI, 3>(st, aw, pl, m32_tiles, grid, block, ev_start, ev_stop);
+    case 1: GW_LAUNCH(1);
+    case 2: GW_LAUNCH(2);
+    default: GW_LAUNCH(3);
   }
+  #undef GW_LAUNCH
 }
 
 template <typename T>
