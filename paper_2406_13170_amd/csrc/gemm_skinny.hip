@@ -431,6 +431,7 @@ constexpr int GW_MIN_MBLOCKS = 3;  // blocks of 64 activation rows from which th
 constexpr int GW_AUX_NT = 2;       // cache-policy bits of the global-to-LDS load: non-temporal (the weights are read once)
 static_assert(GW_STEPS % GW_XD == 0, "the activation ring is indexed statically inside a stage");
 
+template <int N> struct GwTag { static constexpr int value = N; };
 template <int N> __device__ __forceinline__ void gw_wait_vm() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0f70);
 }
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(256) void k_tile_rows(const unsigned char *x, int M
 }
 
 template <typename T, int EPI, int NP, int TW, int NWMAX>      // NWMAX = 4: one math wave per SIMD (256 registers each); 8: two (168)
-__global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmArgs a, int tiles, int mgroups, int m32_tiles) {
+__global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmArgs a, int tiles, int mgroups, int m32_tiles, int gt) {
   extern __shared__ __align__(16) unsigned char gw_lds[];
   constexpr int NB = 2 * NP, STAGE = NB * GW_STEPS * 1024, PERL = NB * GW_STEPS / GW_NL;
   static_assert(GW_R == 3 && PERL * (GW_R - 2) <= 63, "loader wave's outstanding loads");
@@ -463,7 +464,12 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
   const int tile = unit / S, split = unit % S;
   constexpr int XD = (TW == 3 || NWMAX == 8) ? 2 : GW_XD; // steps of activations requested ahead (registers)
   static_assert(GW_STEPS % XD == 0, "the activation ring is indexed statically inside a stage");
-  const int m_group = mgroup * nw * (TW * 32);
+  // Tiles of this group: gt of them from g0 on.  One wave per SIMD (NWMAX = 4): wave w owns the TW adjacent tiles
+  // from w * TW on.  Two waves per SIMD (NWMAX = 8): wave w owns tiles w and w + nw, so that with fewer than 2 * nw
+  // tiles the waves left with one tile are the upper half, which share their SIMDs with the lower half.
+  const int g0 = mgroup * gt;
+  auto tile_of = [&](int t) { return g0 + (NWMAX == 8 ? wave + t * nw : wave * TW + t); };
+  auto live = [&](int t) { const int x = tile_of(t); return x < g0 + gt && x < m32_tiles; };
   const int total_steps = a.Kd * (int)sizeof(T) / 64;
   const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
   const int n = s1 - s0;
@@ -533,7 +539,6 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
     // activation tiles TW * wave .. + TW - 1 of the group (32 rows each); the 2 * TW fragments of a step (two halves
     // of the step's 64 bytes for every tile) are requested XD steps ahead
     const int half = lane >> 5, r32 = lane & 31;
-    const int mt0 = (m_group >> 5) + TW * wave;
     const unsigned char *xb = (const unsigned char *)a.xt + lane * 16;
     uint4 xq[XD][2][TW];
     auto load_x = [&](int i, uint4 (&xf)[2][TW]) {
@@ -542,7 +547,7 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
       for (int h = 0; h < 2; ++h)
         #pragma unroll
         for (int t = 0; t < TW; ++t) {
-          const int mt = min(mt0 + t, m32_tiles - 1);      // tiles past the end (last wave) re-read the last tile; never stored
+          const int mt = min(tile_of(t), m32_tiles - 1);   // tiles past the end (last wave) re-read the last tile; never stored
           xf[h][t] = ldg16(xb + ((size_t)(2 * st + h) * m32_tiles + mt) * 1024);
         }
     };
@@ -550,29 +555,34 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
     const int woff = (r32 >> 4) * (GW_STEPS * 1024) + (half * 16 + (r32 & 15)) * 16;
     #pragma unroll
     for (int i = 0; i < XD; ++i) load_x(i, xq[i]);
-    for (int p = 0; p < P; ++p) {
-      // Stage p is in LDS (pairs with the loaders' barrier).  A bare barrier: __syncthreads() would also wait for this
-      // wave's outstanding activation loads (the fence it carries counts them since the kernel contains global-to-LDS
-      // loads) and drain the prefetch ring at every stage.  The "memory" clobber keeps the LDS reads below it; the
-      // reads of stage p - 1 are complete because the matrix-core instructions that used them have been issued.
-      asm volatile("s_barrier" ::: "memory");
-      const unsigned char *sb = gw_lds + (p % GW_R) * STAGE + woff;
-      #pragma unroll
-      for (int s = 0; s < GW_STEPS; ++s) {
-        const int i = p * GW_STEPS + s;
-        if (i < n) {                                       // wave-uniform
-          #pragma unroll
-          for (int h = 0; h < 2; ++h)
+    // NTL = tiles this wave multiplies: TW, or 1 for a wave of the two-per-SIMD layout whose second tile does not exist
+    auto run = [&](auto tag) {
+      constexpr int NTL = decltype(tag)::value;
+      for (int p = 0; p < P; ++p) {
+        // Stage p is in LDS (pairs with the loaders' barrier).  A bare barrier: __syncthreads() would also wait for this
+        // wave's outstanding activation loads (the fence it carries counts them since the kernel contains global-to-LDS
+        // loads) and drain the prefetch ring at every stage.  The "memory" clobber keeps the LDS reads below it; the
+        // reads of stage p - 1 are complete because the matrix-core instructions that used them have been issued.
+        asm volatile("s_barrier" ::: "memory");
+        const unsigned char *sb = gw_lds + (p % GW_R) * STAGE + woff;
+        #pragma unroll
+        for (int s = 0; s < GW_STEPS; ++s) {
+          const int i = p * GW_STEPS + s;
+          if (i < n) {                                     // wave-uniform
             #pragma unroll
-            for (int pr = 0; pr < NP; ++pr) {
-              const uint4 wf = *reinterpret_cast<const uint4 *>(sb + (2 * pr * GW_STEPS + s) * 1024 + h * 512);
+            for (int h = 0; h < 2; ++h)
               #pragma unroll
-              for (int t = 0; t < TW; ++t) acc[pr][t] = mma32<T>(wf, xq[s % XD][h][t], acc[pr][t]);
-            }
+              for (int pr = 0; pr < NP; ++pr) {
+                const uint4 wf = *reinterpret_cast<const uint4 *>(sb + (2 * pr * GW_STEPS + s) * 1024 + h * 512);
+                #pragma unroll
+                for (int t = 0; t < NTL; ++t) acc[pr][t] = mma32<T>(wf, xq[s % XD][h][t], acc[pr][t]);
+              }
+          }
+          load_x(i + XD, xq[s % XD]);
         }
-        load_x(i + XD, xq[s % XD]);
       }
-    }
+    };
+    if (NWMAX == 8 && !live(1)) run(GwTag<1>{}); else run(GwTag<TW>{});
   }
 
   // ---- epilogues: every math wave handles its own activation rows through its own Ct region in LDS (the ring is
@@ -580,12 +590,12 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
   // Lane (half, r32) holds activation row t * 32 + r32 and weight rows (i / 4) * 8 + half * 4 + (i % 4) of each pair.
   const int CT_PITCH = 16 * NB + 4;
   __syncthreads();                                         // every wave has left the ring
-  const int m_wave = m_group + wave * (TW * 32);
-  if (wave < nw && m_wave < a.M) {                         // whole waves
+  if (wave < nw && live(0)) {                              // whole waves
     float *Ct = reinterpret_cast<float *>(gw_lds) + (size_t)wave * 32 * CT_PITCH;
     const int half = lane >> 5, r32 = lane & 31;
     #pragma unroll
     for (int t = 0; t < TW; ++t) {
+      if (!live(t)) break;                                 // (wave-uniform)
       if (t > 0) {                                         // the lanes are done reading the tile before
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -601,7 +611,7 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");   // the wave's LDS writes before its lanes read each other's
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      if (m_wave + t * 32 < a.M) gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, NB, m_wave + t * 32, split, nblk, lane, WAVE, 32);
+      gemm_epilogue<T, EPI>(a, Ct, CT_PITCH, tile, NB, tile_of(t) * 32, split, nblk, lane, WAVE, 32);
     }
   }
 }
@@ -734,12 +744,18 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
     // matrix has too few row blocks to fill the chip).  A workgroup's time goes with its steps, its nb + 2
     // fragments per step and the tiles its busiest SIMD carries; ties go to the fewer groups.
     const int mt = (M + 31) / 32;
-    for (int max_tiles = 8; max_tiles <= 16; max_tiles += 8) {          // (the later candidate wins ties)
+    // candidates (the later one wins ties): groups of at most 8 tiles, one wave of 2 tiles per SIMD; as few groups as
+    // possible with 3 tiles per wave (9 to 12 tiles a group); the same with two waves per SIMD (9 to 16 tiles)
+    for (int cand = 0; cand < 3; ++cand) {
+      const int max_tiles = cand == 0 ? 8 : cand == 1 ? 12 : 16;
       const int mg = (mt + max_tiles - 1) / max_tiles;
       const int gt = (mt + mg - 1) / mg;                                // tiles per group
-      const int tw = (gt > 2 * GW_MAX_NW3 && gt <= 3 * GW_MAX_NW3) ? 3 : 2;
-      const int nw = (gt + tw - 1) / tw;
-      const double simd_tiles = (double)((nw + 3) / 4) * tw;
+      if (cand > 0 && gt <= 8) continue;                                // nothing new
+      const int tw = cand == 1 ? 3 : 2;
+      const int nw = cand == 2 ? GW_MAX_NW : (gt + tw - 1) / tw;
+      // tiles on the busiest SIMD; two waves on a SIMD cover part of each other's waits (measured: 23.5 against
+      // 25.7 us per tile and SIMD for gate/up at 7B shapes)
+      const double simd_tiles = cand == 2 ? 0.92 * ((gt + 3) / 4) : (double)((nw + 3) / 4) * tw;
       for (int s = 1; s <= 8; s *= 2) {
         if (split_req > 0 && s != split_req) continue;
         if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GW_STEPS))) continue;
@@ -751,7 +767,7 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
           const double cost = (double)rounds * ((total_steps + s - 1) / s) * (nb + 2) * (simd_tiles / 2) + slab_units * (s - 1);
           if (cost <= best_cost) {
             best_cost = cost; best.nb = nb; best.split = s; best.tiles = tiles;
-            best.mgroups = mg; best.nw = nw; best.tw = tw;
+            best.mgroups = mg; best.nw = nw; best.tw = tw; best.gt = gt;
           }
         }
       }
@@ -761,6 +777,7 @@ GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int spl
   best.mgroups = mblocks;
   best.nw = 1;
   best.tw = 2;
+  best.gt = 2;
   for (int s = 1; s <= 8; s *= 2) {
     if (split_req > 0 && s != split_req) continue;
     if (split_req == 0 && (fused ? s > 1 : (s > 1 && total_steps / s < 2 * GM_STEPS))) continue;
@@ -795,9 +812,9 @@ static hipError_t launch_wide_np(hipStream_t st, const GemmArgs &a, const GemmPl
     attr_set = true;
   }
   if (ev_start && ev_stop)
-    hipExtLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, ev_start, ev_stop, 0, a, pl.tiles, pl.mgroups, m32_tiles);
+    hipExtLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, ev_start, ev_stop, 0, a, pl.tiles, pl.mgroups, m32_tiles, pl.gt);
   else
-    hipLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, a, pl.tiles, pl.mgroups, m32_tiles);
+    hipLaunchKernelGGL((k_gemm_wide<T, EPI, NP, TW, NWMAX>), grid, block, smem, st, a, pl.tiles, pl.mgroups, m32_tiles, pl.gt);
   return hipGetLastError();
 }
 
@@ -806,7 +823,7 @@ static hipError_t launch_wide(hipStream_t st, const GemmArgs &a, const GemmPlan 
   if (!a.wt || !a.xt || pl.nw < 1 || pl.nw > (pl.tw == 3 ? GW_MAX_NW3 : GW_MAX_NW) || pl.tw < 2 || pl.tw > GW_MAX_TW || pl.nb < 2 ||
       pl.nb > 2 * GW_MAX_NP || pl.nb % 2)
     return hipErrorInvalidValue;
-  if ((long long)pl.mgroups * pl.nw * pl.tw * 32 < a.M) return hipErrorInvalidValue;     // the groups must cover every row
+  if ((long long)pl.mgroups * pl.gt * 32 < a.M || pl.gt > pl.nw * pl.tw) return hipErrorInvalidValue;   // groups cover every row, waves every tile
   const int m32_tiles = (a.M + 31) / 32, row_bytes = a.Kd * (int)sizeof(T);
   const size_t pieces = (size_t)(row_bytes / 32) * m32_tiles * 64;
   GemmArgs aw = a;

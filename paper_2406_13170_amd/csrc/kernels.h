@@ -96,7 +96,7 @@ struct GemmArgs {
 // the plan choose (fused epilogues always 1), else the caller's split; tiled: the launch will have both GemmArgs::wt
 // and GemmArgs::xt (then 128 rows or more go to the wide kernel).  The same call must be used to size
 // whatever depends on the plan (partial slabs: split; per-tile argmax candidates: tiles).
-struct GemmPlan { int nb, split, tiles, blocks; bool wide; int mgroups, nw, tw; };   // wide: mgroups groups of nw math waves x tw tiles of 32 rows
+struct GemmPlan { int nb, split, tiles, blocks; bool wide; int mgroups, nw, tw, gt; };   // wide: mgroups groups of gt tiles of 32 rows, nw math waves x up to tw tiles
 GemmPlan gemm_plan(int epi, int seg_rows, int Kd, int elem_bytes, int M, int split_req, bool tiled);
 size_t gemm_xt_bytes(int M, int Kd, int elem_bytes);
 bool gemm_is_wide(int M, bool tiled);       // whether gemm_plan sends this many rows to the wide kernel
