@@ -315,16 +315,19 @@ def test_target_forward_batch_two():
 
 @pytest.mark.parametrize("cfg,n_layers,T,caps,L,Bsz", [
     (si.MINI, 2, 64, (10,) * 4, 100, 2),           # M = 128: two blocks of 64 rows, still the skinny kernel
-    (si.MINI, 2, 64, (10,) * 4, 90, 3),            # M = 192: three blocks, the smallest case of the wide kernel
-    (si.MINI, 2, 64, (10,) * 4, 77, 5),            # M = 320: five blocks in one workgroup of the wide kernel
-    (si.MINI, 1, 35, (10,) * 4, 61, 10),           # M = 350: ragged last block and last 32-row tile
-    (si.MINI, 1, 64, (10,) * 4, 40, 7),            # M = 448: two groups of rows (4 + 3 blocks)
-    (si.TINY, 2, 64, (10,) * 4, 5, 6),             # float32, M = 384: six blocks
+    (si.MINI, 2, 64, (10,) * 4, 90, 3),            # M = 192: 6 tiles of 32 rows, the smallest case of the wide kernel
+    (si.MINI, 2, 64, (10,) * 4, 77, 5),            # M = 320: 10 tiles, two math waves per SIMD, two of them with 2 tiles
+    (si.MINI, 1, 35, (10,) * 4, 61, 10),           # M = 350: 11 tiles, the last one ragged
+    (si.MINI, 1, 64, (10,) * 4, 40, 7),            # M = 448: 14 tiles in one group
+    (si.TINY, 2, 64, (10,) * 4, 5, 6),             # float32, M = 384: 12 tiles
+    (si.MINI, 1, 96, (10,) * 5, 30, 3),            # M = 288: 9 tiles, only the first wave has two
+    (si.MINI, 1, 64, (10,) * 4, 20, 8),            # M = 512: 16 tiles, every wave two
+    (si.MINI, 1, 64, (10,) * 4, 12, 9),            # M = 576: 18 tiles, two groups of 9
 ])
 def test_target_forward_batches_on_tiled_weights(cfg, n_layers, T, caps, L, Bsz):
-    """Three blocks of 64 activation rows or more with tiled weights take the wide GEMM (all rows of a weight tile in
-    one workgroup, 32 x 32 matrix-core tiles); the same inputs with row-major weights take the skinny one.  Both
-    against the oracle."""
+    """Three blocks of 64 activation rows or more with tiled weights take the wide GEMM (groups of up to 16 tiles of 32
+    rows of a weight tile in one workgroup, 32 x 32 matrix-core tiles, one or two math waves per SIMD); the same inputs
+    with row-major weights take the skinny one.  Both against the oracle."""
     say(f"target_forward {cfg.name} layers={n_layers} T={T} L={L} batch={Bsz} (M = {T * Bsz}), tiled weights")
     cfgx, refs, got, _ = run_target(cfg, n_layers, T, caps, L, Bsz=Bsz, tiled=True)
     check_target(cfgx, refs, got)
