@@ -1,6 +1,6 @@
 // GEMMs of the target's forward pass over the tree tokens (Sec. 2 "Tree Attention"): M = B*T activation rows
 // against [N, Kd] weights that stream from HBM once, on the matrix cores.  Two kernels: the skinny one
-// (described first; up to four blocks of 64 rows) and the wide one (further down; five blocks or more).
+// (described first; up to two blocks of 64 rows) and the wide one (further down; three blocks or more).
 //
 // The unit of work is a ROW BLOCK: 16 weight rows that one wave keeps as matrix-core A fragments and
 // whose outputs need nothing from any other block:
@@ -403,14 +403,16 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
 // Wide GEMM: 128 or more activation rows (batches of trees).  The skinny kernel above re-reads the weights
 // from L2 once per block of 64 rows, every math wave re-reads the whole activation chunk from LDS, and its
 // 16 x 16 matrix-core instruction runs at half the rate of the 32 x 32 one: with several blocks of rows L2, LDS
-// and the matrix cores, not HBM, set the pace.  Here a workgroup owns ALL activation rows (up to 384) of NB weight
-// row blocks, and the roles of the operands are swapped:
+// and the matrix cores, not HBM, set the pace.  Here a workgroup owns a group of up to 16 tiles of 32 activation
+// rows (all rows, up to 512; more rows form several groups) against NB weight row blocks, and the roles of the
+// operands are swapped:
 //   * the weights are the shared operand: two loader waves stream the workgroup's NB blocks from HBM straight
 //     into a ring of LDS stages (global-to-LDS loads, 8 steps of 64 bytes of k per stage), so they cross L2 once;
-//   * each math wave owns 64 activation rows (two 32-row tiles) against all NB blocks, taken in pairs (32 weight
-//     rows): per step and half-step it reads one weight fragment per pair from LDS and 2 activation fragments from
-//     global memory (L2 hits, requested GW_XD steps ahead into registers) and issues 2 matrix-core instructions
-//     of 32 x 32 per pair; one barrier per 8 steps.
+//   * each math wave owns 2 (or 3) of the group's tiles against all NB blocks, taken in pairs (32 weight rows): per
+//     step and half-step it reads one weight fragment per pair from LDS and one activation fragment per tile from
+//     global memory (L2 hits, requested 2 or 4 steps ahead into registers) and issues one matrix-core instruction
+//     of 32 x 32 per pair and tile; one barrier per 8 steps.  Up to 8 tiles there is one math wave per SIMD (2
+//     adjacent tiles each); from 9 tiles on two per SIMD, wave w owning tiles w and w + 8.
 // A 32 x 32 instruction takes, per lane (half, r), 16 bytes of row r: the bytes [half * 16, half * 16 + 16) of
 // 32 bytes of k.  The weight fragments in LDS are the 16-row x 64-byte ones of the tiled layout, piece (g, r16)
 // at (g * 16 + r16) * 16: lane (half, r) of half-step h reads piece (2h + half, r % 16) of block r / 16 of the
