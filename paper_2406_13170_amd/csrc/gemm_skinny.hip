@@ -129,7 +129,10 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
       }
     }
   } else if (EPI == EPI_QKV_ROPE) {
-    const int d_h = a.d_h, d = a.n_heads * d_h, bps = d / 16, bph = d_h / 16, half = d_h / 2;
+    // d_h is a power of two (checked at launch): heads and dims come from shifts; the segment of a block (q, k or v:
+    // bps blocks each) from two comparisons instead of a division by a run-time value
+    const int d_h = a.d_h, d = a.n_heads * d_h, bps = d >> 4, bph = d_h >> 4, bsh = __ffs(bph) - 1, half = d_h >> 1;
+    auto seg_of = [&](int b) { return (b >= 2 * bps) ? 2 : (b >= bps) ? 1 : 0; };
     // q and k blocks: one (block, token) per thread = 8 rotation pairs.  Everything the item needs from global
     // memory (64 bytes of the cos/sin table, the committed length) is requested first, for up to QK_U items of the
     // thread at once: a wave of the wide kernel walks several items, and stores in between would keep the next item's
@@ -142,8 +145,8 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
       #pragma unroll
       for (int u = 0; u < QK_U; ++u) {
         const int idx = base + u * NT, w = idx / rows, m = idx % rows, b = tile * nb + w, mg = m_base + m;
-        const bool live = idx < nb * rows && b < nblk && mg < a.M && b / bps < 2;
-        const int e0 = ((b % bps) % bph) * 8;
+        const bool live = idx < nb * rows && b < nblk && mg < a.M && seg_of(b) < 2;
+        const int e0 = ((b - seg_of(b) * bps) & (bph - 1)) * 8;
         // (unconditional loads from clamped addresses: dead items read the table's first entry and element 0's length)
         const float4 *csp = reinterpret_cast<const float4 *>(a.rope_cs + (live ? (size_t)mg * half + e0 : (size_t)0));
         #pragma unroll
@@ -154,9 +157,9 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
       for (int u = 0; u < QK_U; ++u) {
         const int idx = base + u * NT, w = idx / rows, m = idx % rows, b = tile * nb + w, mg = m_base + m;
         if (idx >= nb * rows || b >= nblk || mg >= a.M) continue;
-        const int seg = b / bps, bl = b % bps;
+        const int seg = seg_of(b), bl = b - seg * bps;
         if (seg >= 2) continue;
-        const int head = bl / bph, e0 = (bl % bph) * 8;
+        const int head = bl >> bsh, e0 = (bl & (bph - 1)) * 8;
         const float4 c01 = tab[u][0], c23 = tab[u][1], c45 = tab[u][2], c67 = tab[u][3];
         const float cs[8] = {c01.x, c01.z, c23.x, c23.z, c45.x, c45.z, c67.x, c67.z};
         const float sn[8] = {c01.y, c01.w, c23.y, c23.w, c45.y, c45.w, c67.y, c67.w};
@@ -198,11 +201,11 @@ __device__ __forceinline__ void gemm_epilogue(const GemmArgs &a, const float *Ct
         for (int q = tid / rows; q < nb * 8; q += NT / rows) {
           const int w = q >> 3, j = q & 7, b = tile * nb + w;
           if (b >= nblk) continue;
-          const int seg = b / bps, bl = b % bps;
+          const int seg = seg_of(b), bl = b - seg * bps;
           if (seg < 2) continue;
           #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
-            const int n = bl * 16 + j + 8 * hh, head = n / d_h, e = n % d_h;
+            const int head = bl >> bsh, e = ((bl & (bph - 1)) << 4) + j + 8 * hh;
             T *vc = (T *)a.v_cache + ((size_t)bb * a.n_heads + head) * (size_t)a.max_kv * d_h;
             vc[v_tiled_index<T>(L + node, e, d_h)] = Elem<T>::from_f32(Ct[m * CT_PITCH + w * 16 + j + 8 * hh]);
           }
@@ -853,7 +856,7 @@ hipError_t launch_gemm(hipStream_t st, int epi, const GemmArgs &a_in, hipEvent_t
   if (a.M < 1 || a.Kd < 1 || (a.Kd * (int)sizeof(T)) % 64) return hipErrorInvalidValue;
   if (a.split_k != 1 && a.split_k != 2 && a.split_k != 4 && a.split_k != 8) return hipErrorInvalidValue;
   if (epi != EPI_STORE && a.split_k != 1) return hipErrorInvalidValue;     // fused epilogues need complete sums
-  if (epi == EPI_QKV_ROPE && (a.d_h % 16 || a.seg_rows != a.n_heads * a.d_h || !a.rope_cs)) return hipErrorInvalidValue;
+  if (epi == EPI_QKV_ROPE && (a.d_h < 16 || (a.d_h & (a.d_h - 1)) || a.seg_rows != a.n_heads * a.d_h || !a.rope_cs)) return hipErrorInvalidValue;
   const GemmPlan pl = gemm_plan(epi, a.seg_rows, a.Kd, (int)sizeof(T), a.M, a.split_k, a.wt != nullptr && a.xt != nullptr);
   a.nb = pl.nb;
   if (!pl.wide && (a.x_tiled || a.act_tiles)) return hipErrorInvalidValue;   // only the wide kernel knows the tiled activations
