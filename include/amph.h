@@ -50,7 +50,7 @@ typedef struct amph_config {
   int32_t K;                 /* drafting heads, 1..AMPH_MAX_HEADS_K                                */
   int32_t topk;              /* per-head candidates, 1..AMPH_MAX_TOPK                              */
   int32_t max_tree;          /* largest tree (nodes incl. root) used with this context, <= 128     */
-  int32_t max_kv;            /* rows of every KV cache; multiple of 32                             */
+  int32_t max_kv;            /* rows of every KV cache; multiple of 32, at most 2^24               */
   int32_t batch;             /* independent sequences per call                                     */
   int32_t dtype;             /* AMPH_F32 | AMPH_BF16                                               */
   float rms_eps;             /* RMSNorm epsilon                                                    */

@@ -342,7 +342,7 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
   if (c.d_model != c.n_heads * c.head_dim) return AMPH_ESHAPE;
   if (c.d_model % 64 || c.d_ffn % 16 || (c.dtype == AMPH_BF16 && c.d_ffn % 32)) return AMPH_ESHAPE;
   if (c.K > AMPH_MAX_HEADS_K || c.topk > AMPH_MAX_TOPK || c.topk > c.vocab || c.max_tree > AMPH_MAX_TREE) return AMPH_ESHAPE;
-  if (c.max_kv % 32 || c.max_kv < c.max_tree) return AMPH_ESHAPE;
+  if (c.max_kv % 32 || c.max_kv < c.max_tree || c.max_kv > (1 << 24)) return AMPH_ESHAPE;   // (kernels index key steps in 32 bits)
   if (c.vocab > 65536 || c.batch > 64 || (long long)c.batch * c.n_heads > 1000) return AMPH_ESHAPE;
   if ((c.n_stages != 1 && c.n_stages != 2) || (c.aeb_layers != 1 && c.aeb_layers != 2)) return AMPH_EINVAL;
   if (c.lm_rank < 0 || c.lm_rank % 8 || c.lm_rank > c.d_model) return AMPH_ESHAPE;

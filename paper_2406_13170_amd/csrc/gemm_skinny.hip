@@ -259,7 +259,8 @@ __global__ __launch_bounds__(64 * (GM_MAX_NB + GM_NLW)) void k_gemm_skinny(const
   const int m_base = mblock * GM_BM;
   const int row_bytes = a.Kd * (int)sizeof(T);
   const int total_steps = row_bytes / 64;
-  const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
+  const int ssh = __ffs(S) - 1;                           // S is 1, 2, 4 or 8
+  const int s0 = (total_steps * split) >> ssh, s1 = (total_steps * (split + 1)) >> ssh;
   const int nch = (s1 - s0 + GM_STEPS - 1) / GM_STEPS;
   const int nblk = gemm_blocks(EPI, a.seg_rows);
   // Both roles run the same number of iterations (a multiple of two, the depth of every ring) with
@@ -476,7 +477,8 @@ __global__ __launch_bounds__(64 * (NWMAX + GW_NL)) void k_gemm_wide(const GemmAr
   auto tile_of = [&](int t) { return g0 + (NWMAX == 8 ? wave + t * nw : wave * TW + t); };
   auto live = [&](int t) { const int x = tile_of(t); return x < g0 + gt && x < m32_tiles; };
   const int total_steps = a.Kd * (int)sizeof(T) / 64;
-  const int s0 = (int)((long long)total_steps * split / S), s1 = (int)((long long)total_steps * (split + 1) / S);
+  const int ssh = __ffs(S) - 1;                           // S is 1, 2, 4 or 8
+  const int s0 = (total_steps * split) >> ssh, s1 = (total_steps * (split + 1)) >> ssh;
   const int n = s1 - s0;
   const int P = (n + GW_STEPS - 1) / GW_STEPS;             // weight stages
   const int nblk = gemm_blocks(EPI, a.seg_rows);

@@ -71,7 +71,8 @@ __global__ __launch_bounds__(256) void k_verify_attn_regs(const VerifyArgs a, in
   }
   const int n_keys = L + Tn;
   const int n_steps = (n_keys + KSTEP - 1) / KSTEP;
-  const int st0 = (int)((long long)n_steps * split / S), st1 = (int)((long long)n_steps * (split + 1) / S);
+  // (32-bit: key steps x splits stay far below 2^31; a 64-bit division costs a few hundred instructions up front)
+  const int st0 = (int)((unsigned)(n_steps * split) / (unsigned)S), st1 = (int)((unsigned)(n_steps * (split + 1)) / (unsigned)S);
   const float scale = 1.4426950408889634f * rsqrtf((float)DH);
   const float NEG_INF = -__builtin_huge_valf();
 
@@ -332,7 +333,8 @@ __global__ __launch_bounds__(KG == 2 ? 1024 : (VA_MAX_MATH + 2) * 64) void k_ver
   }
   const int n_keys = L + Tn;
   const int n_steps = (n_keys + KSTEP - 1) / KSTEP;
-  const int st0 = (int)((long long)n_steps * split / S), st1 = (int)((long long)n_steps * (split + 1) / S);
+  // (32-bit: key steps x splits stay far below 2^31; a 64-bit division costs a few hundred instructions up front)
+  const int st0 = (int)((unsigned)(n_steps * split) / (unsigned)S), st1 = (int)((unsigned)(n_steps * (split + 1)) / (unsigned)S);
   const int n = st1 - st0;                           // key steps of this workgroup; may be 0
   const int n_stages = (n + NS - 1) / NS;            // ring stages: NS steps each, the last one possibly ragged
   const size_t head_bytes = ((size_t)b * n_h + h) * (size_t)max_kv * DH * sizeof(T);
