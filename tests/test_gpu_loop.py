@@ -116,16 +116,12 @@ def test_draft_catches_up_over_new_positions(cfg, n_rows, n_live):
 
 
 # ---------------------------------------------------------------------------- the generator
-def test_generator_matches_oracle_and_autoregressive_greedy():
-    """Eight steps of the whole loop on the device, float32 configuration.  The draft module is untrained,
-    so the vocabulary is cut to 8 tokens (top-4 candidates per head) to make acceptances happen by chance:
-    with this seed the oracle's generator accepts 1, 0, 0, 1, 1, 1, 2, 1 draft tokens, and every decision
-    of the target and every top-4 boundary of the draft has a margin above 2e-2 (float32 error: ~1e-5).
-    Every step's tree, accepted path and next token must equal the oracle generator's, and the emitted
-    tokens are the target's own greedy continuation."""
-    say("generator tiny (vocabulary 8), 8 steps")
+def generator_state(n_steps_max=8):
+    """Weights scaled so that decisions have margins, a vocabulary of 8 tokens (top-4 candidates per head) so that an
+    untrained draft is accepted by chance, a random prompt, and the device state after the prompt: the target's caches
+    from the oracle's causal pass, empty adaptation-layer caches, the inputs of the first draft."""
     cfg = si.with_(si.TINY, kv_len=5, sal_len=0, vocab=8)
-    seed, scale, n_steps = 8, 6.0, 8
+    seed, scale = 8, 6.0
     n_h, d_h, d, V, K, T = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab, cfg.K, cfg.T
     f = lambda t: (t.f32 * np.float32(scale)).astype(np.float32)
     dw_t, tw_t = si.draft_weights(cfg, seed), si.target_weights(cfg, seed)
@@ -139,20 +135,10 @@ def test_generator_matches_oracle_and_autoregressive_greedy():
     otree = orc.tree_from_paths(paths, K)
     rng = np.random.default_rng(3)
     prompt = [int(t) for t in rng.integers(0, V, size=K + 2)]           # K + 1 prompt positions feed the first draft
-    emitted, recs = orc.generate(dw, tw, otree, prompt, n_steps, n_h, cfg.topk, cfg.rms_eps, cfg.rope_theta)
     P = len(prompt) - 1
-    ar = list(prompt)
-    for _ in range(len(emitted)):                                          # autoregressive greedy, full recompute
-        S = len(ar)
-        t = orc.target_forward(tw, np.asarray(ar), np.arange(S), np.tril(np.ones((S, S), dtype=bool)),
-                               [np.zeros((n_h, 0, d_h))] * len(tw["layers"]), [np.zeros((n_h, 0, d_h))] * len(tw["layers"]),
-                               n_h, cfg.rms_eps, cfg.rope_theta)
-        ar.append(int(t["tgt"][-1]))
-    assert emitted == ar[len(prompt):]
-
-    # ---- device state: weights, the prompt's target caches (from the oracle's causal pass), empty adaptation-layer caches
     n_layers = len(tw["layers"])
-    max_kv = (P + sum(r["accept_len"] + 1 for r in recs) + T + 31) // 32 * 32
+    max_kv = (P + n_steps_max * (K + 1) + T + 31) // 32 * 32
+    # ---- device state: weights, the prompt's target caches (from the oracle's causal pass), empty adaptation-layer caches
     ctx = make_ctx(cfg, max_kv=max_kv)
     to = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
     lay = lambda lw: {k: to(v) for k, v in lw.items()}
@@ -184,6 +170,40 @@ def test_generator_matches_oracle_and_autoregressive_greedy():
     tree_tok, tree_pos, tgt = i32(1, T), i32(1, T), i32(1, T)
     hidden = torch.zeros((1, T, d), dtype=torch.float32, device=DEV)
     a_len, a_path, nxt, best = i32(1), i32(1, K + 1), i32(1), i32(1)
+    return dict(cfg=cfg, dw=dw, tw=tw, otree=otree, prompt=prompt, P=P, n_layers=n_layers, ctx=ctx, dstruct=dstruct, dwd=dwd,
+                structs=structs, fn_d=fn_d, lm_d=lm_d, tree=tree, k_caches=k_caches, v_caches=v_caches, sal_kv=sal_kv,
+                kv_len=kv_len, sal_len=sal_len, h_new=h_new, tok_new=tok_new, n_new=n_new, root=root, topk_idx=topk_idx,
+                topk_val=topk_val, tree_tok=tree_tok, tree_pos=tree_pos, tgt=tgt, hidden=hidden, a_len=a_len, a_path=a_path,
+                nxt=nxt, best=best)
+
+
+def test_generator_matches_oracle_and_autoregressive_greedy():
+    """Eight steps of the whole loop on the device, float32 configuration.  The draft module is untrained,
+    so the vocabulary is cut to 8 tokens (top-4 candidates per head) to make acceptances happen by chance:
+    with this seed the oracle's generator accepts 1, 0, 0, 1, 1, 1, 2, 1 draft tokens, and every decision
+    of the target and every top-4 boundary of the draft has a margin above 2e-2 (float32 error: ~1e-5).
+    Every step's tree, accepted path and next token must equal the oracle generator's, and the emitted
+    tokens are the target's own greedy continuation."""
+    say("generator tiny (vocabulary 8), 8 steps")
+    n_steps = 8
+    st = generator_state(n_steps)
+    cfg, dw, tw, otree, prompt, P, n_layers = st["cfg"], st["dw"], st["tw"], st["otree"], st["prompt"], st["P"], st["n_layers"]
+    n_h, d_h, K, T = cfg.n_heads, cfg.head_dim, cfg.K, cfg.T
+    ctx, dstruct, dwd, structs, fn_d, lm_d, tree = st["ctx"], st["dstruct"], st["dwd"], st["structs"], st["fn_d"], st["lm_d"], st["tree"]
+    k_caches, v_caches, sal_kv, kv_len, sal_len = st["k_caches"], st["v_caches"], st["sal_kv"], st["kv_len"], st["sal_len"]
+    h_new, tok_new, n_new, root = st["h_new"], st["tok_new"], st["n_new"], st["root"]
+    topk_idx, topk_val, tree_tok, tree_pos, tgt, hidden = st["topk_idx"], st["topk_val"], st["tree_tok"], st["tree_pos"], st["tgt"], st["hidden"]
+    a_len, a_path, nxt, best = st["a_len"], st["a_path"], st["nxt"], st["best"]
+    emitted, recs = orc.generate(dw, tw, otree, prompt, n_steps, n_h, cfg.topk, cfg.rms_eps, cfg.rope_theta)
+    ar = list(prompt)
+    for _ in range(len(emitted)):                                          # autoregressive greedy, full recompute
+        S = len(ar)
+        t = orc.target_forward(tw, np.asarray(ar), np.arange(S), np.tril(np.ones((S, S), dtype=bool)),
+                               [np.zeros((n_h, 0, d_h))] * len(tw["layers"]), [np.zeros((n_h, 0, d_h))] * len(tw["layers"]),
+                               n_h, cfg.rms_eps, cfg.rope_theta)
+        ar.append(int(t["tgt"][-1]))
+    assert emitted == ar[len(prompt):]
+
     got_emitted = []
     for step, r in enumerate(recs):
         ctx.amph_draft(dstruct, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, None, n_new=K + 1, n_valid=n_new)

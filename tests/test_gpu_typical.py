@@ -214,3 +214,54 @@ def test_accept_typical_on_the_target_forward_logits():
             assert (int(a_len[b]), int(best[b])) == (oa, obest)
             np.testing.assert_array_equal(np_of(a_path)[b], opath)
         say(f"  delta={delta}: accept lengths {list(np_of(a_len))}")
+
+
+def test_generator_with_typical_acceptance():
+    """Six steps of the whole loop on the device (draft, tree, target pass, acceptance under sampling, commit, catch-up),
+    float32 Tiny configuration with a vocabulary of 8.  There is no oracle generator for this rule (it is not
+    lossless, so no autoregressive sequence pins it); each step's decision is checked by giving the oracle's rule the
+    device's own float32 logits and tree tokens, and the chain around it by its bookkeeping: the committed length grows
+    by the accepted tokens plus one, the adaptation layers have seen every position before the step, the next root is
+    the drawn token."""
+    from test_gpu_loop import generator_state
+    n_steps = 6
+    st = generator_state(n_steps)
+    cfg, otree, P, n_layers = st["cfg"], st["otree"], st["P"], st["n_layers"]
+    K, T, V = cfg.K, cfg.T, cfg.vocab
+    ctx, tree = st["ctx"], st["tree"]
+    logits = torch.zeros((1, T, V), dtype=torch.float32, device=DEV)
+    rng = np.random.default_rng(12)
+    us = rng.random(n_steps).astype(np.float32)
+    temp, eps, delta = 0.7, 0.09, 0.3
+    committed, lens = P, []
+    for step in range(n_steps):
+        ctx.amph_draft(st["dstruct"], st["h_new"], st["tok_new"], st["sal_kv"], st["sal_len"], st["topk_idx"], st["topk_val"], None,
+                       n_new=K + 1, n_valid=st["n_new"])
+        ctx.amph_tree_build(tree, st["root"], st["topk_idx"], st["kv_len"], st["tree_tok"], st["tree_pos"])
+        ctx.amph_target_forward(tree, st["structs"], st["dwd"]["embed"], st["fn_d"], st["lm_d"], st["tree_tok"], st["tree_pos"],
+                                st["k_caches"], st["v_caches"], st["kv_len"], st["hidden"], logits, st["tgt"])
+        ctx.amph_accept_typical(tree, st["tree_tok"], logits, temp, eps, delta, f32_to_dev(us[step:step + 1]), st["a_len"],
+                                st["a_path"], st["nxt"], st["best"])
+        tt, lg = np_of(st["tree_tok"])[0], np_of(logits)[0]
+        al, ap, nx, bn = int(np_of(st["a_len"])[0]), np_of(st["a_path"])[0], int(np_of(st["nxt"])[0]), int(np_of(st["best"])[0])
+        ctx.amph_commit(tree, n_layers, st["k_caches"], st["v_caches"], st["kv_len"], st["a_len"], st["a_path"], st["nxt"],
+                        st["tree_tok"], st["hidden"], st["h_new"], st["tok_new"], st["n_new"])
+        st["root"].copy_(st["nxt"])
+        torch.cuda.synchronize()
+        assert ctx.device_status() == 0
+        oa, opath, onxt, obest, margin, held = orc.accept_typical(otree, tt, lg, temp, eps, delta, float(us[step]))
+        near = [i for i in range(1, T) if abs(margin[i]) <= REL_TIE * held[i]]
+        assert not near, f"step {step}: nodes {near} are near ties; pick another seed"
+        assert (al, bn) == (oa, obest), f"step {step}"
+        np.testing.assert_array_equal(ap, opath)
+        if nx != onxt:
+            p = orc.softmax(lg[obest].astype(np.float64) / temp)
+            cdf = np.cumsum(p)
+            lo = cdf[nx - 1] if nx > 0 else 0.0
+            assert p[nx] > 0 and lo - CDF_TOL <= us[step] < cdf[nx] + CDF_TOL
+        assert int(np_of(st["kv_len"])[0]) == committed + al + 1 and int(np_of(st["sal_len"])[0]) == committed
+        assert int(np_of(st["n_new"])[0]) == al + 1 and int(np_of(st["root"])[0]) == nx
+        committed += al + 1
+        lens.append(al)
+        say(f"  step {step}: accepted {al}, drew {nx}")
+    assert max(lens) >= 1, "the seed should accept at least one draft token somewhere"
