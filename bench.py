@@ -22,7 +22,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PROF_EVERY = 7
+PROF_EVERY = 31
 HBM_PEAK_GBS = 8000.0
 
 
@@ -295,7 +295,8 @@ def main():
     # The matrix-core GEMMs carry their two events in the launch itself (the events take the kernel's own begin and
     # end time stamps); other kinds are bracketed by events on the stream.  Either way a timed launch costs the
     # stream a few microseconds, so only one launch in PROF_EVERY of the dominant kind is timed inside the timed
-    # region (7 is coprime to the launches per step, so samples rotate over layers).
+    # region: about one per step, 3 us of a 4 ms step (31 is coprime to the launches per step, so samples rotate
+    # over layers).
     ctx.amph_profile_kind(dom_id, min(65536, 64 * args.steps + 64), PROF_EVERY)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
