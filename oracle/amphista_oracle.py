@@ -476,13 +476,16 @@ def draft_catchup(dw: Dict[str, object], h_rows: np.ndarray, toks: Sequence[int]
                   sal_v: List[np.ndarray], n_heads: int, topk: int, eps: float, theta: float):
     """Eq. 1 applied to several newly committed positions, oldest first: position j contributes
     the pair (h_j, token that follows it) and appends one row to each stage's cache; the heads
-    (Eq. 2-6) of the LAST position are the draft.  Returns (draft of the last position, caches)."""
+    (Eq. 2-6) of the LAST position are the draft.  Returns (draft of the last position, caches).
+    The number of stages is the number of adaptation layers in dw (one in the ablation of Sec. 4.3
+    that keeps a single adaptation layer): sal_k, sal_v hold one cache per stage."""
     sal_k = [_f(k) for k in sal_k]
     sal_v = [_f(v) for v in sal_v]
+    n_stages = len(dw["sal"])
     d = None
     for h_t, tok in zip(h_rows, toks):
         d = draft(dw, h_t, int(tok), sal_k, sal_v, n_heads, topk, eps, theta)
-        for s in range(2):
+        for s in range(n_stages):
             sal_k[s] = np.concatenate([sal_k[s], d["k_new"][s][:, None, :]], axis=1)
             sal_v[s] = np.concatenate([sal_v[s], d["v_new"][s][:, None, :]], axis=1)
     return d, sal_k, sal_v
@@ -502,8 +505,8 @@ def generate(dw, tw, tree: Tree, prompt: Sequence[int], n_steps: int, n_heads: i
                          empty, empty, n_heads, eps, theta, keep=True)
     k_caches = [l["k_new"] for l in pre["layers"]]
     v_caches = [l["v_new"] for l in pre["layers"]]
-    sal_k = [np.zeros((n_heads, 0, d_h)) for _ in range(2)]
-    sal_v = [np.zeros((n_heads, 0, d_h)) for _ in range(2)]
+    sal_k = [np.zeros((n_heads, 0, d_h)) for _ in dw["sal"]]
+    sal_v = [np.zeros((n_heads, 0, d_h)) for _ in dw["sal"]]
     h_rows, toks, root = pre["hidden"], prompt[1:], prompt[-1]
     emitted, records = [], []
     for _ in range(n_steps):

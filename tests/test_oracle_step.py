@@ -304,6 +304,39 @@ def test_draft_catchup_is_the_single_position_draft_repeated():
     assert not np.allclose(dr["logits"], dl["logits"])
 
 
+def test_catchup_with_one_adaptation_layer_equals_a_causal_recompute():
+    """The variant with a single adaptation layer (Sec. 4.3) through the catch-up over several new positions: the
+    incremental result (one position at a time, each appending a cache row) must equal the textbook recompute, i.e.
+    the same decoder layer applied to all new rows at once under a causal mask on top of the committed cache; the
+    heads then read the last row, every head the first (only) stage's output."""
+    cfg, dw, tw = tiny_setup(seed=6)
+    one = {**dw, "sal": dw["sal"][:1], "fc": dw["fc"][:1]}
+    rng = np.random.default_rng(15)
+    n_h, d_h, d, K = cfg.n_heads, cfg.head_dim, cfg.d_model, 4
+    sal_k, sal_v = [rng.standard_normal((n_h, 5, d_h))], [rng.standard_normal((n_h, 5, d_h))]
+    hs, toks = rng.standard_normal((3, d)), [3, 9, 27]
+    dl, k3, v3 = orc.draft_catchup(one, hs, toks, sal_k, sal_v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    assert len(k3) == 1 and len(v3) == 1 and k3[0].shape[1] == 8 and len(dl["h"]) == 1
+    x_rows = np.stack([orc.fc_concat(one["fc"][0], hs[j], one["embed"][toks[j]]) for j in range(3)])
+    h_rows, k_new, v_new, _, _ = orc.decoder_layer_rows(x_rows, one["sal"][0], sal_k[0], sal_v[0], [5, 6, 7],
+                                                        np.tril(np.ones((3, 3), dtype=bool)), n_h, cfg.rms_eps, cfg.rope_theta)
+    assert np.allclose(dl["h"][0], h_rows[2], rtol=0, atol=1e-10)
+    assert np.allclose(k3[0][:, 5:], k_new, rtol=0, atol=1e-10) and np.allclose(v3[0][:, 5:], v_new, rtol=0, atol=1e-10)
+    for k in range(K):
+        assert np.allclose(dl["Hp"][k], orc.head_mlp(one["mlp"][k], h_rows[2]) + one["pe"][k], rtol=0, atol=1e-9)
+    # the two-stage model's first stage is the same computation: its first-stage rows agree with the one-stage run
+    two_k = [sal_k[0], rng.standard_normal((n_h, 5, d_h))]
+    two_v = [sal_v[0], rng.standard_normal((n_h, 5, d_h))]
+    d2, k2, _ = orc.draft_catchup(dw, hs, toks, two_k, two_v, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    assert len(k2) == 2 and np.array_equal(k2[0], k3[0]) and np.array_equal(d2["h"][0], dl["h"][0])
+    # and the generator runs with one stage (it keeps one adaptation-layer cache per stage of the weights)
+    tree = orc.tree_from_paths(si.tree_paths(16, (4, 2, 2, 2)), 4)
+    emitted, recs = orc.generate(one, tw, tree, [5, 17, 3, 44], 3, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    want, _ = orc.generate(dw, tw, tree, [5, 17, 3, 44], 6, n_h, 4, cfg.rms_eps, cfg.rope_theta)
+    n = min(len(emitted), len(want))
+    assert n >= 3 and emitted[:n] == want[:n]          # both emit the target's own greedy continuation
+
+
 def test_commit_rows_keeps_the_path_in_order():
     old = np.arange(2 * 3 * 4, dtype=float).reshape(2, 3, 4)
     new = 100 + np.arange(2 * 6 * 4, dtype=float).reshape(2, 6, 4)
