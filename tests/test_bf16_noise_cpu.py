@@ -1,61 +1,89 @@
-"""How much of the bf16 tolerance is used up by activation rounding alone?  (CPU only.)
+"""How much of the bf16 tolerance is used up by activation rounding alone, and how does it grow with depth?
+(CPU only.)
 
-The GPU path keeps the residual stream in float32 but hands the matrix cores bf16 activations at five
-points of a decoder layer: the two normalised inputs, q/k/v, the attention output and the SwiGLU
-product.  This test rounds the oracle's float64 values at exactly those points and compares with the
-unrounded oracle.  It pins the fact the bf16 tolerance rests on: this inherent noise is a few 1e-3 per
-layer at small widths (it grows with width: 1.4e-2 at d 6656 / FFN 17920 / 96 rows, measured once with the
-same code), i.e. the same order as the 2e-2 bound the parity tests use."""
+The GPU path keeps the residual stream in float32 but hands the matrix cores bf16 activations at five points of
+a decoder layer (tests/bf16_noise_model.py).  These tests round the oracle's float64 values at exactly those
+points and compare with the unrounded oracle.  They pin the two facts the bf16 tolerances rest on:
+  * the inherent noise of ONE layer is a few 1e-3 at small widths and grows with width (7e-3 at the 7B width,
+    1.4e-2 at the 33B width): the same order as the 2e-2 bound the per-layer parity tests use;
+  * through a stack of n layers it grows like sqrt(n) (independent per-layer noise adds in quadrature), so the
+    end-to-end error of a deep stack against the EXACT oracle exceeds 2e-2 whatever the kernels do; the GPU tests
+    at depth therefore compare with the rounding model at 2e-2 and bound the error against the exact oracle by
+    1.5 x the model's own drift on the same inputs (tests/test_gpu_full_depth.py).
+Set AMPH_FULL_NOISE=1 to run the depth test at the full 7B width through all 32 layers (about 7 minutes, most
+of it generating 6.5 G weights); the default runs 32 layers at d = 1024 and 2 layers at the 7B width."""
+import os
+
 import numpy as np
-
 import synth_inputs as si
 from oracle import amphista_oracle as orc
 
-
-def bf16(a):
-    return si.bf16_bits_to_f32(si.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))).astype(np.float64)
+import bf16_noise_model as nm
 
 
-def layer(x, lw, kc, vc, positions, visible, n_heads, eps, theta, rnd):
-    """One decoder layer over the tree rows (Sec. 2 "Tree Attention"), with `rnd` applied where the GPU stores bf16."""
-    R, d = x.shape
-    d_h = d // n_heads
-    n = rnd(orc.rmsnorm(x, lw["rms1"], eps))
-    q = orc.linear(lw["wq"], n).reshape(R, n_heads, d_h)
-    k = orc.linear(lw["wk"], n).reshape(R, n_heads, d_h)
-    v = orc.linear(lw["wv"], n).reshape(R, n_heads, d_h)
-    for r in range(R):
-        q[r], k[r] = orc.rope(q[r], positions[r], theta), orc.rope(k[r], positions[r], theta)
-    q, k, v = rnd(q), rnd(k), rnd(v)
-    k_new, v_new = np.transpose(k, (1, 0, 2)), np.transpose(v, (1, 0, 2))
-    attn = np.zeros((R, n_heads, d_h))
-    for h in range(n_heads):
-        for r in range(R):
-            sel = np.nonzero(visible[r])[0]
-            attn[r, h] = orc.attend_segments(q[r, h], [(kc[h], vc[h]), (k_new[h][sel], v_new[h][sel])])
-    y = x + orc.linear(lw["wo"], rnd(attn).reshape(R, d))
-    m = rnd(orc.rmsnorm(y, lw["rms2"], eps))
-    act = rnd(orc.silu(orc.linear(lw["w_gate"], m)) * orc.linear(lw["w_up"], m))
-    return y + orc.linear(lw["w_down"], act)
+def drift_by_depth(cfg, n_layers, T, L, caps, seed=0, report=()):
+    """Worst-row distance between the rounded and the exact stack after each layer (final-normed hidden states).
+    Layers are generated one at a time.  Returns the list of drifts."""
+    n_h, d_h, d = cfg.n_heads, cfg.head_dim, cfg.d_model
+    otree = orc.tree_from_paths(si.tree_paths(T, caps), len(caps))
+    embed = si.normal(cfg, seed, "target.embed", (cfg.vocab, d), si.W_STD)
+    tok = si.tokens(cfg, seed, "tree.tok", (1, T))[0]
+    pos = list((L + otree.depth).astype(np.int32))
+    fn = np.ones(d)
+    xe = embed.f32[tok].astype(np.float64)
+    xr = xe.copy()
+    out = []
+    for li in range(n_layers):
+        lw = {k: v.f32 for k, v in si.decoder_layer(cfg, seed, f"target.layer{li}").items()}
+        kc = si.normal(cfg, seed, f"tkv{li}.k", (1, n_h, L, d_h), 1.0).f32[0]
+        vc = si.normal(cfg, seed, f"tkv{li}.v", (1, n_h, L, d_h), 1.0).f32[0]
+        if li == 0:      # the unrounded model is the oracle's own layer
+            ref = orc.decoder_layer_rows(xe, lw, kc, vc, pos, otree.mask, n_h, cfg.rms_eps, cfg.rope_theta)[0]
+        xe = nm.layer(xe, lw, kc, vc, pos, otree.mask, n_h, cfg.rms_eps, cfg.rope_theta, nm.exact)[0]
+        if li == 0:
+            assert np.allclose(ref, xe, rtol=0, atol=1e-12)
+        xr = nm.layer(xr, lw, kc, vc, pos, otree.mask, n_h, cfg.rms_eps, cfg.rope_theta, nm.bf16)[0]
+        out.append(nm.worst_row(orc.rmsnorm(xr, fn, cfg.rms_eps), orc.rmsnorm(xe, fn, cfg.rms_eps)))
+    return out
 
 
 def test_bf16_activation_rounding_alone_costs_a_few_1e3_per_layer():
     d, n_h, f, L, T = 1024, 8, 2752, 512, 64
     cfg = si.with_(si.MINI, d_model=d, n_heads=n_h, head_dim=d // n_h, d_ffn=f, vocab=512, n_layers=1, T=T, kv_len=L)
-    tw = si.target_weights(cfg, 0, 1)
-    otree = orc.tree_from_paths(si.tree_paths(T, (10,) * 4), 4)
-    tok = si.tokens(cfg, 0, "tree.tok", (1, T))[0]
-    pos = list((L + otree.depth).astype(np.int32))
-    kc = si.normal(cfg, 0, "tkv0.k", (1, n_h, L, d // n_h), 1.0).f32[0].astype(np.float64)
-    vc = si.normal(cfg, 0, "tkv0.v", (1, n_h, L, d // n_h), 1.0).f32[0].astype(np.float64)
-    lw = {k: v.f32.astype(np.float64) for k, v in tw["layers"][0].items()}
-    x0 = tw["embed"].f32.astype(np.float64)[tok]
-    fn = tw["final_norm"].f32.astype(np.float64)
-    exact = orc.rmsnorm(layer(x0, lw, kc, vc, pos, otree.mask, n_h, 1e-6, 10000.0, lambda a: a), fn, 1e-6)
-    noisy = orc.rmsnorm(layer(x0, lw, kc, vc, pos, otree.mask, n_h, 1e-6, 10000.0, bf16), fn, 1e-6)
-    # the unrounded layer is the oracle's own layer
-    ref = orc.decoder_layer_rows(x0, tw["layers"][0] and {k: v.f32 for k, v in tw["layers"][0].items()}, kc, vc, pos,
-                                 otree.mask, n_h, 1e-6, 10000.0)[0]
-    assert np.allclose(orc.rmsnorm(ref, fn, 1e-6), exact, rtol=0, atol=1e-12)
-    err = (np.abs(noisy - exact).max(axis=1) / np.abs(exact).max(axis=1)).max()
+    err = drift_by_depth(cfg, 1, T, L, (10,) * 4)[0]
     assert 2e-3 < err < 1.2e-2, err
+
+
+def test_rounding_noise_grows_like_the_square_root_of_the_depth():
+    """32 layers at d = 1024: the drift after n layers stays within a factor 2 of sqrt(n) x the one-layer drift,
+    far below linear growth."""
+    d, n_h, f, L, T = 1024, 8, 2752, 256, 64
+    cfg = si.with_(si.MINI, d_model=d, n_heads=n_h, head_dim=d // n_h, d_ffn=f, vocab=512, n_layers=32, T=T, kv_len=L)
+    e = drift_by_depth(cfg, 32, T, L, (10,) * 4)
+    print("drift by depth at d=1024:", " ".join(f"{x:.2e}" for x in e))
+    for n in (4, 8, 16, 32):
+        ratio = e[n - 1] / e[0]
+        assert 0.5 * np.sqrt(n) <= ratio <= 2.0 * np.sqrt(n), (n, ratio)
+    assert e[31] < 0.5 * 32 * e[0]
+
+
+def test_rounding_noise_at_the_7b_width():
+    """Two layers of the 7B shape (d 4096, FFN 11008, 64 rows, 1024 cached rows): 7e-3 after one layer, about sqrt(2) x
+    that after two.  With AMPH_FULL_NOISE=1: all 32 layers; the drift then passes the 2e-2 of a single layer's
+    bound and stays below 2e-2 * sqrt(32) / 2."""
+    cfg = si.V7B
+    full = os.environ.get("AMPH_FULL_NOISE") == "1"
+    e = drift_by_depth(cfg, 32 if full else 2, cfg.T, cfg.kv_len, cfg.tree_caps)
+    print("drift by depth at the 7B width:", " ".join(f"{x:.2e}" for x in e))
+    assert 4e-3 < e[0] < 1.1e-2, e[0]
+    assert e[0] < e[1] < 2.0 * e[0]
+    if full:
+        assert 2e-2 < e[31] < 2e-2 * np.sqrt(32) / 2, e[31]
+
+
+def test_rounding_noise_at_the_33b_width():
+    """One layer of the 33B shape (d 6656, FFN 17920, 96 rows): 1.4e-2, i.e. most of the 2e-2 bound in one layer."""
+    cfg = si.V33B
+    e = drift_by_depth(cfg, 1, cfg.T, 1024, cfg.tree_caps)[0]
+    print(f"drift of one 33B-width layer: {e:.2e}")
+    assert 8e-3 < e < 2e-2, e
