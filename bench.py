@@ -47,8 +47,8 @@ def algo_bytes(kind: str, c, M: int) -> float:
         "aeb_qkv": 3 * d * d * e + 4 * B * K * d * 4,
         "aeb_attn": 4 * B * K * d * 4,
         "aeb_wo": d * d * e + 2 * B * K * d * 4,
-        "lm_head": V * d * e + B * K * (d + V) * 4,
-        "topk": B * K * V * 4,
+        "lm_head": V * d * e + B * K * d * 4,                 # candidates instead of logits: a few hundred KB
+        "topk": B * K * 512 * c.topk * 8,                     # (value, token) candidates of about 512 workgroups per row
         "t_rmsnorm": M * d * (4 + e),
         "t_qkv": 3 * d * d * e + M * d * e + 3 * M * d * e,
         "verify": 2 * B * (L + T) * d * e + 2 * M * d * e,
@@ -66,11 +66,26 @@ def step_bytes(c, M: int, n_layers: int) -> float:
     return draft + n_layers * per_layer + algo_bytes("t_rmsnorm", c, M) + algo_bytes("t_lmhead", c, M)
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+CPU_BUDGET_S = 90.0      # oracle time above which the target layers are sampled instead of all run
+
+
 def cpu_baseline(cfg, n_layers: int):
-    """The oracle as it stands, timed on the host cores on a bounded sample of the same workload (about 15 s of
-    oracle time): the whole draft (mean of 4 runs), ONE of the n_layers target layers over the tree tokens
-    (mean of N_LAYER_RUNS runs, each fed the previous run's output), and the final norm + LM head + accept;
-    the step time is t_draft + n_layers * t_layer + t_head."""
+    """The oracle as it stands, timed on the host cores over ONE whole step of the same workload: the draft, every
+    one of the n_layers target layers over the tree tokens (each fed the previous one's output), the final norm,
+    the LM head, the argmax and the acceptance.  The oracle's time does not depend on the weights' values, so the
+    seeded weights of ONE layer (and one layer's cache rows) serve all n_layers layers: generating 32 distinct
+    layers on the host would take minutes and add nothing to the timing.  If the first layer shows that the whole
+    stack would take more than CPU_BUDGET_S (the 33B shapes), the layers are sampled instead and the result says so."""
     import numpy as np
     import synth_inputs as si
     from oracle import amphista_oracle as orc
@@ -85,37 +100,45 @@ def cpu_baseline(cfg, n_layers: int):
     tok = int(si.tokens(cfg, 0, "bench.tok", (1,))[0])
     sal_k = [si.normal(cfg, 0, f"sal{s}.k", (n_h, Ls, d_h), 1.0).f32 for s in range(2)]
     sal_v = [si.normal(cfg, 0, f"sal{s}.v", (n_h, Ls, d_h), 1.0).f32 for s in range(2)]
-    log(f"[cpu_baseline] inputs for the draft generated in {time.time() - t0:.1f}s")
-    N_DRAFT_RUNS, N_LAYER_RUNS = 4, 40
-    t1 = time.time()
-    for _ in range(N_DRAFT_RUNS):
-        dr = orc.draft(dwo, h, tok, sal_k, sal_v, n_h, cfg.topk, cfg.rms_eps, cfg.rope_theta)
-    t_draft = (time.time() - t1) / N_DRAFT_RUNS
     tree = orc.tree_from_paths(si.tree_paths(T, cfg.tree_caps), cfg.K)
-    tree_tok, tree_pos = orc.tree_tokens(tree, tok, dr["topk_idx"], L)
     lw = f32l(si.decoder_layer(cfg, 0, "target.layer0"))
     kc = si.normal(cfg, 0, "tkv0.k", (n_h, L, d_h), 1.0).f32
     vc = si.normal(cfg, 0, "tkv0.v", (n_h, L, d_h), 1.0).f32
+    lm = si.normal(cfg, 0, "target.lm_head", (cfg.vocab, d), si.W_STD).f32
+    log(f"[cpu_baseline] seeded inputs generated in {time.time() - t0:.1f}s")
+    t1 = time.time()
+    dr = orc.draft(dwo, h, tok, sal_k, sal_v, n_h, cfg.topk, cfg.rms_eps, cfg.rope_theta)
+    tree_tok, tree_pos = orc.tree_tokens(tree, tok, dr["topk_idx"], L)
+    t_draft = time.time() - t1
     x = dwo["embed"][tree_tok]
     t2 = time.time()
-    x1 = x
-    for _ in range(N_LAYER_RUNS):
-        x1, _, _, _, _ = orc.decoder_layer_rows(x1, lw, kc, vc, list(tree_pos), tree.mask, n_h, cfg.rms_eps, cfg.rope_theta)
-    t_layer = (time.time() - t2) / N_LAYER_RUNS
-    lm = si.normal(cfg, 0, "target.lm_head", (cfg.vocab, d), si.W_STD).f32
+    x, _, _, _, _ = orc.decoder_layer_rows(x, lw, kc, vc, list(tree_pos), tree.mask, n_h, cfg.rms_eps, cfg.rope_theta)
+    t_first = time.time() - t2
+    full = t_first * n_layers <= CPU_BUDGET_S
+    n_run = n_layers if full else max(2, int(CPU_BUDGET_S / 3 / t_first))
+    for _ in range(n_run - 1):
+        x, _, _, _, _ = orc.decoder_layer_rows(x, lw, kc, vc, list(tree_pos), tree.mask, n_h, cfg.rms_eps, cfg.rope_theta)
+    t_layers = time.time() - t2
     t3 = time.time()
-    hidden = orc.rmsnorm(x1, np.ones(d), cfg.rms_eps)
+    hidden = orc.rmsnorm(x, np.ones(d), cfg.rms_eps)
     logits = orc.linear(lm, hidden)
     tgt = np.array([orc.row_argmax(r) for r in logits], dtype=np.int32)
     orc.accept_greedy(tree, tree_tok, tgt)
     t_head = time.time() - t3
-    total = t_draft + n_layers * t_layer + t_head
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    log(f"[cpu_baseline] draft {t_draft:.2f}s, one layer {t_layer:.2f}s, head {t_head:.2f}s -> step {total:.1f}s")
-    return {"value": 1.0 / total, "unit": "steps/s", "cores": cores, "kind": "oracle",
-            "sample": f"whole draft (mean of {N_DRAFT_RUNS} runs) + 1 of {n_layers} target layers (T={T}, L={L}; mean of "
-                      f"{N_LAYER_RUNS} runs) + final norm/LM head/accept, scaled: t_draft + {n_layers} * t_layer + t_head = "
-                      f"{total:.1f} s per step; {N_DRAFT_RUNS * t_draft + N_LAYER_RUNS * t_layer + t_head:.0f} s of oracle time"}
+    if full:
+        total = t_draft + t_layers + t_head
+        sample = (f"full step, 1 run: draft + tree + all {n_layers} target layers (T={T}, L={L}) + final norm / LM head / argmax / "
+                  f"accept = {total:.1f} s of oracle time (draft {t_draft:.2f} s, layers {t_layers:.2f} s, head {t_head:.2f} s); "
+                  f"one layer's seeded weights serve every layer (the oracle's time does not depend on the values)")
+    else:
+        total = t_draft + t_layers / n_run * n_layers + t_head
+        sample = (f"SCALED, not a full run: all {n_layers} layers would take {t_first * n_layers:.0f} s (> {CPU_BUDGET_S:.0f} s): whole draft + "
+                  f"{n_run} of {n_layers} target layers (T={T}, L={L}) + final norm / LM head / argmax / accept, "
+                  f"t_draft + {n_layers} * t_layer + t_head = {total:.1f} s per step; {t_draft + t_layers + t_head:.0f} s of oracle time")
+    log(f"[cpu_baseline] draft {t_draft:.2f}s, {n_run} layers {t_layers:.2f}s, head {t_head:.2f}s -> step {total:.1f}s on {cores} threads, {cpu_model()}")
+    return {"value": 1.0 / total, "unit": "steps/s", "cores": cores, "kind": "oracle", "sample": sample, "cpu_model": cpu_model(),
+            "seconds_per_step": total}
 
 
 def main():
@@ -130,6 +153,8 @@ def main():
     ap.add_argument("--unequal-kv", action="store_true",
                     help="batch elements get committed lengths spread over [L/4, L] instead of all L")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-loop", action="store_true",
+                    help="skip the second timed region (the loop iteration: catch-up draft + step + commit)")
     ap.add_argument("--breakdown", action="store_true", help="time every kernel kind (one extra step each) and print it")
     ap.add_argument("--row-major", action="store_true",
                     help="feed the target's GEMMs the row-major matrices instead of their tiled copies (slower; for comparison)")
@@ -256,6 +281,34 @@ def main():
         else:
             ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
 
+    # The iteration of the decode loop (Sec. 2 "Speculative Decoding"): what a serving loop runs between two emitted
+    # chunks.  The draft catches up over the K + 1 rows amph_commit gathered (n_valid of them live), the target also
+    # writes its final-normed hidden states, and amph_commit compacts the accepted rows in every layer and gathers the
+    # next draft's inputs.  Lengths are reset every iteration so that each one does the same work.
+    hidden = torch.zeros((Bsz, T, d), dtype=torch.float32, device=dev)
+    h_new = torch.zeros((Bsz, K + 1, d), dtype=torch.float32, device=dev)
+    h_new[:, 0] = h
+    tok_new = i32(Bsz, K + 1)
+    tok_new[:, 0] = tok
+    n_new = torch.ones((Bsz,), dtype=torch.int32, device=dev)
+    root = tok.clone()
+    kv_len0 = kv_len.clone()
+    kv_len_loop = kv_len.clone()
+
+    def loop_iteration():
+        sal_len.copy_(sal_len0)
+        kv_len_loop.copy_(kv_len0)
+        ctx.amph_draft(dstruct, h_new, tok_new, sal_kv, sal_len, topk_idx, topk_val, None, n_new=K + 1, n_valid=n_new)
+        ctx.amph_tree_build(tree, root, topk_idx, kv_len_loop, tree_tok, tree_pos)
+        ctx.amph_target_forward(tree, structs, dw["embed"], final_norm, t_lm_head, tree_tok, tree_pos, k_caches, v_caches,
+                                kv_len_loop, hidden, t_logits, tgt, tiled_structs=tiled_structs, lm_head_tiled=lm_tiled)
+        if sampling:
+            ctx.amph_accept_typical(tree, tree_tok, t_logits, args.temperature, 0.09, 0.3, u_draws, a_len, a_path, nxt, best)
+        else:
+            ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
+        ctx.amph_commit(tree, n_layers, k_caches, v_caches, kv_len_loop, a_len, a_path, nxt, tree_tok, hidden, h_new, tok_new, n_new)
+        root.copy_(nxt)
+
     if args.calibrate_copy:
         n_cal = 64 * 2 ** 20                                   # float32 elements: 256 MiB in, 256 MiB out
         cal_src = torch.ones(n_cal, dtype=torch.float32, device=dev)
@@ -315,6 +368,23 @@ def main():
     empty_us = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / len(pairs) * 1e3
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     steps_per_s = 1e3 / ms_per_step
+    loop = None
+    if not args.no_loop:
+        for _ in range(3):
+            loop_iteration()
+        torch.cuda.synchronize()
+        assert ctx.device_status() == 0, "device-side range check failed in the loop iteration"
+        tl0 = time.perf_counter()
+        for _ in range(args.steps):
+            loop_iteration()
+        torch.cuda.synchronize()
+        loop_ms = (time.perf_counter() - tl0) * 1e3 / args.steps
+        loop = {"ms_per_iteration": loop_ms, "iterations_per_s": 1e3 / loop_ms, "iterations": args.steps,
+                "what": f"amph_draft over K + 1 = {K + 1} catch-up rows per sequence (n_valid live) + amph_tree_build + "
+                        f"amph_target_forward (hidden states out) + accept + amph_commit in all {n_layers} layers; "
+                        "lengths reset every iteration",
+                "mean_accept_len": float(a_len.float().mean().item())}
+        log(f"[bench] loop iteration: {loop_ms:.3f} ms ({1e3 / loop_ms:.1f} per s) against {ms_per_step:.3f} ms for the step alone")
     dom_avg_s = dom_ms * 1e-3 / max(dom_n, 1)
     dom_bytes = algo_bytes(dominant, cfg, M)
     achieved = dom_bytes / dom_avg_s / 1e9
@@ -348,6 +418,21 @@ def main():
                      "avg_launch_us": dom_avg_s * 1e6, "empty_event_pair_us": empty_us,
                      "algorithmic_bytes_per_launch": dom_bytes},
     }
+    if per_kind:
+        # every kernel kind of one step, event-bracketed in its own untimed step (the brackets add the markers' own
+        # few microseconds to the short kinds: see roofline.empty_event_pair_us); GB/s = algorithmic bytes / time
+        out["per_kind"] = {name: {"launches": n, "avg_us": ms * 1e3 / n,
+                                  "GBps": algo_bytes(name, cfg, M) * n / (ms * 1e-3) / 1e9,
+                                  "frac_of_hbm_peak": algo_bytes(name, cfg, M) * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+                           for name, (ms, n) in per_kind.items() if n}
+        draft_kinds = ("fc", "sal_qkv", "sal_attn", "sal_wo", "sal_gateup", "sal_down", "head_mlp", "aeb_qkv", "aeb_attn", "aeb_wo",
+                       "lm_head", "topk")
+        draft_us = sum(per_kind[k][0] for k in draft_kinds if k in per_kind) * 1e3
+        draft_b = sum(algo_bytes(k, cfg, M) * per_kind[k][1] for k in draft_kinds if k in per_kind)
+        out["draft"] = {"kernel_time_us": draft_us, "algorithmic_GB": draft_b / 1e9,
+                        "frac_of_hbm_peak": draft_b / (draft_us * 1e-6) / 1e9 / HBM_PEAK_GBS if draft_us else None}
+    if loop is not None:
+        out["loop"] = loop
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, n_layers)
     print(json.dumps(out), flush=True)

@@ -7,10 +7,14 @@
  *     synchronous; all device work is enqueued on the context's stream and returns at once.  No call
  *     synchronises the stream or reads device memory on the host unless its comment says so.
  *   - Unless marked "host", every pointer is a DEVICE pointer owned by the caller; the library never
- *     frees or reallocates caller memory.  The library owns amph_ctx (a few KB of device counters)
- *     and amph_tree (host tables plus device copies), released by their _destroy calls.
- *   - Layouts are dense row-major in the order written, last index fastest.  "T" below is the
- *     configuration's storage type: float for AMPH_F32, bfloat16 (16-bit patterns) for AMPH_BF16.
+ *     frees or reallocates caller memory.  The library owns amph_ctx (one device status word) and
+ *     amph_tree (host tables plus device copies), both allocated by their _create calls and released
+ *     by their _destroy calls; no other call allocates, frees or blocks.
+ *   - Layouts are dense row-major in the order written, last index fastest, with two exceptions that
+ *     are private to the matrix-core kernels and have converters here: the target's K/V caches are
+ *     STEP-TILED (amph_pack_kv / amph_unpack_kv; formulas at amph_verify_attn) and the target's weight
+ *     matrices may be given as tiled copies (amph_pack_weights).  "T" below is the configuration's
+ *     storage type: float for AMPH_F32, bfloat16 (16-bit patterns) for AMPH_BF16.
  *     Weights are [out_features, in_features].  Accumulation is always float32.
  *   - Quantities that only the device knows (kv_len, sal_len) are range-checked inside the kernels:
  *     a violation sets a sticky device flag, the offending call writes no output for that batch
@@ -103,7 +107,8 @@ typedef struct amph_ctx amph_ctx;
 typedef struct amph_tree amph_tree;
 
 /* ---- context --------------------------------------------------------------------------------- */
-/* Validates cfg (host pointer), allocates the context's device counters.  *out is NULL on failure. */
+/* Validates cfg (host pointer), allocates the context's device status word on the CURRENT device.
+ * *out is NULL on failure. */
 amph_status amph_create(const amph_config *cfg, amph_ctx **out);
 void amph_destroy(amph_ctx *ctx);
 /* hip_stream is a hipStream_t (NULL = the default stream).  The caller keeps it alive. */
@@ -124,15 +129,20 @@ amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits);
  * adaptation layers first catch up over the a + 1 new positions, oldest first (each row attends to the
  * cache and to the new rows before it); the heads read the LAST live position.
  *   h_new    [B, n_new, d] float32     tok_new [B, n_new] int32 (the token that follows each position)
- *            1 <= n_new, B * n_new <= 8
+ *            1 <= n_new <= K + 1.  The adaptation layers' weight-streaming kernels take 8 rows at a time: a
+ *            call with B * n_new > 8 streams their weights ceil(B * n_new / 8) times.
  *   n_valid  [B] int32 on the device or NULL: positions j >= n_valid[b] of element b are ignored (no
  *            cache row, no effect on the heads); NULL = all n_new live.  amph_commit writes such a triple.
  *   sal_kv   [2 stages, B, 2 (K then V), n_heads, max_kv, head_dim] T; rows sal_len[b] + j of both stages
  *            are written (keys after RoPE at that position) and attended together with the rows below them
- *   sal_len  [B] int32, read on the device and advanced by n_valid[b] (or n_new) when the call completes
+ *   sal_len  [B] int32, read on the device and advanced by n_valid[b] (or n_new) when the call completes,
+ *            unless that would pass max_kv: then it stays as it was (see below)
  *   topk_idx [B, K, topk] int32        topk_val [B, K, topk] float32
  *   logits   [B, K, V] float32 or NULL (then the logits live only in the workspace)
- * Device-side errors: sal_len[b] + 1 > max_kv (AMPH_DEV_SAL_OVERFLOW), token id outside [0, V). */
+ * Device-side errors: a new position j whose cache row sal_len[b] + j would lie at or beyond max_kv writes
+ * no cache row and raises AMPH_DEV_SAL_OVERFLOW (rows below it are still written); sal_len[b] is then left
+ * unchanged and the top-k written for element b is meaningless.  A token id outside [0, V) raises
+ * AMPH_DEV_BAD_TOKEN and is read as token 0. */
 amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w /* host */, const float *h_new,
                        const int32_t *tok_new, int n_new, const int32_t *n_valid, void *sal_kv,
                        int32_t *sal_len, int32_t *topk_idx, float *topk_val, float *logits,
@@ -142,7 +152,10 @@ amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w /* host */, const fl
  * paths: host array [n, K] of top-k ranks, -1 padded; one row per non-root node, any order; the
  * root (the token the target just sampled) is implicit.  Nodes are numbered root first, then by
  * (depth, rank path).  Fails with AMPH_ETREE on a missing parent, a duplicate or a path longer
- * than K, AMPH_ESHAPE if n + 1 > AMPH_MAX_TREE or a rank >= AMPH_MAX_TOPK. */
+ * than K, AMPH_ESHAPE if n + 1 > AMPH_MAX_TREE or a rank >= AMPH_MAX_TOPK.
+ * A set-up call: it allocates the tree's device tables (a few KB) on the CURRENT device and copies
+ * them there with a blocking copy, so that no call of the step allocates or blocks.  Without a visible
+ * device the tree is a host object (amph_tree_info works; device calls given it return AMPH_EINVAL). */
 amph_status amph_tree_create(const int32_t *paths /* host */, int n, int K, amph_tree **out);
 void amph_tree_destroy(amph_tree *tree);
 /* Host views valid until amph_tree_destroy; any output pointer may be NULL.
@@ -254,6 +267,18 @@ amph_status amph_target_forward(amph_ctx *ctx, const amph_tree *tree, const amph
 typedef enum { AMPH_PACK_QKV = 0, AMPH_PACK_WO, AMPH_PACK_GATEUP, AMPH_PACK_DOWN, AMPH_PACK_LMHEAD, AMPH_PACK_COUNT } amph_pack_role;
 amph_status amph_tiled_bytes(const amph_ctx *ctx, int role, size_t *bytes /* host */);
 amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const void *w1, const void *w2, void *dst);
+
+/* ---- K/V cache layout conversion (Sec. 2 "Tree Attention": the committed rows the tree attends to) ------
+ * A caller that filled its caches elsewhere (a prefill) holds them row-major [n_caches, max_kv, head_dim]
+ * with n_caches = layers * batch * heads; amph_verify_attn / amph_target_forward / amph_commit want the
+ * step-tiled storage whose byte formulas stand at amph_verify_attn.  amph_pack_kv writes the tiled form of
+ * every cache, amph_unpack_kv the row-major form back (all max_kv rows; one kernel per call, on the context's
+ * stream).  Keys, values or both: a NULL source skips that half (its destination must then be NULL too).
+ * Source and destination must not overlap.  n_caches <= 65535 * 16. */
+amph_status amph_pack_kv(amph_ctx *ctx, const void *k_rows, const void *v_rows, void *k_tiled, void *v_tiled,
+                         int n_caches);
+amph_status amph_unpack_kv(amph_ctx *ctx, const void *k_tiled, const void *v_tiled, void *k_rows, void *v_rows,
+                           int n_caches);
 
 /* ---- choice of the verification-attention kernel, for tests and measurements -----------------------
  * The tree attention (amph_verify_attn, and inside amph_target_forward) has two kernels with the same

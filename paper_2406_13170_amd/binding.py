@@ -62,6 +62,8 @@ EXPORTS = {
     "amph_tree_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)] + [C.POINTER(C.c_void_p)] * 5),
     "amph_tree_build": (C.c_int, [C.c_void_p] * 7),
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
+    "amph_pack_kv": (C.c_int, [C.c_void_p] * 5 + [C.c_int]),
+    "amph_unpack_kv": (C.c_int, [C.c_void_p] * 5 + [C.c_int]),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
     "amph_accept_typical": (C.c_int, [C.c_void_p] * 4 + [C.c_float] * 3 + [C.c_void_p] * 6),
     "amph_target_forward": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(amph_layer_w), C.POINTER(amph_layer_tiled), C.c_int]
@@ -243,6 +245,14 @@ class Context:
     def amph_verify_attn(self, tree: Tree, q, k_cache, v_cache, kv_len, out):
         self._check(lib().amph_verify_attn(self.handle, tree.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
                                            _ptr(out), _ptr(self.workspace)), "amph_verify_attn")
+
+    def amph_pack_kv(self, k_rows, v_rows, k_tiled, v_tiled, n_caches: int):
+        self._check(lib().amph_pack_kv(self.handle, _ptr(k_rows), _ptr(v_rows), _ptr(k_tiled), _ptr(v_tiled), n_caches),
+                    "amph_pack_kv")
+
+    def amph_unpack_kv(self, k_tiled, v_tiled, k_rows, v_rows, n_caches: int):
+        self._check(lib().amph_unpack_kv(self.handle, _ptr(k_tiled), _ptr(v_tiled), _ptr(k_rows), _ptr(v_rows), n_caches),
+                    "amph_unpack_kv")
 
     def amph_accept(self, tree: Tree, tree_tok, tgt_argmax, tgt_logits, accept_len, accept_path, next_tok, best_node):
         self._check(lib().amph_accept(self.handle, tree.handle, _ptr(tree_tok), _ptr(tgt_argmax), _ptr(tgt_logits),

@@ -14,8 +14,6 @@ using namespace amph;
 
 namespace {
 
-constexpr size_t N_COUNTERS = 64;      // device words owned by a context; word N_COUNTERS is the status word
-
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct WsLayout {   // byte offsets into the caller's workspace
@@ -30,8 +28,7 @@ struct WsLayout {   // byte offsets into the caller's workspace
 struct amph_ctx {
   amph_config cfg;
   hipStream_t stream = nullptr;
-  unsigned int *counters = nullptr;   // device, zero between launches
-  uint32_t *dev_status = nullptr;     // device, sticky
+  uint32_t *dev_status = nullptr;     // device, sticky (the context's only device allocation)
   std::string err = "";
   WsLayout ws;
   int esz = 2;
@@ -47,9 +44,10 @@ struct amph_tree {
   int T = 0, K = 0, n_leaves = 0;
   std::vector<int32_t> parent, depth, rank, retrieve;
   std::vector<uint64_t> mask;
+  // device copies, one allocation made by amph_tree_create: mask, then parent, depth, rank
+  void *d_block = nullptr;
   int32_t *d_parent = nullptr, *d_depth = nullptr, *d_rank = nullptr;
   uint64_t *d_mask = nullptr;
-  bool on_device = false;
 };
 
 namespace {
@@ -104,12 +102,13 @@ WsLayout make_layout(const amph_config &c) {
   const size_t M = B * (size_t)c.max_tree;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at = align_up(at + bytes, 256); return o; };
-  const size_t Mr = std::max<size_t>(B, 8);     // adaptation-layer rows: up to 8 (batch element, new position) pairs
+  const size_t Mr = B * (K + 1);                // adaptation-layer rows: (batch element, new position) pairs, n_new <= K + 1
   w.x = take(Mr * d * 4); w.q = take(Mr * d * 4); w.att = take(Mr * d * 4); w.y = take(Mr * d * 4);
   w.act = take(Mr * f * 4); w.h[0] = take(Mr * d * 4); w.h[1] = take(Mr * d * 4);
   w.Hp = take(BK * d * 4); w.Qa = take(BK * d * 4); w.Ka = take(BK * d * 4); w.Va = take(BK * d * 4);
   w.ctxa = take(BK * d * 4); w.attn_o = take(BK * d * 4); w.logits = take(BK * V * 4);
-  w.topk_ws = take(std::max(topk_ws_floats((int)BK, c.vocab, c.topk), topk_ws_floats((int)M, c.vocab, 1)) * 4);
+  w.topk_ws = take(std::max(std::max(topk_ws_floats((int)BK, c.vocab, c.topk), topk_ws_floats((int)M, c.vocab, 1)),
+                            lmtk_ws_floats((int)BK, c.topk)) * 4);
   const size_t Mp = (M + 31) / 32 * 32;         // activations may be kept in 32-row tiles for the wide GEMM
   w.xres = take(M * d * 4); w.xn = take(Mp * d * esz); w.qb = take(M * d * esz); w.attb = take(Mp * d * esz);
   w.actb = take(Mp * f * esz);
@@ -130,19 +129,26 @@ WsLayout make_layout(const amph_config &c) {
   return w;
 }
 
-amph_status tree_upload(amph_ctx *ctx, amph_tree *t) {
-  if (t->on_device) return AMPH_OK;
+// Device copies of a tree's tables on the current device: one allocation, one blocking copy.  Called from
+// amph_tree_create only (a set-up call), so that no call of the step allocates or blocks.
+hipError_t tree_upload(amph_tree *t) {
   const size_t n = t->T;
-  HIP_TRY(ctx, hipMalloc(&t->d_parent, n * 4));
-  HIP_TRY(ctx, hipMalloc(&t->d_depth, n * 4));
-  HIP_TRY(ctx, hipMalloc(&t->d_rank, n * 4));
-  HIP_TRY(ctx, hipMalloc(&t->d_mask, n * 16));
-  HIP_TRY(ctx, hipMemcpy(t->d_parent, t->parent.data(), n * 4, hipMemcpyHostToDevice));
-  HIP_TRY(ctx, hipMemcpy(t->d_depth, t->depth.data(), n * 4, hipMemcpyHostToDevice));
-  HIP_TRY(ctx, hipMemcpy(t->d_rank, t->rank.data(), n * 4, hipMemcpyHostToDevice));
-  HIP_TRY(ctx, hipMemcpy(t->d_mask, t->mask.data(), n * 16, hipMemcpyHostToDevice));
-  t->on_device = true;
-  return AMPH_OK;
+  const size_t bytes = n * 16 + 3 * n * 4;
+  hipError_t e = hipMalloc(&t->d_block, bytes);
+  if (e != hipSuccess) { t->d_block = nullptr; return e; }
+  std::vector<unsigned char> host(bytes);
+  std::memcpy(host.data(), t->mask.data(), n * 16);
+  std::memcpy(host.data() + n * 16, t->parent.data(), n * 4);
+  std::memcpy(host.data() + n * 16 + n * 4, t->depth.data(), n * 4);
+  std::memcpy(host.data() + n * 16 + 2 * n * 4, t->rank.data(), n * 4);
+  e = hipMemcpy(t->d_block, host.data(), bytes, hipMemcpyHostToDevice);
+  if (e != hipSuccess) { (void)hipFree(t->d_block); t->d_block = nullptr; return e; }
+  unsigned char *base = (unsigned char *)t->d_block;
+  t->d_mask = (uint64_t *)base;
+  t->d_parent = (int32_t *)(base + n * 16);
+  t->d_depth = (int32_t *)(base + n * 16 + n * 4);
+  t->d_rank = (int32_t *)(base + n * 16 + 2 * n * 4);
+  return hipSuccess;
 }
 
 template <typename T>
@@ -182,7 +188,6 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   }
   float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);
   float *attn_o = F(ctx->ws.attn_o);
-  float *lg = logits ? logits : F(ctx->ws.logits);
   PROF_TRY(ctx, AMPH_K_HEAD_MLP, launch_head_mlp<T>(st, w->mlp, w->pe, h1, h2, d, K, B, Hp));
   const int BK = B * K;
   // Eq. 5, once or twice: q/k/v projections of the K rows, K x K attention per head, output projection
@@ -218,24 +223,25 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     }
     head_in = Qa; lm_w = w->lm_b; lm_k = c.lm_rank;
   }
-  for (int r0 = 0; r0 < BK; r0 += 8) {
-    const int m = std::min(8, BK - r0);
-    PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_linear<T>(st, lm_w, nullptr, nullptr, 1, V, lm_k, head_in + (size_t)r0 * lm_k, lm_k, m,
-                                  nullptr, lg + (size_t)r0 * V, nullptr, nullptr, V));
-  }
-  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_rows(st, lg, BK, V, c.topk, topk_idx, topk_val, sal_len, B, R, n_valid, F(ctx->ws.topk_ws)));
+  // Eq. 6: the LM head's launches leave per-workgroup top-k candidates (and the logits only if the caller wants them);
+  // the merge kernel picks every row's top k and advances the adaptation layers' cache lengths
+  float *cand = F(ctx->ws.topk_ws);
+  int n_cand = 0;
+  PROF_TRY(ctx, AMPH_K_LM_HEAD, launch_lmhead_cands<T>(st, lm_w, V, lm_k, head_in, BK, c.topk, logits, cand, &n_cand));
+  PROF_TRY(ctx, AMPH_K_TOPK, launch_topk_merge(st, cand, reinterpret_cast<const int *>(cand + (size_t)BK * n_cand), BK, n_cand, V, c.topk,
+                                               topk_idx, topk_val, sal_len, B, R, n_valid, c.max_kv));
   return AMPH_OK;
 }
 
 template <typename T>
 amph_status verify_impl(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache, const void *v_cache,
-                        const int32_t *kv_len, void *out, void *workspace, int out_tiles = 0) {
+                        const int32_t *kv_len, void *out, float *partials, size_t partials_floats, int out_tiles = 0) {
   const amph_config &c = ctx->cfg;
   VerifyArgs a{};
   a.q = q; a.k_cache = k_cache; a.v_cache = v_cache; a.out = out; a.kv_len = kv_len; a.mask_bits = tree->d_mask;
   a.B = c.batch; a.T = tree->T; a.n_heads = c.n_heads; a.d_h = c.head_dim; a.max_kv = c.max_kv;
-  a.partials = (float *)((char *)workspace + ctx->ws.ver_part);
-  a.partials_cap = ctx->ws.ver_part_floats;
+  a.partials = partials;
+  a.partials_cap = partials_floats;
   a.dev_status = ctx->dev_status;
   a.kernel = ctx->verify_kernel;
   a.out_tiles = out_tiles;
@@ -291,7 +297,9 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
     a.x_tiled = w_qkv;
     a.q_out = qb; a.k_cache = kc; a.v_cache = vc;
     PROF_GEMM(ctx, AMPH_K_T_QKV, T, st, EPI_QKV_ROPE, a);
-    if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, workspace, w_wo ? xt_tiles : 0)) return s;
+    if (amph_status s = verify_impl<T>(ctx, tree, qb, kc, vc, kv_len, attb, (float *)(ws + ctx->ws.ver_part), ctx->ws.ver_part_floats,
+                                       w_wo ? xt_tiles : 0))
+      return s;
     a = g;
     a.w0 = lw.wo; a.wt = lt.wo; a.n_seg = 1; a.seg_rows = d; a.Kd = d; a.x = attb; a.out = slabs; a.split_k = s_wo;
     a.x_tiled = w_wo;
@@ -351,14 +359,13 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
   ctx->cfg = c;
   ctx->esz = (c.dtype == AMPH_BF16) ? 2 : 4;
   ctx->ws = make_layout(c);
-  hipError_t e = hipMalloc(&ctx->counters, N_COUNTERS * sizeof(unsigned int) + 256);
-  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, N_COUNTERS * sizeof(unsigned int) + 256);
+  hipError_t e = hipMalloc(&ctx->dev_status, 256);
+  if (e == hipSuccess) e = hipMemset(ctx->dev_status, 0, 256);
   if (e != hipSuccess) {
-    if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->dev_status) (void)hipFree(ctx->dev_status);
     delete ctx;
     return AMPH_EHIP;
   }
-  ctx->dev_status = reinterpret_cast<uint32_t *>(ctx->counters + N_COUNTERS);
   *out = ctx;
   return AMPH_OK;
 }
@@ -366,7 +373,7 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
 void amph_destroy(amph_ctx *ctx) {
   if (!ctx) return;
   for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
-  if (ctx->counters) (void)hipFree(ctx->counters);
+  if (ctx->dev_status) (void)hipFree(ctx->dev_status);
   delete ctx;
 }
 
@@ -394,8 +401,8 @@ amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
   if (!ctx) return AMPH_EINVAL;
   if (!w || !h_new || !tok_new || !sal_kv || !sal_len || !topk_idx || !topk_val || !workspace)
     return fail(ctx, AMPH_EINVAL, "amph_draft: null argument");
-  if (n_new < 1 || (long long)n_new * ctx->cfg.batch > 8)
-    return fail(ctx, AMPH_ESHAPE, "amph_draft: need 1 <= n_new and batch * n_new <= 8");
+  if (n_new < 1 || n_new > ctx->cfg.K + 1)
+    return fail(ctx, AMPH_ESHAPE, "amph_draft: need 1 <= n_new <= K + 1");
   const amph_config &cf = ctx->cfg;
   const void *ptrs[] = {w->embed, w->fc[0], w->mlp, w->aeb_wq, w->aeb_wk, w->aeb_wv, w->aeb_wo, h_new, sal_kv, workspace};
   for (const void *p : ptrs)
@@ -415,7 +422,6 @@ amph_status amph_draft(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     for (const void *p : lp)
       if (!p || !aligned16(p)) return fail(ctx, AMPH_EINVAL, "amph_draft: null or misaligned SAL weight");
   }
-  if (ctx->cfg.batch > 8) return fail(ctx, AMPH_ESHAPE, "amph_draft: batch > 8 is not supported");
   if (ctx->cfg.dtype == AMPH_BF16)
     return draft_impl<bf16_t>(ctx, w, h_new, tok_new, n_new, n_valid, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
   return draft_impl<float>(ctx, w, h_new, tok_new, n_new, n_valid, sal_kv, sal_len, topk_idx, topk_val, logits, workspace);
@@ -475,16 +481,21 @@ amph_status amph_tree_create(const int32_t *paths, int n, int K, amph_tree **out
     t->retrieve.insert(t->retrieve.end(), chain.begin(), chain.end());
     t->n_leaves++;
   }
+  // With a device visible the tables go to the current device now; without one (host-only use of the tree's
+  // tables) the tree stays a host object and every device call that takes it reports AMPH_EINVAL.
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) == hipSuccess && n_dev > 0) {
+    if (tree_upload(t) != hipSuccess) { delete t; return AMPH_EHIP; }
+  } else {
+    (void)hipGetLastError();                                // a failed device query leaves a sticky error behind
+  }
   *out = t;
   return AMPH_OK;
 }
 
 void amph_tree_destroy(amph_tree *t) {
   if (!t) return;
-  if (t->d_parent) (void)hipFree(t->d_parent);
-  if (t->d_depth) (void)hipFree(t->d_depth);
-  if (t->d_rank) (void)hipFree(t->d_rank);
-  if (t->d_mask) (void)hipFree(t->d_mask);
+  if (t->d_block) (void)hipFree(t->d_block);
   delete t;
 }
 
@@ -507,7 +518,8 @@ static amph_status check_tree(amph_ctx *ctx, const amph_tree *tree, const char *
   if (tree->K != ctx->cfg.K) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": tree depth K differs from cfg.K");
   for (int i = 1; i < tree->T; ++i)
     if (tree->rank[i] >= ctx->cfg.topk) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": tree uses a rank >= cfg.topk");
-  return tree_upload(ctx, const_cast<amph_tree *>(tree));
+  if (!tree->d_block) return fail(ctx, AMPH_EINVAL, std::string(who) + ": the tree was created without a visible device");
+  return AMPH_OK;
 }
 
 amph_status amph_tree_build(amph_ctx *ctx, const amph_tree *tree, const int32_t *root_tok, const int32_t *topk_idx,
@@ -528,8 +540,10 @@ amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q
     return fail(ctx, AMPH_EINVAL, "amph_verify_attn: pointers must be 16-byte aligned");
   if (q == out) return fail(ctx, AMPH_EINVAL, "amph_verify_attn: out must not alias q");
   if (amph_status s = check_tree(ctx, tree, "amph_verify_attn")) return s;
-  if (ctx->cfg.dtype == AMPH_BF16) return verify_impl<bf16_t>(ctx, tree, q, k_cache, v_cache, kv_len, out, workspace);
-  return verify_impl<float>(ctx, tree, q, k_cache, v_cache, kv_len, out, workspace);
+  float *partials = (float *)((char *)workspace + ctx->ws.ver_part);
+  if (ctx->cfg.dtype == AMPH_BF16)
+    return verify_impl<bf16_t>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, ctx->ws.ver_part_floats);
+  return verify_impl<float>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, ctx->ws.ver_part_floats);
 }
 
 amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok, const int32_t *tgt_argmax,
@@ -658,6 +672,29 @@ amph_status amph_pack_weights(amph_ctx *ctx, int role, const void *w0, const voi
   if (ctx->cfg.dtype == AMPH_BF16) HIP_TRY(ctx, launch_pack_weights<bf16_t>(ctx->stream, epi, a, dst));
   else HIP_TRY(ctx, launch_pack_weights<float>(ctx->stream, epi, a, dst));
   return AMPH_OK;
+}
+
+static amph_status kv_layout(amph_ctx *ctx, const char *who, const void *k_src, const void *v_src, void *k_dst, void *v_dst,
+                             int n_caches, bool to_tiled) {
+  if (!ctx) return AMPH_EINVAL;
+  if (n_caches < 1 || (!k_src && !v_src) || (k_src != nullptr) != (k_dst != nullptr) || (v_src != nullptr) != (v_dst != nullptr))
+    return fail(ctx, AMPH_EINVAL, std::string(who) + ": need n_caches >= 1 and source and destination of keys, values or both");
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_dst) || !aligned16(v_dst))
+    return fail(ctx, AMPH_EINVAL, std::string(who) + ": pointers must be 16-byte aligned");
+  if ((k_src && k_src == k_dst) || (v_src && v_src == v_dst)) return fail(ctx, AMPH_EINVAL, std::string(who) + ": in-place conversion is not supported");
+  if (n_caches > 65535 * 16) return fail(ctx, AMPH_ESHAPE, std::string(who) + ": more than 65535 * 16 caches in one call");
+  const amph_config &c = ctx->cfg;
+  if (c.dtype == AMPH_BF16) HIP_TRY(ctx, launch_kv_layout<bf16_t>(ctx->stream, k_src, v_src, k_dst, v_dst, n_caches, c.max_kv, c.head_dim, to_tiled));
+  else HIP_TRY(ctx, launch_kv_layout<float>(ctx->stream, k_src, v_src, k_dst, v_dst, n_caches, c.max_kv, c.head_dim, to_tiled));
+  return AMPH_OK;
+}
+
+amph_status amph_pack_kv(amph_ctx *ctx, const void *k_rows, const void *v_rows, void *k_tiled, void *v_tiled, int n_caches) {
+  return kv_layout(ctx, "amph_pack_kv", k_rows, v_rows, k_tiled, v_tiled, n_caches, true);
+}
+
+amph_status amph_unpack_kv(amph_ctx *ctx, const void *k_tiled, const void *v_tiled, void *k_rows, void *v_rows, int n_caches) {
+  return kv_layout(ctx, "amph_unpack_kv", k_tiled, v_tiled, k_rows, v_rows, n_caches, false);
 }
 
 amph_status amph_verify_kernel(amph_ctx *ctx, int kernel) {

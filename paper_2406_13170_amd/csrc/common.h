@@ -161,4 +161,61 @@ __device__ __forceinline__ float block_sum_256(float v, float *red) {
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
+// ---- selection inside one wave (top-k of Eq. 6) ---------------------------------------------------------
+// "Better" means a larger value, or the same value and a smaller index, so results are sorted and ties deterministic.
+__device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
+  return (v1 > v2) || (v1 == v2 && i1 < i2);
+}
+
+// The best (value, index) pair of the wave, in every lane.  Six data-parallel-primitive steps instead of a
+// butterfly of cross-lane permutes through the LDS crossbar (twelve dependent permutes cost about 1400 clocks per
+// selection round, which made a ten-round top-k the longest part of its kernel): inside each row of 16 lanes
+// the pair is folded with its neighbour at distance 1, 2, then its mirror inside 8 and inside 16 lanes (after which
+// every lane of a row holds the row's best); lane 15 of rows 0 and 2 is then broadcast into rows 1 and 3, lane 31
+// into rows 2 and 3, so lane 63 ends with the wave's best, which a lane read hands to everybody.  A lane that a
+// step does not write keeps its own pair, which never beats itself.  All 64 lanes must be active.
+__device__ __forceinline__ void wave_best(float &v, int &i) {
+  #define AMPH_DPP_STEP(CTRL, ROWS)                                                                              \
+    {                                                                                                            \
+      const int ovb = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROWS, 0xf, false); \
+      const int oi = __builtin_amdgcn_update_dpp(i, i, CTRL, ROWS, 0xf, false);                                  \
+      const float ov = __int_as_float(ovb);                                                                      \
+      if (better(ov, oi, v, i)) { v = ov; i = oi; }                                                              \
+    }
+  AMPH_DPP_STEP(0xb1, 0xf)       // quad_perm [1, 0, 3, 2]
+  AMPH_DPP_STEP(0x4e, 0xf)       // quad_perm [2, 3, 0, 1]
+  AMPH_DPP_STEP(0x141, 0xf)      // row_half_mirror
+  AMPH_DPP_STEP(0x140, 0xf)      // row_mirror
+  AMPH_DPP_STEP(0x142, 0xa)      // row_bcast:15 into rows 1 and 3
+  AMPH_DPP_STEP(0x143, 0xc)      // row_bcast:31 into rows 2 and 3
+  #undef AMPH_DPP_STEP
+  v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+  i = __builtin_amdgcn_readlane(i, 63);
+}
+
+// Select k times from NPT per-lane (value, index) pairs spread over a wave.  Lane 0 writes the results.
+template <int NPT>
+__device__ __forceinline__ void wave_select(float (&x)[NPT], int (&id)[NPT], int k, int none, float *out_v, int *out_i) {
+  const float NEG_INF = -__builtin_huge_valf();
+  const int lane = threadIdx.x & 63;
+  float bv = NEG_INF; int bi = none, bj = -1;
+  #pragma unroll
+  for (int j = 0; j < NPT; ++j)
+    if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
+  for (int r = 0; r < k; ++r) {
+    float wv = bv; int wi = bi;
+    wave_best(wv, wi);
+    if (lane == 0) { out_v[r] = wv; out_i[r] = (wi == none) ? -1 : wi; }
+    if (wi != none && wi == bi) {              // this lane owned the winner: retire it and rescan
+      bv = NEG_INF; bi = none;
+      const int gone = bj; bj = -1;
+      #pragma unroll
+      for (int j = 0; j < NPT; ++j) {
+        if (j == gone) id[j] = none;
+        if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
+      }
+    }
+  }
+}
+
 }  // namespace amph

@@ -443,6 +443,65 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
   }
 }
 
+// =====================================================================================================
+// K6: the shared LM head of Eq. 6 with the top-k candidates taken in the epilogue.  A workgroup owns Gp
+// consecutive row groups (4 * Gp vocabulary rows), keeps their logits of the M rows in LDS and, when its rows
+// are done, each wave selects the top k of one activation row's 4 * Gp logits: the workgroup emits k (value,
+// token) candidates per row instead of 4 * Gp logits, and k_topk_merge picks the row's top k from the n_wg * k
+// candidates (the top k of a union is the top k of the parts' top k, so the result is exact).  The logits
+// themselves go to global memory only if the caller wants them.
+//   cand_v / cand_i: [M rows of this launch][n_wg][k]
+// =====================================================================================================
+constexpr int LMTK_NPT = 4;                      // logits per lane in the selection: a workgroup owns at most 256 rows
+
+template <typename T, int M>
+__global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, int Kd, const float *x, int m_valid, int Gp,
+                                                            int k, float *logits, float *cand_v, int *cand_i) {
+  extern __shared__ __align__(16) float smem[];
+  constexpr int CH = XLayout<T>::CH;
+  const int nC = (Kd + CH - 1) / CH;
+  float *xs = smem;
+  const int RP = Gp * GV_R;                      // vocabulary rows of a workgroup
+  float *lg = smem + (size_t)M * nC * CH;        // [M][RP]
+  load_x_plain<T, M>(xs, x, Kd, m_valid, Kd, nC);
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int G = (V + GV_R - 1) / GV_R;
+  const int g0 = blockIdx.x * Gp, g1 = min(g0 + Gp, G);
+  for (int g = g0 + wave; g < g1; g += 4) {
+    const T *rows[GV_R];
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = W + (size_t)min(g * GV_R + r, V - 1) * Kd;
+    float acc[GV_R][M];
+    zero_acc<M>(acc);
+    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    if (lane == 0) {
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) {
+        const int n = g * GV_R + r;
+        #pragma unroll
+        for (int m = 0; m < M; ++m) {
+          lg[m * RP + (g - g0) * GV_R + r] = acc[r][m];
+          if (logits && n < V && m < m_valid) logits[(size_t)m * V + n] = acc[r][m];
+        }
+      }
+    }
+  }
+  __syncthreads();
+  const int n_live = min((g1 - g0) * GV_R, V - g0 * GV_R);       // this workgroup's rows inside the vocabulary
+  for (int m = wave; m < m_valid; m += 4) {
+    float xv[LMTK_NPT]; int id[LMTK_NPT];
+    #pragma unroll
+    for (int j = 0; j < LMTK_NPT; ++j) {
+      const int e = j * WAVE + lane;
+      id[j] = (e < n_live) ? g0 * GV_R + e : V;
+      xv[j] = lg[m * RP + min(e, RP - 1)];
+    }
+    const size_t o = ((size_t)m * gridDim.x + blockIdx.x) * k;
+    wave_select<LMTK_NPT>(xv, id, k, V, cand_v + o, cand_i + o);
+  }
+}
+
 // ---- host launchers ---------------------------------------------------------------------------------
 static inline int gv_grid(int groups, int cap = 1024) {
   int g = (groups + 3) / 4;
@@ -467,9 +526,10 @@ template <typename T, typename Kern> static hipError_t gv_set_smem(Kern kern, si
   return hipSuccess;
 }
 
-// Rows per launch: the activation rows of a launch sit in LDS as float32, so a call with more rows than
-// fit (wide models with batch > 1) is served in several launches over row ranges; every launch then
-// streams the weights again.  Returns 0 if not even one row fits.
+// Rows per launch: the activation rows of a launch sit in LDS as float32 and a wave keeps at most 8 rows of
+// accumulators, so a call with more rows than that (catch-up positions of several sequences), or more than fit
+// in LDS (wide models), is served in several launches over row ranges; every launch then streams the weights
+// again.  Returns 0 if not even one row fits.
 static inline int gv_rows_per_launch(int M, size_t bytes_per_row, size_t extra) {
   static const int sizes[] = {8, 5, 4, 2, 1};       // the instantiated row counts
   for (int mm : sizes)
@@ -480,7 +540,7 @@ static inline int gv_rows_per_launch(int M, size_t bytes_per_row, size_t extra) 
 template <typename T>
 hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const void *embed, const int32_t *tok,
                             int vocab, int d, int M, float *out, uint32_t *dev_status) {
-  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  if (M < 1 || d % 8) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, 2 * d), 0);
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
@@ -501,7 +561,7 @@ template <typename T>
 hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int n_heads, int d_h, int M,
                           float eps, float theta, const int32_t *sal_len, int max_kv, void *kv_stage, float *qbuf,
                           uint32_t *dev_status, int R, const int32_t *n_valid) {
-  if (M < 1 || M > 8 || d % 8 || d_h % 4) return hipErrorInvalidValue;
+  if (M < 1 || d % 8 || d_h % 4) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 16);
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
@@ -522,7 +582,7 @@ hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x
 template <typename T>
 hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const void *w2, int n_seg, int seg_rows, int Kd,
                          const float *x, int ldx, int M, const float *res, float *o0, float *o1, float *o2, int ldo) {
-  if (M < 1 || M > 8 || Kd % 8) return hipErrorInvalidValue;
+  if (M < 1 || Kd % 8) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd), 0);
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
@@ -544,7 +604,7 @@ hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const v
 template <typename T>
 hipError_t launch_gate_up(hipStream_t st, const amph_layer_w &lw, const float *x, int d, int f, int M, float eps,
                           float *act) {
-  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  if (M < 1 || d % 8) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 16);
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
@@ -564,7 +624,7 @@ hipError_t launch_gate_up(hipStream_t st, const amph_layer_w &lw, const float *x
 template <typename T>
 hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, const float *h1, const float *h2, int d,
                            int K, int M, float *Hp) {
-  if (M < 1 || M > 8 || d % 8) return hipErrorInvalidValue;
+  if (M < 1 || d % 8) return hipErrorInvalidValue;
   const int mc = gv_rows_per_launch(M, 2 * gv_xs_bytes<T>(1, d), 0);
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
@@ -581,6 +641,48 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
   return hipGetLastError();
 }
 
+// Workgroups of the fused LM head for one launch of m rows: as many as stay resident at once (the activation rows
+// of a launch sit in LDS), at most LMTK_MAX_WG, each owning at most 64 * LMTK_NPT vocabulary rows.
+template <typename T> static inline void lmtk_shape(int V, int Kd, int m, int *n_wg, int *Gp) {
+  const int G = (V + GV_R - 1) / GV_R;
+  const size_t sm = gv_xs_bytes<T>(m, Kd);
+  int per_cu = (int)((160 * 1024) / (sm + 4096));
+  per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+  int want = std::min(std::min(G, 256 * per_cu), LMTK_MAX_WG);
+  int gp = (G + want - 1) / want;
+  *Gp = gp;
+  *n_wg = (G + gp - 1) / gp;
+}
+
+template <typename T>
+hipError_t launch_lmhead_cands(hipStream_t st, const void *W, int V, int Kd, const float *x, int M, int k, float *logits,
+                               float *ws, int *n_cand) {
+  if (M < 1 || Kd % 8 || k < 1 || k > AMPH_MAX_TOPK || k > V) return hipErrorInvalidValue;
+  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd), 8 * 64 * LMTK_NPT * sizeof(float));
+  if (mc < 1) return hipErrorInvalidValue;
+  // every launch uses the shape of a full launch of mc rows, so that all rows have the same number of candidates
+  int n_wg = 0, Gp = 0;
+  lmtk_shape<T>(V, Kd, mc > 4 ? 8 : mc, &n_wg, &Gp);
+  if (Gp * GV_R > 64 * LMTK_NPT) return hipErrorInvalidValue;
+  float *cand_v = ws;
+  int *cand_i = reinterpret_cast<int *>(ws + (size_t)M * n_wg * k);
+  for (int m0 = 0; m0 < M; m0 += mc) {
+    const int m = std::min(mc, M - m0);
+    hipError_t e = hipSuccess;
+    GV_DISPATCH_M(m, {
+      const size_t sm = gv_xs_bytes<T>(MM, Kd) + (size_t)MM * Gp * GV_R * sizeof(float);
+      e = gv_set_smem<T>(k_lmhead_topk<T, MM>, sm);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((k_lmhead_topk<T, MM>), dim3(n_wg), dim3(GV_THREADS), sm, st, (const T *)W, V, Kd, x + (size_t)m0 * Kd, m, Gp,
+                         k, logits ? logits + (size_t)m0 * V : nullptr, cand_v + (size_t)m0 * n_wg * k, cand_i + (size_t)m0 * n_wg * k);
+    });
+  }
+  *n_cand = n_wg * k;
+  return hipGetLastError();
+}
+
+size_t lmtk_ws_floats(int rows, int k) { return 2 * (size_t)rows * LMTK_MAX_WG * k; }
+
 #define INSTANTIATE(T)                                                                                                   \
   template hipError_t launch_fc_concat<T>(hipStream_t, const void *, const float *, const void *, const int32_t *, int, \
                                           int, int, float *, uint32_t *);                                               \
@@ -591,7 +693,9 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
                                        const float *, int, int, const float *, float *, float *, float *, int);         \
   template hipError_t launch_gate_up<T>(hipStream_t, const amph_layer_w &, const float *, int, int, int, float, float *); \
   template hipError_t launch_head_mlp<T>(hipStream_t, const void *, const void *, const float *, const float *, int,    \
-                                         int, int, float *);
+                                         int, int, float *);                                                            \
+  template hipError_t launch_lmhead_cands<T>(hipStream_t, const void *, int, int, const float *, int, int, float *,     \
+                                             float *, int *);
 INSTANTIATE(float)
 INSTANTIATE(bf16_t)
 

@@ -25,6 +25,15 @@ template <typename T>
 hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, const float *h1, const float *h2, int d,
                            int K, int M, float *Hp);
 
+// The shared LM head of Eq. 6 with the top-k candidates taken in its epilogue: every workgroup leaves its k best
+// (value, token) pairs per row in ws (lmtk_ws_floats(M, k) floats: values [M][n_cand], then tokens [M][n_cand]);
+// logits are written only if `logits` is non-NULL.  launch_topk_merge then picks each row's top k.
+constexpr int LMTK_MAX_WG = 1024;
+size_t lmtk_ws_floats(int rows, int k);
+template <typename T>
+hipError_t launch_lmhead_cands(hipStream_t st, const void *W, int V, int Kd, const float *x, int M, int k, float *logits,
+                               float *ws, int *n_cand);
+
 // ---- small.hip (attention of the draft path, top-k, tree, accept, norms) ----
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
@@ -34,7 +43,12 @@ hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, cons
 // ws: topk_ws_floats(rows, V, k) floats of scratch for the per-wave candidates
 size_t topk_ws_floats(int rows, int V, int k);
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, float *ws);
+                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, int advance_limit,
+                            float *ws);   // advance[i] += advance_each ? advance_each[i] : advance_by where the sum stays <= advance_limit
+// top-k of n_cand (value, token) candidates per row (cand_i < 0: no candidate), one workgroup per row
+hipError_t launch_topk_merge(hipStream_t st, const float *cand_v, const int *cand_i, int rows, int n_cand, int V, int k,
+                             int32_t *idx, float *val, int32_t *advance, int n_advance, int advance_by,
+                             const int32_t *advance_each, int advance_limit);
 hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws);
 hipError_t launch_tree_build(hipStream_t st, const int32_t *depth, const int32_t *rank, int T, int B, int K, int topk,
                              const int32_t *root_tok, const int32_t *topk_idx, const int32_t *kv_len, int32_t *tree_tok,
@@ -54,6 +68,10 @@ hipError_t launch_commit(hipStream_t st, void *k_caches, void *v_caches, int n_l
                          int T_nodes, int d, int K, int32_t *kv_len, const int32_t *accept_len, const int32_t *accept_path,
                          const int32_t *next_tok, const int32_t *tree_tok, const float *hidden, float *h_new, int32_t *tok_new,
                          int32_t *n_new);
+// n_caches row-major [max_kv, d_h] caches <-> their step-tiled storage; a NULL source skips keys or values
+template <typename T>
+hipError_t launch_kv_layout(hipStream_t st, const void *k_src, const void *v_src, void *k_dst, void *v_dst, int n_caches,
+                            int max_kv, int d_h, bool to_tiled);
 hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, int d, const int32_t *n_valid, float *out);
 // x[m] (+)= sum_s slabs[s][m] (or x[m] = embed[tok[m]] when tok != NULL); xn[m] = RMSNorm(x[m]) * g as T;
 // hidden_out (float32, optional) receives the same normalised rows.  xn_tiles != 0: xn is written in the tiled
@@ -121,6 +139,8 @@ struct VerifyArgs {
   int kernel;       // -1: chosen by shape; 0: operands through registers; 1: operands through an LDS ring
 };
 size_t verify_ws_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes);
+// floats of key-split partials one call writes with the given kernel choice (VerifyArgs::kernel); 0 without key splits
+size_t verify_partials_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes, int kernel);
 template <typename T> hipError_t launch_verify_attn(hipStream_t st, const VerifyArgs &a);
 
 }  // namespace amph

@@ -2,6 +2,7 @@
 // (Eq. 1), the K x K bi-directional attention of Eq. 5, per-row top-k / argmax (Eq. 6), candidate-tree
 // construction, greedy acceptance, and the row-wise RMSNorm (+ partial-sum fold) of the target path.
 #include "kernels.h"
+#include <algorithm>
 
 namespace amph {
 
@@ -190,38 +191,11 @@ hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, cons
 constexpr int TK_NPT = 8, TK_CHUNK = TK_NPT * WAVE;      // 512 logits per wave
 constexpr int TK_MAXC = 32;                              // pass 2: candidates per lane
 
-__device__ __forceinline__ bool better(float v1, int i1, float v2, int i2) {
-  return (v1 > v2) || (v1 == v2 && i1 < i2);
-}
-
-// Select k times from NPT per-lane (value, index) pairs spread over a wave.  Lane 0 writes the results.
-template <int NPT>
-__device__ __forceinline__ void wave_select(float (&x)[NPT], int (&id)[NPT], int k, int none, float *out_v, int *out_i) {
-  const float NEG_INF = -__builtin_huge_valf();
-  const int lane = threadIdx.x & 63;
-  float bv = NEG_INF; int bi = none, bj = -1;
-  #pragma unroll
-  for (int j = 0; j < NPT; ++j)
-    if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
-  for (int r = 0; r < k; ++r) {
-    float wv = bv; int wi = bi;
-    #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      const float ov = __shfl_xor(wv, off, WAVE);
-      const int oi = __shfl_xor(wi, off, WAVE);
-      if (better(ov, oi, wv, wi)) { wv = ov; wi = oi; }
-    }
-    if (lane == 0) { out_v[r] = wv; out_i[r] = (wi == none) ? -1 : wi; }
-    if (wi != none && wi == bi) {              // this lane owned the winner: retire it and rescan
-      bv = NEG_INF; bi = none;
-      const int gone = bj; bj = -1;
-      #pragma unroll
-      for (int j = 0; j < NPT; ++j) {
-        if (j == gone) id[j] = none;
-        if (id[j] != none && better(x[j], id[j], bv, bi)) { bv = x[j]; bi = id[j]; bj = j; }
-      }
-    }
-  }
+// Cache length of element i after its new rows: advanced only when every new row fitted (the kernels that write
+// the rows skipped those past the limit and raised the overflow flag; the length then stays where it was).
+__device__ __forceinline__ void advance_one(int32_t *len, int i, int by, int limit) {
+  const int v = len[i];
+  if (v >= 0 && by >= 0 && v + by <= limit) len[i] = v + by;
 }
 
 __global__ __launch_bounds__(256) void k_topk_pass1(const float *logits, int V, int k, int chunks_per_row, float *cand_v,
@@ -243,7 +217,7 @@ __global__ __launch_bounds__(256) void k_topk_pass1(const float *logits, int V, 
 
 __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const int *cand_i, int n_cand, int V, int k,
                                                    int32_t *idx, float *val, int32_t *advance, int n_advance,
-                                                   int advance_by, const int32_t *advance_each) {
+                                                   int advance_by, const int32_t *advance_each, int advance_limit) {
   const int row = blockIdx.x, lane = threadIdx.x;
   float x[TK_MAXC]; int id[TK_MAXC];
   #pragma unroll
@@ -264,7 +238,7 @@ __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const in
     if (val) val[(size_t)row * k + lane] = sv[lane];
   }
   if (row == 0 && advance)
-    for (int i = lane; i < n_advance; i += WAVE) advance[i] += advance_each ? advance_each[i] : advance_by;
+    for (int i = lane; i < n_advance; i += WAVE) advance_one(advance, i, advance_each ? advance_each[i] : advance_by, advance_limit);
 }
 
 // One workgroup of 1024 threads per row for vocabularies up to 65536: every thread keeps NPT logits (element
@@ -274,7 +248,7 @@ __global__ __launch_bounds__(64) void k_topk_pass2(const float *cand_v, const in
 template <int NPT>
 __global__ __launch_bounds__(1024) void k_topk_row(const float *logits, int V, int k, int32_t *idx, float *val,
                                                    int32_t *advance, int n_advance, int advance_by,
-                                                   const int32_t *advance_each) {
+                                                   const int32_t *advance_each, int advance_limit) {
   __shared__ float sm_v[16];
   __shared__ int sm_i[16];
   const float NEG_INF = -__builtin_huge_valf();
@@ -328,7 +302,62 @@ __global__ __launch_bounds__(1024) void k_topk_row(const float *logits, int V, i
     __syncthreads();                                       // the wave winners are rewritten in the next round
   }
   if (row == 0 && advance)
-    for (int i = tid; i < n_advance; i += 1024) advance[i] += advance_each ? advance_each[i] : advance_by;
+    for (int i = tid; i < n_advance; i += 1024) advance_one(advance, i, advance_each ? advance_each[i] : advance_by, advance_limit);
+}
+
+// Top-k of the candidates the fused LM head left: one 1024-thread workgroup per row.  Every wave selects the top k
+// of its share (NPT candidates per lane), the 16 x k survivors go through LDS, and the first wave selects among them.
+template <int NPT>
+__global__ __launch_bounds__(1024) void k_topk_merge(const float *cand_v, const int *cand_i, int n_cand, int V, int k,
+                                                     int32_t *idx, float *val, int32_t *advance, int n_advance, int advance_by,
+                                                     const int32_t *advance_each, int advance_limit) {
+  __shared__ float sv[16 * AMPH_MAX_TOPK];
+  __shared__ int si[16 * AMPH_MAX_TOPK];
+  __shared__ float fv[AMPH_MAX_TOPK];
+  __shared__ int fi[AMPH_MAX_TOPK];
+  const int row = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const float *cv = cand_v + (size_t)row * n_cand;
+  const int *ci = cand_i + (size_t)row * n_cand;
+  float x[NPT]; int id[NPT];
+  #pragma unroll
+  for (int j = 0; j < NPT; ++j) {                          // unconditional loads from clamped addresses
+    const int c = j * 1024 + tid, cc = min(c, n_cand - 1);
+    const int t = ci[cc];
+    x[j] = cv[cc];
+    id[j] = (c < n_cand && t >= 0 && t < V) ? t : V;
+  }
+  wave_select<NPT>(x, id, k, V, sv + wave * k, si + wave * k);
+  __syncthreads();
+  if (wave == 0) {
+    constexpr int NP2 = (16 * AMPH_MAX_TOPK) / WAVE;       // 4
+    float y[NP2]; int jd[NP2];
+    #pragma unroll
+    for (int j = 0; j < NP2; ++j) {
+      const int c = j * WAVE + lane, cc = min(c, 16 * k - 1);
+      y[j] = sv[cc];
+      jd[j] = (c < 16 * k && si[cc] >= 0) ? si[cc] : V;
+    }
+    wave_select<NP2>(y, jd, k, V, fv, fi);
+  }
+  __syncthreads();
+  if (tid < k) {
+    if (idx) idx[(size_t)row * k + tid] = fi[tid];
+    if (val) val[(size_t)row * k + tid] = fv[tid];
+  }
+  if (row == 0 && advance)
+    for (int i = tid; i < n_advance; i += 1024) advance_one(advance, i, advance_each ? advance_each[i] : advance_by, advance_limit);
+}
+
+hipError_t launch_topk_merge(hipStream_t st, const float *cand_v, const int *cand_i, int rows, int n_cand, int V, int k,
+                             int32_t *idx, float *val, int32_t *advance, int n_advance, int advance_by,
+                             const int32_t *advance_each, int advance_limit) {
+  if (rows < 1 || n_cand < 1 || k < 1 || k > AMPH_MAX_TOPK || n_cand > 16 * 1024) return hipErrorInvalidValue;
+  #define TM_LAUNCH(N) hipLaunchKernelGGL((k_topk_merge<N>), dim3(rows), dim3(1024), 0, st, cand_v, cand_i, n_cand, V, k, idx, val, \
+                                          advance, n_advance, advance_by, advance_each, advance_limit)
+  if (n_cand <= 1024) TM_LAUNCH(1); else if (n_cand <= 2048) TM_LAUNCH(2); else if (n_cand <= 4096) TM_LAUNCH(4);
+  else if (n_cand <= 8192) TM_LAUNCH(8); else TM_LAUNCH(16);
+  #undef TM_LAUNCH
+  return hipGetLastError();
 }
 
 size_t topk_ws_floats(int rows, int V, int k) {
@@ -337,11 +366,12 @@ size_t topk_ws_floats(int rows, int V, int k) {
 }
 
 hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V, int k, int32_t *idx, float *val,
-                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, float *ws) {
+                            int32_t *advance, int n_advance, int advance_by, const int32_t *advance_each, int advance_limit,
+                            float *ws) {
   if (rows < 1 || V < 1 || k < 1 || k > V || k > AMPH_MAX_TOPK) return hipErrorInvalidValue;
   if (V <= 65536) {
     #define TK_ROW(N) hipLaunchKernelGGL((k_topk_row<N>), dim3(rows), dim3(1024), 0, st, logits, V, k, idx, val, advance, \
-                                         n_advance, advance_by, advance_each)
+                                         n_advance, advance_by, advance_each, advance_limit)
     if (V <= 8192) TK_ROW(8); else if (V <= 16384) TK_ROW(16); else if (V <= 32768) TK_ROW(32); else TK_ROW(64);
     #undef TK_ROW
     return hipGetLastError();
@@ -353,12 +383,12 @@ hipError_t launch_topk_rows(hipStream_t st, const float *logits, int rows, int V
   int *cand_i = reinterpret_cast<int *>(ws + (size_t)rows * n_cand);
   hipLaunchKernelGGL(k_topk_pass1, dim3((chunks + 3) / 4, rows), dim3(256), 0, st, logits, V, k, chunks, cand_v, cand_i);
   hipLaunchKernelGGL(k_topk_pass2, dim3(rows), dim3(64), 0, st, cand_v, cand_i, n_cand, V, k, idx, val, advance, n_advance,
-                     advance_by, advance_each);
+                     advance_by, advance_each, advance_limit);
   return hipGetLastError();
 }
 
 hipError_t launch_row_argmax(hipStream_t st, const float *logits, int rows, int V, int32_t *out, float *ws) {
-  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0, nullptr, ws);
+  return launch_topk_rows(st, logits, rows, V, 1, out, nullptr, nullptr, 0, 0, nullptr, 0, ws);
 }
 
 // =====================================================================================================
@@ -715,6 +745,54 @@ hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, i
   hipLaunchKernelGGL(k_gather_rows, dim3(B), dim3(256), 0, st, rows, R, d, n_valid, out);
   return hipGetLastError();
 }
+
+// =====================================================================================================
+// Row-major [max_kv, d_h] caches <-> the step-tiled storage of the verification attention (formulas: header of
+// the C ABI, k_tiled_index / v_tiled_index).  One thread moves 4 adjacent dims of one row: in the key layout they
+// stay adjacent (inside one 64-byte piece); in the value layout they are 4 single elements.  grid = (chunks of
+// 256 items, caches); to_tiled = false runs the same index map backwards.
+// =====================================================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void k_kv_layout(const T *k_src, const T *v_src, T *k_dst, T *v_dst, int max_kv, int d_h,
+                                                   bool to_tiled) {
+  const size_t head = (size_t)blockIdx.y * (size_t)max_kv * d_h;
+  const int q = d_h / 4;
+  for (int item = blockIdx.x * 256 + threadIdx.x; item < max_kv * q; item += gridDim.x * 256) {
+    const int row = item / q, c = (item % q) * 4;
+    const size_t rm = head + (size_t)row * d_h + c;
+    if (k_src) {
+      const size_t tl = head + k_tiled_index<T>(row, c, d_h);
+      float f[4];
+      load4<T>(k_src + (to_tiled ? rm : tl), f);              // (a widening to float and back is exact for both types)
+      store4<T>(k_dst + (to_tiled ? tl : rm), f);
+    }
+    if (v_src) {
+      #pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t tl = head + v_tiled_index<T>(row, c + j, d_h);
+        if (to_tiled) v_dst[tl] = v_src[rm + j]; else v_dst[rm + j] = v_src[tl];
+      }
+    }
+  }
+}
+
+template <typename T>
+hipError_t launch_kv_layout(hipStream_t st, const void *k_src, const void *v_src, void *k_dst, void *v_dst, int n_caches,
+                            int max_kv, int d_h, bool to_tiled) {
+  if (n_caches < 1 || n_caches > 65535 * 16 || max_kv % 32 || d_h % 16) return hipErrorInvalidValue;
+  const int items = max_kv * (d_h / 4);
+  const unsigned chunks = (unsigned)std::min((items + 255) / 256, 64);
+  for (int c0 = 0; c0 < n_caches; c0 += 65535) {           // grid.y is limited to 65535
+    const int nc = std::min(65535, n_caches - c0);
+    const size_t off = (size_t)c0 * max_kv * d_h;
+    hipLaunchKernelGGL((k_kv_layout<T>), dim3(chunks, nc), dim3(256), 0, st, k_src ? (const T *)k_src + off : nullptr,
+                       v_src ? (const T *)v_src + off : nullptr, k_dst ? (T *)k_dst + off : nullptr,
+                       v_dst ? (T *)v_dst + off : nullptr, max_kv, d_h, to_tiled);
+  }
+  return hipGetLastError();
+}
+template hipError_t launch_kv_layout<float>(hipStream_t, const void *, const void *, void *, void *, int, int, int, bool);
+template hipError_t launch_kv_layout<bf16_t>(hipStream_t, const void *, const void *, void *, void *, int, int, int, bool);
 
 // =====================================================================================================
 // Row-wise RMSNorm for the target path, fused with the fold of the previous GEMM's partial slabs:

@@ -663,8 +663,14 @@ static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int
   return p;
 }
 
+// floats of key-split partials a plan writes: none without key splits (the kernels then write the output directly)
 static size_t va_plan_floats(const VaPlan &p, int B, int n_heads, int d_h) {
+  if (p.S <= 1) return 0;
   return (size_t)B * p.groups * n_heads * p.S * ((size_t)p.nq * d_h + 2 * p.nq);
+}
+
+size_t verify_partials_floats(int B, int T, int n_heads, int d_h, int max_kv, int elem_bytes, int kernel) {
+  return va_plan_floats(va_plan(B, T, n_heads, max_kv, elem_bytes, kernel), B, n_heads, d_h);
 }
 
 // partial results of the larger of the two kernels' plans: the choice may be overridden per call

@@ -41,53 +41,29 @@ def draft_to_device(dw: Dict[str, object], device="cuda:0") -> Dict[str, object]
     return out
 
 
-def _step(t: torch.Tensor):
-    """(rows per key step, elements per 64 bytes): 32 for bf16, 16 for float32 (both numbers coincide)."""
-    return 64 // t.element_size()
+def _kv_check(ctx, t: torch.Tensor) -> int:
+    """Number of [max_kv, head_dim] caches in t (all leading dimensions); shape and type must be the context's."""
+    assert t.is_contiguous() and t.shape[-2] == ctx.cfg.max_kv and t.shape[-1] == ctx.cfg.head_dim, tuple(t.shape)
+    assert t.dtype == (torch.bfloat16 if ctx.cfg.dtype == AMPH_BF16 else torch.float32)
+    return t.numel() // (t.shape[-2] * t.shape[-1])
 
 
-def keys_to_tiled(k_rows: torch.Tensor) -> torch.Tensor:
-    """[..., rows, head_dim] -> the step-tiled key-cache layout of amph_verify_attn (same shape, permuted
-    storage).  rows must be a multiple of the key step."""
-    P = _step(k_rows)                     # rows per step == elements per 64-byte piece
-    nt = P // 16                          # fragments of 16 rows per step
-    *lead, R, dh = k_rows.shape
-    assert R % P == 0 and dh % P == 0
-    # row = s*P + grp*(4*nt) + t*4 + lo  (slot i = grp*4 + lo);  dim = ds*P + w
-    x = k_rows.reshape(*lead, R // P, 4, nt, 4, dh // P, P)
-    n = len(lead)
-    x = x.permute(*range(n), n, n + 2, n + 4, n + 1, n + 3, n + 5)      # [s, t, ds, grp, lo, w]
-    return x.contiguous().reshape(*lead, R, dh)
+def pack_kv(ctx, k_rows: torch.Tensor, v_rows: torch.Tensor):
+    """Row-major caches [..., max_kv, head_dim] -> their step-tiled storage (amph_pack_kv); same shapes."""
+    k_t, v_t = torch.empty_like(k_rows), torch.empty_like(v_rows)
+    n = _kv_check(ctx, k_rows)
+    assert _kv_check(ctx, v_rows) == n
+    ctx.amph_pack_kv(k_rows, v_rows, k_t, v_t, n)
+    return k_t, v_t
 
 
-def tiled_to_keys(k_tiled: torch.Tensor) -> torch.Tensor:
-    P = _step(k_tiled)
-    nt = P // 16
-    *lead, R, dh = k_tiled.shape
-    x = k_tiled.reshape(*lead, R // P, nt, dh // P, 4, 4, P)
-    n = len(lead)
-    x = x.permute(*range(n), n, n + 3, n + 1, n + 4, n + 2, n + 5)      # [s, grp, t, lo, ds, w]
-    return x.contiguous().reshape(*lead, R, dh)
-
-
-def values_to_tiled(v_rows: torch.Tensor) -> torch.Tensor:
-    """[..., rows, head_dim] -> the step-tiled value-cache layout of amph_verify_attn."""
-    P = _step(v_rows)
-    *lead, R, dh = v_rows.shape
-    assert R % P == 0 and dh % 16 == 0
-    x = v_rows.reshape(*lead, R // P, P, dh // 16, 16)                  # [s, kk, db, r]
-    n = len(lead)
-    x = x.permute(*range(n), n, n + 2, n + 3, n + 1)                    # [s, db, r, kk]
-    return x.contiguous().reshape(*lead, R, dh)
-
-
-def tiled_to_values(v_tiled: torch.Tensor) -> torch.Tensor:
-    P = _step(v_tiled)
-    *lead, R, dh = v_tiled.shape
-    x = v_tiled.reshape(*lead, R // P, dh // 16, 16, P)
-    n = len(lead)
-    x = x.permute(*range(n), n, n + 3, n + 1, n + 2)                    # [s, kk, db, r]
-    return x.contiguous().reshape(*lead, R, dh)
+def unpack_kv(ctx, k_tiled: torch.Tensor, v_tiled: torch.Tensor):
+    """Step-tiled caches -> row-major [..., max_kv, head_dim] (amph_unpack_kv)."""
+    k_r, v_r = torch.empty_like(k_tiled), torch.empty_like(v_tiled)
+    n = _kv_check(ctx, k_tiled)
+    assert _kv_check(ctx, v_tiled) == n
+    ctx.amph_unpack_kv(k_tiled, v_tiled, k_r, v_r, n)
+    return k_r, v_r
 
 
 def pack_layer(ctx, lw: Dict[str, torch.Tensor]):

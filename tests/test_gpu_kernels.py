@@ -85,7 +85,7 @@ def verify_case(cfg, T, caps, L, B_=1, seed=21, heads=None, lens=None, kernel=-1
     for b in range(B_):                                   # element b uses rows [0, lens[b] + T) of its random rows
         k_rows[b, :, :lens[b] + T] = cfg_tensor_to_dev(k)[b, :, :lens[b] + T]
         v_rows[b, :, :lens[b] + T] = cfg_tensor_to_dev(v)[b, :, :lens[b] + T]
-    kc, vc = D.keys_to_tiled(k_rows), D.values_to_tiled(v_rows)
+    kc, vc = D.pack_kv(ctx, k_rows, v_rows)
     out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
     kv_len = i32_to_dev(np.asarray(lens))
     ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), kc, vc, kv_len, out)
@@ -314,8 +314,8 @@ def verify_case_paths(cfg, paths, K, topk, L, B_, kernel, seed=23):
     k_rows[:, :, :L + T] = cfg_tensor_to_dev(k)
     v_rows[:, :, :L + T] = cfg_tensor_to_dev(v)
     out = torch.full((B_, T, n_h, d_h), float("nan"), dtype=tdt, device=DEV)
-    ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), D.keys_to_tiled(k_rows), D.values_to_tiled(v_rows),
-                         i32_to_dev(np.full(B_, L)), out)
+    kc, vc = D.pack_kv(ctx, k_rows, v_rows)
+    ctx.amph_verify_attn(tree, cfg_tensor_to_dev(q), kc, vc, i32_to_dev(np.full(B_, L)), out)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
     got = np_of(out)
@@ -355,3 +355,33 @@ def test_accept_from_logits_takes_argmax_with_lowest_id_on_ties():
     assert oa == 4
     assert (int(a_len[0]), int(best[0]), int(nxt[0])) == (oa, obest, onxt)
     np.testing.assert_array_equal(np_of(a_path)[0], opath)
+
+
+# ---------------------------------------------------------------------------- K/V cache layout converters
+@pytest.mark.parametrize("cfg,max_kv,lead", [(si.TINY, 96, (2, 1, 4)), (si.MINI, 160, (3, 2, 4)), (si.V7B, 1088, (1, 1, 32))])
+def test_pack_and_unpack_kv_follow_the_header_formulas(cfg, max_kv, lead):
+    """amph_pack_kv / amph_unpack_kv against the torch-permute reference of the header's byte formulas
+    (tests/layout_ref.py, itself checked against those formulas on the CPU): pure data movement, bit-exact."""
+    import layout_ref as R
+    say(f"pack_kv / unpack_kv {cfg.name} max_kv={max_kv} caches={lead}")
+    ctx = make_ctx(cfg, max_kv=max_kv)
+    tdt = D.torch_dtype(cfg.dtype)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    shape = (*lead, max_kv, cfg.head_dim)
+    k_rows = torch.randn(shape, generator=g).to(tdt).to(DEV)
+    v_rows = torch.randn(shape, generator=g).to(tdt).to(DEV)
+    k_t, v_t = D.pack_kv(ctx, k_rows, v_rows)
+    torch.cuda.synchronize()
+    assert torch.equal(k_t, R.keys_to_tiled(k_rows)) and torch.equal(v_t, R.values_to_tiled(v_rows))
+    k_back, v_back = D.unpack_kv(ctx, k_t, v_t)
+    torch.cuda.synchronize()
+    assert torch.equal(k_back, k_rows) and torch.equal(v_back, v_rows)
+    # keys alone / values alone leave the other destination untouched
+    only_k = torch.zeros_like(k_rows)
+    ctx.amph_pack_kv(k_rows, None, only_k, None, k_rows.numel() // (max_kv * cfg.head_dim))
+    torch.cuda.synchronize()
+    assert torch.equal(only_k, k_t)
+    with pytest.raises(B.AmphError):
+        ctx.amph_pack_kv(k_rows, None, None, v_t, 1)          # a destination without its source
+    with pytest.raises(B.AmphError):
+        ctx.amph_pack_kv(k_rows, None, k_rows, None, 1)       # in place

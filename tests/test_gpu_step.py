@@ -9,6 +9,7 @@ from oracle import amphista_oracle as orc
 from paper_2406_13170_amd import binding as B
 from paper_2406_13170_amd import device as D
 
+import bf16_noise_model as nm
 from gpu_common import (DEV, TOL, assert_rows_close, cfg_tensor_to_dev, draft_f32, f32_layers, f32_to_dev, i32_to_dev,
                         make_ctx, np_of, say, topk_consistent)
 
@@ -204,7 +205,8 @@ def test_draft_is_deterministic_and_flags_overflow():
 
 
 # ---------------------------------------------------------------------------- amph_target_forward (A7-A9)
-def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False, oracle=True, tiled_keys=None):
+def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False, oracle=True, tiled_keys=None, model=False,
+               keep_all=False):
     cfg = si.with_(cfg, batch=Bsz, K=len(caps), topk=min(16, max(caps)))
     n_h, d_h, d, V = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab
     max_kv = (L + T + 31) // 32 * 32
@@ -224,7 +226,7 @@ def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False,
     for li in range(n_layers):
         k_caches[li, :, :, :L] = cfg_tensor_to_dev(kcs[li])
         v_caches[li, :, :, :L] = cfg_tensor_to_dev(vcs[li])
-    k_caches, v_caches = D.keys_to_tiled(k_caches), D.values_to_tiled(v_caches)      # rows -> step-tiled storage
+    k_caches, v_caches = D.pack_kv(ctx, k_caches, v_caches)      # rows -> step-tiled storage
     tok = si.tokens(cfg, seed, "tree.tok", (Bsz, T))
     pos = np.stack([L + otree.depth for _ in range(Bsz)]).astype(np.int32)
     hidden = torch.full((Bsz, T, d), float("nan"), dtype=torch.float32, device=DEV)
@@ -249,16 +251,31 @@ def run_target(cfg: si.Config, n_layers, T, caps, L, seed=0, Bsz=1, tiled=False,
                             tiled_structs=tiled_structs, lm_head_tiled=lm_t)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
-    del keep
+    dev = dict(structs=structs, tiled_structs=tiled_structs, lm_t=lm_t, embed_d=embed_d, fn_d=fn_d, lm_d=None if tiled else lm_d,
+               keep=(keep, layers_d))       # what a further pass on the same weights needs (kept alive with the result)
     if not oracle:
         return cfg, None, dict(hidden=np_of(hidden), logits=np_of(logits), tgt=np_of(tgt), k_caches=k_caches,
-                               v_caches=v_caches, L=L, T=T), (ctx, tree, otree)
+                               v_caches=v_caches, L=L, T=T, ctx=ctx, dev=dev), (ctx, tree, otree)
     two = dict(embed=tw["embed"].f32, layers=f32_layers(tw["layers"]), final_norm=tw["final_norm"].f32, lm_head=tw["lm_head"].f32)
     refs = [orc.target_forward(two, tok[b], pos[b], otree.mask, [kcs[li].f32[b] for li in range(n_layers)],
                                [vcs[li].f32[b] for li in range(n_layers)], n_h, cfg.rms_eps, cfg.rope_theta, keep=True)
             for b in range(Bsz)]
+    models = None
+    if model:      # the oracle with its values rounded where the device stores bf16 (tests/bf16_noise_model.py)
+        models = []
+        for b in range(Bsz):
+            m = nm.target_forward(two, tok[b], pos[b], otree.mask, [kcs[li].f32[b] for li in range(n_layers)],
+                                  [vcs[li].f32[b] for li in range(n_layers)], n_h, cfg.rms_eps, cfg.rope_theta, nm.bf16)
+            m["tgt"] = np.array([orc.row_argmax(r) for r in m["logits"]])
+            models.append(m)
+    host = None
+    if keep_all:   # the last layer's host-side weights and cache rows, the final norm and the LM head, as float arrays
+        host = (two["layers"][-1], [x for x in kcs[-1].f32], [x for x in vcs[-1].f32], two["final_norm"], two["lm_head"])
     return cfg, refs, dict(hidden=np_of(hidden), logits=np_of(logits), tgt=np_of(tgt), k_caches=k_caches, v_caches=v_caches,
-                           L=L, T=T), (ctx, tree, otree)
+                           L=L, T=T, ctx=ctx, model=models, dev=dev, host=host), (ctx, tree, otree)
+
+
+HEAD_ROW_SCALE = 1.0      # (head, node) rows of the tree K/V are held to the same bound as whole node rows (worst measured: 1.6e-2 at the 33B width)
 
 
 def check_target(cfg, refs, got, tol_scale=1.0):
@@ -283,14 +300,24 @@ def check_target(cfg, refs, got, tol_scale=1.0):
             # and the GPU's argmax is the exact argmax of the GPU's own logits (ties -> lowest id)
             assert got["tgt"][b, i] == orc.row_argmax(got["logits"][b, i])
         say(f"  b={b} nodes with an oracle top-1/top-2 gap below tolerance: {undecided}/{T}")
-        # tree K/V rows written by every layer at rows [L, L+T)
+        # tree K/V rows written by every layer at rows [L, L+T), read back through amph_unpack_kv.  Two row
+        # definitions: (i) one tree node's whole key (value) vector = one output row of the projection GEMM, held to
+        # the tolerance; (ii) one (head, node) row of d_h values = what the attention consumes.  The absolute error of
+        # a GEMM output does not depend on the head, but a single head's largest value is smaller than the largest of
+        # all n_h heads together, so (ii) reads higher than (i) by that ratio; it still fits the plain tolerance at every
+        # shape tested (HEAD_ROW_SCALE = 1) and its worst value is printed.
+        k_rows, v_rows = D.unpack_kv(got["ctx"], got["k_caches"], got["v_caches"])
+        worst_head = 0.0
         for li, lay in enumerate(r["layers"]):
-            # a row = one tree node's whole key (value) vector, i.e. one output row of the projection GEMM
             per_node = lambda a: np.transpose(a, (1, 0, 2)).reshape(a.shape[1], -1)             # [n_h, T, d_h] -> [T, d]
-            kc = np_of(D.tiled_to_keys(got["k_caches"][li, b])[:, L:L + T])
-            vc = np_of(D.tiled_to_values(got["v_caches"][li, b])[:, L:L + T])
+            per_head = lambda a: a.reshape(-1, a.shape[-1])                                      # [n_h, T, d_h] -> [n_h*T, d_h]
+            kc, vc = np_of(k_rows[li, b][:, L:L + T]), np_of(v_rows[li, b][:, L:L + T])
             assert_rows_close(per_node(kc), per_node(lay["k_new"]), tol, f"layer {li} tree keys")
             assert_rows_close(per_node(vc), per_node(lay["v_new"]), tol, f"layer {li} tree values")
+            wk = assert_rows_close(per_head(kc), per_head(lay["k_new"]), HEAD_ROW_SCALE * tol, f"layer {li} tree keys per head")
+            wv = assert_rows_close(per_head(vc), per_head(lay["v_new"]), HEAD_ROW_SCALE * tol, f"layer {li} tree values per head")
+            worst_head = max(worst_head, wk, wv)
+        say(f"  b={b} worst (head, node) K/V row error {worst_head:.2e} (bound {HEAD_ROW_SCALE * tol:.1e})")
 
 
 @pytest.mark.parametrize("tiled", [False, True], ids=["rowmajor", "tiled"])
@@ -377,31 +404,77 @@ def test_target_forward_vicuna33b_one_layer_batch4(seed):
 
 
 def test_target_forward_vicuna33b_two_layers_batch4():
-    """The same configuration end to end through two layers.  At this width the rounding of the bf16
-    activations between kernels alone (emulated on the CPU: tests/test_bf16_noise_cpu.py, and 1.4e-2 for one
-    layer of this shape) nearly uses up the 2e-2 bound in ONE layer; independent per-layer noise adds in
-    quadrature, so the bound for a chain of n layers is taken as 2e-2 * sqrt(n) here."""
+    """The same configuration end to end through two layers.  At this width the rounding of the bf16 activations
+    between kernels alone (emulated on the CPU: tests/test_bf16_noise_cpu.py, 1.6e-2 for one layer of this shape)
+    nearly uses up the 2e-2 bound in ONE layer and passes it in two.  So the stated 2e-2 is held per layer (the
+    first layer by the one-layer tests above, the second one here, teacher-forced: it gets the oracle's input to
+    it), and the two-layer chain against the exact oracle is bounded by 1.5 x the drift of the oracle with its own
+    values rounded at the device's five rounding points (tests/bf16_noise_model.py) on the same inputs."""
     say("target_forward vicuna33b 2 layers, batch 4 (tiled weights)")
-    cfgx, refs, got, _ = run_target(si.V33B, 2, 96, (10,) * 5, 4096, Bsz=4, tiled=True)
-    check_target(cfgx, refs, got, tol_scale=2 ** 0.5)
+    T, L, Bsz = 96, 4096, 4
+    cfgx, refs, got, (ctx, tree, otree) = run_target(si.V33B, 2, T, (10,) * 5, L, Bsz=Bsz, tiled=True, model=True, keep_all=True)
+    tol = TOL[cfgx.dtype]
+    for b, (r, m) in enumerate(zip(refs, got["model"])):
+        d_h, d_l = nm.worst_row(m["hidden"], r["hidden"]), nm.worst_row(m["logits"], r["logits"])
+        e_h, e_l = nm.worst_row(got["hidden"][b], r["hidden"]), nm.worst_row(got["logits"][b], r["logits"])
+        say(f"  b={b} two-layer chain against the exact oracle: hidden {e_h:.2e}, logits {e_l:.2e}; the rounding model's own drift: "
+            f"{d_h:.2e}, {d_l:.2e}")
+        assert e_h <= 1.5 * d_h and e_l <= 1.5 * d_l
+    # the second layer alone on the oracle's first-layer output (rounded to bf16, as both sides then see it)
+    dev = got["dev"]
+    n_h, d = cfgx.n_heads, cfgx.d_model
+    x1 = np.stack([nm.bf16(r["layers"][0]["x"]) for r in refs])                     # [B, T, d]
+    x_dev = torch.from_numpy(x1.reshape(Bsz * T, d).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    rows = i32_to_dev(np.arange(Bsz * T).reshape(Bsz, T))
+    pos = i32_to_dev(np.stack([L + otree.depth for _ in range(Bsz)]))
+    hidden = torch.zeros((Bsz, T, d), dtype=torch.float32, device=DEV)
+    logits = torch.zeros((Bsz, T, cfgx.vocab), dtype=torch.float32, device=DEV)
+    tgt = torch.zeros((Bsz, T), dtype=torch.int32, device=DEV)
+    ctx.amph_target_forward(tree, dev["structs"][1:2], x_dev, dev["fn_d"], None, rows, pos, got["k_caches"][1:2], got["v_caches"][1:2],
+                            i32_to_dev(np.full(Bsz, L)), hidden, logits, tgt, tiled_structs=dev["tiled_structs"][1:2],
+                            lm_head_tiled=dev["lm_t"])
+    torch.cuda.synchronize()
+    assert ctx.device_status() == 0
+    lw1, kcs1, vcs1, fn, lm = got["host"]
+    forced = []
+    for b in range(Bsz):
+        o, k_new, v_new, _, _ = orc.decoder_layer_rows(x1[b], lw1, kcs1[b], vcs1[b], list(L + otree.depth), otree.mask, n_h,
+                                                       cfgx.rms_eps, cfgx.rope_theta)
+        hid = orc.rmsnorm(o, fn, cfgx.rms_eps)
+        lg = orc.linear(lm, hid)
+        forced.append(dict(hidden=hid, logits=lg, tgt=np.array([orc.row_argmax(x) for x in lg]), layers=[dict(k_new=k_new, v_new=v_new)]))
+    got2 = dict(hidden=np_of(hidden), logits=np_of(logits), tgt=np_of(tgt), k_caches=got["k_caches"][1:2], v_caches=got["v_caches"][1:2],
+                L=L, T=T, ctx=ctx)
+    say("  second layer alone, teacher-forced, at the plain tolerance:")
+    check_target(cfgx, forced, got2)
 
 
 # ---------------------------------------------------------------------------- one whole step (A1-A10)
-@pytest.mark.parametrize("cfg", [si.TINY, si.MINI])
-def test_full_step_matches_oracle(cfg):
+@pytest.mark.parametrize("cfg,n_layers,tiled", [(si.TINY, None, False), (si.MINI, None, False), (si.V7B, 2, True), (si.V13B, 2, True)],
+                         ids=["tiny", "mini", "vicuna7b-2-layers-tiled", "vicuna13b-2-layers-tiled"])
+def test_full_step_matches_oracle(cfg, n_layers, tiled):
     """amph_draft -> amph_tree_build -> amph_target_forward -> amph_accept on the device, with the
-    integer decisions compared exactly wherever the oracle's own margins are clear."""
+    integer decisions compared exactly wherever the oracle's own margins are clear.  At the 7B and 13B shapes this
+    is the call sequence the bench times (tiled target weights, the draft's own top-k through the tree), at reduced
+    depth; the target's logits are also compared with the oracle run on the tree the device built."""
     say(f"full step {cfg.name}")
     seed = 4
     n_h, d_h, d, V, K, T, L = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab, cfg.K, cfg.T, cfg.kv_len
     max_kv = cfg.max_kv
     ctx = make_ctx(cfg)
-    dw, tw = si.draft_weights(cfg, seed), si.target_weights(cfg, seed)
+    nl = cfg.n_layers if n_layers is None else n_layers
+    dw, tw = si.draft_weights(cfg, seed), si.target_weights(cfg, seed, nl)
     dwd = D.draft_to_device(dw, DEV)
     dstruct = B.Context.draft_struct(dwd)
     layers_d = [D.layer_to_device(lw, DEV) for lw in tw["layers"]]
     structs = [B.Context.layer_struct(l) for l in layers_d]
     fn_d, lm_d = cfg_tensor_to_dev(tw["final_norm"]), cfg_tensor_to_dev(tw["lm_head"])
+    tiled_structs = lm_t = keep = None
+    if tiled:
+        packed = [D.pack_layer(ctx, l) for l in layers_d]
+        tiled_structs, keep = [p[0] for p in packed], [p[1] for p in packed]
+        lm_t = D.pack_lm_head(ctx, lm_d)
+        structs = [B.amph_layer_w(rms1=l["rms1"].data_ptr(), rms2=l["rms2"].data_ptr()) for l in layers_d]
     paths = si.tree_paths(T, cfg.tree_caps)
     tree = B.Tree(paths, K)
     otree = orc.tree_from_paths(paths, K)
@@ -415,7 +488,6 @@ def test_full_step_matches_oracle(cfg):
     for s in range(2):
         sal_kv[s, :, 0, :, :Ls] = cfg_tensor_to_dev(sal_k[s])
         sal_kv[s, :, 1, :, :Ls] = cfg_tensor_to_dev(sal_v[s])
-    nl = cfg.n_layers
     kcs = [si.normal(cfg, seed, f"tkv{li}.k", (1, n_h, L, d_h), 1.0) for li in range(nl)]
     vcs = [si.normal(cfg, seed, f"tkv{li}.v", (1, n_h, L, d_h), 1.0) for li in range(nl)]
     k_caches = torch.zeros((nl, 1, n_h, max_kv, d_h), dtype=tdt, device=DEV)
@@ -423,7 +495,7 @@ def test_full_step_matches_oracle(cfg):
     for li in range(nl):
         k_caches[li, :, :, :L] = cfg_tensor_to_dev(kcs[li])
         v_caches[li, :, :, :L] = cfg_tensor_to_dev(vcs[li])
-    k_caches, v_caches = D.keys_to_tiled(k_caches), D.values_to_tiled(v_caches)
+    k_caches, v_caches = D.pack_kv(ctx, k_caches, v_caches)
     i32 = lambda *shape: torch.full(shape, -9, dtype=torch.int32, device=DEV)
     topk_idx, topk_val = i32(1, K, cfg.topk), torch.zeros((1, K, cfg.topk), dtype=torch.float32, device=DEV)
     tree_tok, tree_pos, tgt = i32(1, T), i32(1, T), i32(1, T)
@@ -431,11 +503,13 @@ def test_full_step_matches_oracle(cfg):
     tok_d, kv_len_d, sal_len_d = i32_to_dev(tok), i32_to_dev([L]), i32_to_dev([Ls])
     ctx.amph_draft(dstruct, f32_to_dev(h), tok_d, sal_kv, sal_len_d, topk_idx, topk_val, None)
     ctx.amph_tree_build(tree, tok_d, topk_idx, kv_len_d, tree_tok, tree_pos)
-    ctx.amph_target_forward(tree, structs, dwd["embed"], fn_d, lm_d, tree_tok, tree_pos, k_caches, v_caches, kv_len_d,
-                            None, None, tgt)
+    t_logits = torch.full((1, T, V), float("nan"), dtype=torch.float32, device=DEV)
+    ctx.amph_target_forward(tree, structs, dwd["embed"], fn_d, None if tiled else lm_d, tree_tok, tree_pos, k_caches, v_caches,
+                            kv_len_d, None, t_logits, tgt, tiled_structs=tiled_structs, lm_head_tiled=lm_t)
     ctx.amph_accept(tree, tree_tok, tgt, None, a_len, a_path, nxt, best)
     torch.cuda.synchronize()
     assert ctx.device_status() == 0
+    del keep
 
     two = dict(embed=tw["embed"].f32, layers=f32_layers(tw["layers"]), final_norm=tw["final_norm"].f32, lm_head=tw["lm_head"].f32)
     o = orc.step(draft_f32(dw), two, otree, h[0], int(tok[0]), [x.f32[0] for x in sal_k], [x.f32[0] for x in sal_v],
@@ -451,6 +525,12 @@ def test_full_step_matches_oracle(cfg):
     e_tok, e_pos = orc.tree_tokens(otree, int(tok[0]), g_topk, L)
     np.testing.assert_array_equal(g_tok, e_tok)
     np.testing.assert_array_equal(g_pos, e_pos)
+    # the target's logits against the oracle run on the tree the device built (equal to the oracle's own tree when
+    # the draft's candidates agree)
+    t_ref = orc.target_forward(two, g_tok, e_pos, otree.mask, [x.f32[0] for x in kcs], [x.f32[0] for x in vcs], n_h,
+                               cfg.rms_eps, cfg.rope_theta)
+    w_t = assert_rows_close(np_of(t_logits)[0], t_ref["logits"], tol, "target logits on the device's own tree")
+    say(f"  target logits on the device's tree: worst row error {w_t:.2e}")
     # acceptance is integer work on the GPU's own target argmax: exact against the oracle's rule
     g_tgt = np_of(tgt)[0]
     ea, epath, enxt, ebest = orc.accept_greedy(otree, g_tok, g_tgt)
@@ -472,37 +552,58 @@ def test_full_step_matches_oracle(cfg):
         say("  top-k differs from the oracle within tolerance (near-ties); end-to-end equality not applicable")
 
 
-def test_planted_drafts_are_fully_accepted_on_the_gpu():
+@pytest.mark.parametrize("cfg,n_layers,T,caps,L,tiled", [
+    (si.TINY, 2, 16, (4, 2, 2, 2), 64, False),
+    (si.V7B, 2, 64, (10,) * 4, 1024, True),
+    (si.V13B, 2, 64, (10,) * 4, 2048, True),
+], ids=["tiny", "vicuna7b-2-layers-tiled", "vicuna13b-2-layers-tiled"])
+def test_planted_drafts_are_fully_accepted_on_the_gpu(cfg, n_layers, T, caps, L, tiled):
     """Invariant: drafts set to the target's argmax along a path are accepted to that path's depth.  The
     tokens are planted depth by depth from the GPU's own target argmax (a node's logits depend only on
-    its ancestors), then one more forward pass must accept the whole path."""
-    say("planted path tiny")
-    cfg = si.TINY
-    cfgx, refs, got, (ctx, tree, otree) = run_target(cfg, 2, 16, (4, 2, 2, 2), 64, seed=9)
-    # rebuild the inputs of run_target to drive further passes
-    seed, T, L, K = 9, 16, 64, 4
-    n_h, d_h, d, V = cfg.n_heads, cfg.head_dim, cfg.d_model, cfg.vocab
-    tw = si.target_weights(cfgx, seed, 2)
-    layers_d = [D.layer_to_device(lw, DEV) for lw in tw["layers"]]
-    structs = [B.Context.layer_struct(l) for l in layers_d]
-    embed_d, fn_d, lm_d = cfg_tensor_to_dev(tw["embed"]), cfg_tensor_to_dev(tw["final_norm"]), cfg_tensor_to_dev(tw["lm_head"])
+    its ancestors), then one more forward pass must accept the whole path: accept_len = K at full width, through
+    the kernels and the launch configuration of the 7B and 13B steps."""
+    say(f"planted path {cfg.name}")
+    seed, K = 9, len(caps)
+    cfgx, _, got, (ctx, tree, otree) = run_target(cfg, n_layers, T, caps, L, seed=seed, tiled=tiled, oracle=False)
+    dev = got["dev"]
     k_caches, v_caches = got["k_caches"], got["v_caches"]
     leaf = [int(n) for n in otree.retrieve[np.argmax((otree.retrieve >= 0).sum(axis=1))] if n >= 0]
+    assert len(leaf) == K + 1
     tok = si.tokens(cfgx, seed, "tree.tok", (1, T)).copy()
     pos = i32_to_dev((L + otree.depth)[None])
     kv_len = i32_to_dev([L])
     tgt = torch.zeros((1, T), dtype=torch.int32, device=DEV)
     a_len, a_path = torch.zeros(1, dtype=torch.int32, device=DEV), torch.zeros((1, K + 1), dtype=torch.int32, device=DEV)
     nxt, best = torch.zeros(1, dtype=torch.int32, device=DEV), torch.zeros(1, dtype=torch.int32, device=DEV)
-    for m in range(1, 5):
-        ctx.amph_target_forward(tree, structs, embed_d, fn_d, lm_d, i32_to_dev(tok), pos, k_caches, v_caches, kv_len, None,
-                                None, tgt)
+
+    def forward(tok_d):
+        ctx.amph_target_forward(tree, dev["structs"], dev["embed_d"], dev["fn_d"], dev["lm_d"], tok_d, pos, k_caches, v_caches,
+                                kv_len, None, None, tgt, tiled_structs=dev["tiled_structs"], lm_head_tiled=dev["lm_t"])
         torch.cuda.synchronize()
+
+    for m in range(1, K + 1):
+        forward(i32_to_dev(tok))
         tok[0, leaf[m]] = int(tgt[0, leaf[m - 1]])
+        # a sibling that happens to carry the same token would be an equally valid accepted node: make it differ
+        for j in range(1, T):
+            if j != leaf[m] and otree.parent[j] == otree.parent[leaf[m]] and tok[0, j] == tok[0, leaf[m]]:
+                tok[0, j] = (tok[0, j] + 1) % cfgx.vocab
     tok_d = i32_to_dev(tok)
-    ctx.amph_target_forward(tree, structs, embed_d, fn_d, lm_d, tok_d, pos, k_caches, v_caches, kv_len, None, None, tgt)
+    forward(tok_d)
     ctx.amph_accept(tree, tok_d, tgt, None, a_len, a_path, nxt, best)
     torch.cuda.synchronize()
-    assert int(a_len[0]) == 4
+    assert ctx.device_status() == 0
+    assert int(a_len[0]) == K
     assert list(np_of(a_path)[0]) == leaf
     assert int(nxt[0]) == int(tgt[0, leaf[-1]])
+    # one wrong token in the middle of the path stops the acceptance there
+    tok[0, leaf[2]] = (tok[0, leaf[2]] + 1) % cfgx.vocab
+    sib = [j for j in range(1, T) if j != leaf[2] and otree.parent[j] == otree.parent[leaf[2]]]
+    for j in sib:                                          # no sibling may pick up the planted token
+        if tok[0, j] == int(tgt[0, leaf[1]]):
+            tok[0, j] = (tok[0, j] + 2) % cfgx.vocab
+    tok_d = i32_to_dev(tok)
+    forward(tok_d)
+    ctx.amph_accept(tree, tok_d, tgt, None, a_len, a_path, nxt, best)
+    torch.cuda.synchronize()
+    assert int(a_len[0]) == 1 and list(np_of(a_path)[0][:2]) == leaf[:2]

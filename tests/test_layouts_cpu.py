@@ -1,9 +1,10 @@
-"""Host-side layout helpers against the formulas that include/amph.h states for the step-tiled K and V
-caches (CPU only: pure data movement)."""
+"""The torch-permute reference of the step-tiled K and V caches (tests/layout_ref.py) against the byte formulas
+that include/amph.h states (CPU only: pure data movement).  The library's own converters are checked against
+the same reference on the GPU (tests/test_gpu_kernels.py)."""
 import pytest
 import torch
 
-from paper_2406_13170_amd import device as D
+import layout_ref as D
 
 
 @pytest.mark.parametrize("dt,E", [(torch.bfloat16, 2), (torch.float32, 4)])
