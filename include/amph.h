@@ -107,8 +107,9 @@ typedef struct amph_ctx amph_ctx;
 typedef struct amph_tree amph_tree;
 
 /* ---- context --------------------------------------------------------------------------------- */
-/* Validates cfg (host pointer), allocates the context's device status word on the CURRENT device.
- * *out is NULL on failure. */
+/* Validates cfg (host pointer), allocates the context's device status word on the CURRENT device and
+ * resolves that device's copy of the library's static scratch (amph_verify_attn_static).  *out is NULL
+ * on failure. */
 amph_status amph_create(const amph_config *cfg, amph_ctx **out);
 void amph_destroy(amph_ctx *ctx);
 /* hip_stream is a hipStream_t (NULL = the default stream).  The caller keeps it alive. */
@@ -191,6 +192,19 @@ amph_status amph_tree_build(amph_ctx *ctx, const amph_tree *tree, const int32_t 
  * Device-side error: kv_len[b] + T > max_kv (AMPH_DEV_KV_OVERFLOW). */
 amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache,
                              const void *v_cache, const int32_t *kv_len, void *out, void *workspace);
+
+/* ---- the same call for callers that cannot allocate ---------------------------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc and have no
+ * workspace to pass: the key-split partial results live in a static device array of the library
+ * (AMPH_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of the caller's workspace.
+ * The call itself allocates and frees nothing.  Same arguments, arithmetic and results as amph_verify_attn.
+ * AMPH_ESHAPE when the shape's partials exceed the array (the 7B and 13B shapes at batch 1 need 4.1 MiB;
+ * shapes without key splits need none), AMPH_EINVAL when the current device is not the one the context was
+ * created on.  All calls on one GPU share the array: calls that overlap in time there (different streams or
+ * contexts) race; calls on one stream are ordered and safe.  Nothing in it needs to start at zero. */
+#define AMPH_STATIC_SCRATCH_BYTES (8u << 20)
+amph_status amph_verify_attn_static(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache,
+                                    const void *v_cache, const int32_t *kv_len, void *out);
 
 /* ---- A10: greedy longest-accepted-prefix (Sec. 2 "Speculative Decoding"; Table 1, Temperature 0)
  * ok[root] = 1; ok[i] = ok[parent_i] and tree_tok[i] == tgt[parent_i]; best = deepest ok node

@@ -62,6 +62,7 @@ EXPORTS = {
     "amph_tree_info": (C.c_int, [C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_int)] + [C.POINTER(C.c_void_p)] * 5),
     "amph_tree_build": (C.c_int, [C.c_void_p] * 7),
     "amph_verify_attn": (C.c_int, [C.c_void_p] * 8),
+    "amph_verify_attn_static": (C.c_int, [C.c_void_p] * 7),
     "amph_pack_kv": (C.c_int, [C.c_void_p] * 5 + [C.c_int]),
     "amph_unpack_kv": (C.c_int, [C.c_void_p] * 5 + [C.c_int]),
     "amph_accept": (C.c_int, [C.c_void_p] * 10),
@@ -245,6 +246,10 @@ class Context:
     def amph_verify_attn(self, tree: Tree, q, k_cache, v_cache, kv_len, out):
         self._check(lib().amph_verify_attn(self.handle, tree.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
                                            _ptr(out), _ptr(self.workspace)), "amph_verify_attn")
+
+    def amph_verify_attn_static(self, tree: Tree, q, k_cache, v_cache, kv_len, out):
+        self._check(lib().amph_verify_attn_static(self.handle, tree.handle, _ptr(q), _ptr(k_cache), _ptr(v_cache),
+                                                  _ptr(kv_len), _ptr(out)), "amph_verify_attn_static")
 
     def amph_pack_kv(self, k_rows, v_rows, k_tiled, v_tiled, n_caches: int):
         self._check(lib().amph_pack_kv(self.handle, _ptr(k_rows), _ptr(v_rows), _ptr(k_tiled), _ptr(v_tiled), n_caches),

@@ -12,7 +12,32 @@
 
 using namespace amph;
 
+// Scratch of amph_verify_attn_static: the key-split partials of the verification attention, for callers that
+// cannot bring a workspace or allocate one.  Every GPU holds its own copy at its own address; host code never
+// uses the array's name as an address, only the pointer hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[AMPH_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES] = {};      // device address of `scratch` on each device that created a context
+
+// Address of this device's copy of `scratch` (resolved once per device, with that device current).
+hipError_t scratch_for_current_device(int *dev_out, void **ptr_out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[dev] = p;
+  }
+  *dev_out = dev;
+  *ptr_out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
@@ -29,6 +54,8 @@ struct amph_ctx {
   amph_config cfg;
   hipStream_t stream = nullptr;
   uint32_t *dev_status = nullptr;     // device, sticky (the context's only device allocation)
+  int device = -1;                    // the device that was current in amph_create
+  void *static_scratch = nullptr;     // that device's copy of the library's static scratch array
   std::string err = "";
   WsLayout ws;
   int esz = 2;
@@ -359,7 +386,8 @@ amph_status amph_create(const amph_config *cfg, amph_ctx **out) {
   ctx->cfg = c;
   ctx->esz = (c.dtype == AMPH_BF16) ? 2 : 4;
   ctx->ws = make_layout(c);
-  hipError_t e = hipMalloc(&ctx->dev_status, 256);
+  hipError_t e = scratch_for_current_device(&ctx->device, &ctx->static_scratch);
+  if (e == hipSuccess) e = hipMalloc(&ctx->dev_status, 256);
   if (e == hipSuccess) e = hipMemset(ctx->dev_status, 0, 256);
   if (e != hipSuccess) {
     if (ctx->dev_status) (void)hipFree(ctx->dev_status);
@@ -544,6 +572,35 @@ amph_status amph_verify_attn(amph_ctx *ctx, const amph_tree *tree, const void *q
   if (ctx->cfg.dtype == AMPH_BF16)
     return verify_impl<bf16_t>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, ctx->ws.ver_part_floats);
   return verify_impl<float>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, ctx->ws.ver_part_floats);
+}
+
+// The same call with the key-split partials in the library's static device array instead of a workspace: no
+// hipMalloc, no hipFree, no allocating library routine anywhere on this path (the tree's tables and the context's
+// status word were allocated by their _create calls).
+amph_status amph_verify_attn_static(amph_ctx *ctx, const amph_tree *tree, const void *q, const void *k_cache,
+                                    const void *v_cache, const int32_t *kv_len, void *out) {
+  if (!ctx) return AMPH_EINVAL;
+  if (!q || !k_cache || !v_cache || !kv_len || !out) return fail(ctx, AMPH_EINVAL, "amph_verify_attn_static: null argument");
+  if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out))
+    return fail(ctx, AMPH_EINVAL, "amph_verify_attn_static: pointers must be 16-byte aligned");
+  if (q == out) return fail(ctx, AMPH_EINVAL, "amph_verify_attn_static: out must not alias q");
+  if (amph_status s = check_tree(ctx, tree, "amph_verify_attn_static")) return s;
+  int dev = -1;
+  HIP_TRY(ctx, hipGetDevice(&dev));
+  if (dev != ctx->device || !ctx->static_scratch)
+    return fail(ctx, AMPH_EINVAL, "amph_verify_attn_static: the current device is not the one the context was created on");
+  const amph_config &c = ctx->cfg;
+  const size_t need = 4 * verify_partials_floats(c.batch, tree->T, c.n_heads, c.head_dim, c.max_kv, ctx->esz, ctx->verify_kernel);
+  if (need > (size_t)AMPH_STATIC_SCRATCH_BYTES) {
+    char msg[192];
+    std::snprintf(msg, sizeof msg, "amph_verify_attn_static: this shape needs %zu bytes of key-split partials, the static scratch holds %u",
+                  need, (unsigned)AMPH_STATIC_SCRATCH_BYTES);
+    return fail(ctx, AMPH_ESHAPE, msg);
+  }
+  float *partials = (float *)ctx->static_scratch;
+  const size_t cap = (size_t)AMPH_STATIC_SCRATCH_BYTES / 4;
+  if (c.dtype == AMPH_BF16) return verify_impl<bf16_t>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, cap);
+  return verify_impl<float>(ctx, tree, q, k_cache, v_cache, kv_len, out, partials, cap);
 }
 
 amph_status amph_accept(amph_ctx *ctx, const amph_tree *tree, const int32_t *tree_tok, const int32_t *tgt_argmax,
