@@ -627,8 +627,12 @@ static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int
   const int max_steps = max_kv / kstep;
   // regs: at most two blocks per wave, as few query groups as cover T; enough splits for every compute unit,
   // at least one step per wave
+  // One block per wave when the grid then still has room for two key splits: twice the workgroups read every key (L2
+  // hits), but each carries half the partials and half the queries' work (measured, 32 heads, T = 64, L = 1024, by
+  // the event brackets, attention + fold: 2 splits x 4 groups 16.5 us, 4 x 2 17.2, 1 x 4 18.2, 1 x 2 21.0, 8 x 2 26.6)
   const int blocks = (T + 15) / 16;
-  const int n_qg = (blocks + VA_MAX_QB - 1) / VA_MAX_QB;
+  const int max_qb = (B * blocks * n_heads * 2 <= 256) ? 1 : VA_MAX_QB;
+  const int n_qg = (blocks + max_qb - 1) / max_qb;
   int s = 256 / (B * n_qg * n_heads);
   const int cap = (max_steps + 3) / 4;
   if (s > cap) s = cap;
