@@ -582,22 +582,45 @@ __global__ __launch_bounds__(256) void k_verify_fold(const VerifyArgs a, int n_q
   const int NQ = nqb * 16, PART = NQ * DH + 2 * NQ;
   const int h = blockIdx.x, b = blockIdx.y / n_qg, qg = blockIdx.y % n_qg, tid = threadIdx.x;
   const int Tn = a.T, n_h = a.n_heads;
-  const int L = a.kv_len[b];
-  if (L < 0 || L + Tn > a.max_kv) return;               // the main kernel wrote nothing for this element
   const int q = blockIdx.z * QW + tid / (DH / 4), d4 = (tid % (DH / 4)) * 4;
   const int qi = qg * NQ + q;
-  if (q >= NQ || qi >= Tn) return;
+  const bool dead = (q >= NQ || qi >= Tn);
+  const int qc = dead ? 0 : q;                          // (dead threads read query 0's partials and store nothing)
   const float *p0 = a.partials + ((size_t)(b * n_qg + qg) * n_h + h) * S * PART;
-  float mt = NEG_BIG;
-  for (int s = 0; s < S; ++s) mt = fmaxf(mt, p0[(size_t)s * PART + NQ * DH + q]);
+  // The kernel is a chain of memory round trips and little else, so everything a thread needs is requested before
+  // anything is looked at: the committed length and, four splits at a time, each split's maximum, sum and four
+  // dims (splits past the last re-read it and are left out).  The splits are merged in ascending order.
+  const int L = a.kv_len[b];
+  constexpr int FU = 4;
+  float mt = NEG_BIG, l = 0.f;
   f32x4 o = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float l = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float *ps = p0 + (size_t)s * PART;
-    const float f = exp2f(ps[NQ * DH + q] - mt);
-    o += *reinterpret_cast<const f32x4 *>(ps + (size_t)q * DH + d4) * f;
-    l += ps[NQ * DH + NQ + q] * f;
+  for (int s0 = 0; s0 < S; s0 += FU) {
+    float ms[FU], ls[FU];
+    f32x4 os[FU];
+    #pragma unroll
+    for (int u = 0; u < FU; ++u) {
+      const float *ps = p0 + (size_t)min(s0 + u, S - 1) * PART;
+      ms[u] = ps[NQ * DH + qc];
+      ls[u] = ps[NQ * DH + NQ + qc];
+      os[u] = *reinterpret_cast<const f32x4 *>(ps + (size_t)qc * DH + d4);
+    }
+    float mb = mt;
+    #pragma unroll
+    for (int u = 0; u < FU; ++u) if (s0 + u < S) mb = fmaxf(mb, ms[u]);
+    const float f0 = exp2f(mt - mb);
+    o *= f0; l *= f0;
+    #pragma unroll
+    for (int u = 0; u < FU; ++u) {
+      if (s0 + u < S) {
+        const float f = exp2f(ms[u] - mb);
+        o += os[u] * f;
+        l += ls[u] * f;
+      }
+    }
+    mt = mb;
   }
+  if (L < 0 || L + Tn > a.max_kv) return;               // the main kernel wrote nothing for this element
+  if (dead) return;
   const float inv = (l > 0.f) ? 1.0f / l : 0.f;
   float r[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
   T *dst = a.out_tiles ? (T *)a.out + xt_index<T>(b * Tn + qi, h * DH + d4, a.out_tiles)
@@ -627,12 +650,8 @@ static VaPlan va_plan(int B, int T, int n_heads, int max_kv, int elem_bytes, int
   const int max_steps = max_kv / kstep;
   // regs: at most two blocks per wave, as few query groups as cover T; enough splits for every compute unit,
   // at least one step per wave
-  // One block per wave when the grid then still has room for two key splits: twice the workgroups read every key (L2
-  // hits), but each carries half the partials and half the queries' work (measured, 32 heads, T = 64, L = 1024, by
-  // the event brackets, attention + fold: 2 splits x 4 groups 16.5 us, 4 x 2 17.2, 1 x 4 18.2, 1 x 2 21.0, 8 x 2 26.6)
   const int blocks = (T + 15) / 16;
-  const int max_qb = (B * blocks * n_heads * 2 <= 256) ? 1 : VA_MAX_QB;
-  const int n_qg = (blocks + max_qb - 1) / max_qb;
+  const int n_qg = (blocks + VA_MAX_QB - 1) / VA_MAX_QB;
   int s = 256 / (B * n_qg * n_heads);
   const int cap = (max_steps + 3) / 4;
   if (s > cap) s = cap;
