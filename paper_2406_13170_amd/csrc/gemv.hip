@@ -30,45 +30,101 @@ template <typename T> struct XLayout {
   }
 };
 
-// Accumulate acc[r][m] += sum_k W_r[k] * x[m][k] over the whole reduction axis for this lane's slots.
+// Request the GV_U fragments from chunk c0 on of each of the R rows.  Unconditional loads (a predicated load with a
+// zero alternative makes the compiler wait for every load at the merge): lanes past the end re-read the row's
+// first fragment; x is zero-padded there and weights are finite, so they add nothing.
+template <typename T>
+__device__ __forceinline__ void gemv_request(const T *const (&rows)[GV_R], int c0, int Kd, uint4 (&w)[GV_U][GV_R]) {
+  constexpr int PER = Elem<T>::PER, CH = WAVE * PER;
+  const int lane = threadIdx.x & 63;
+  #pragma unroll
+  for (int u = 0; u < GV_U; ++u) {
+    const int k = (c0 + u) * CH + lane * PER;
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) w[u][r] = ldg16_stream(rows[r] + (k < Kd ? k : 0));
+  }
+}
+
+// acc[r][m] += the fragments of chunks c0 .. c0 + GV_U - 1 times the LDS copy of x
 template <typename T, int M>
-__device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const float *xs, int Kd, int nC,
-                                          float (&acc)[GV_R][M]) {
-  constexpr int PER = Elem<T>::PER, NQ = PER / 4, CH = WAVE * PER;
+__device__ __forceinline__ void gemv_consume(const float *xs, int nC, int c0, const uint4 (&w)[GV_U][GV_R],
+                                             float (&acc)[GV_R][M]) {
+  constexpr int PER = Elem<T>::PER, NQ = PER / 4;
   const int lane = threadIdx.x & 63;
   const float4 *xs4 = reinterpret_cast<const float4 *>(xs);
-  for (int c0 = 0; c0 < nC; c0 += GV_U) {
-    uint4 w[GV_U][GV_R];
-    #pragma unroll
-    for (int u = 0; u < GV_U; ++u) {
-      const int k = (c0 + u) * CH + lane * PER;
+  #pragma unroll
+  for (int u = 0; u < GV_U; ++u) {
+    if (c0 + u < nC) {
+      float wf[GV_R][PER];
       #pragma unroll
-      // Unconditional loads (a predicated load with a zero alternative makes the compiler wait for every
-      // load at the merge).  Lanes past the end re-read the row's first fragment; x is zero-padded there
-      // and weights are finite, so they add nothing.
-      for (int r = 0; r < GV_R; ++r) w[u][r] = ldg16_stream(rows[r] + (k < Kd ? k : 0));
-    }
-    #pragma unroll
-    for (int u = 0; u < GV_U; ++u) {
-      if (c0 + u < nC) {
-        float wf[GV_R][PER];
+      for (int r = 0; r < GV_R; ++r) Elem<T>::unpack(w[u][r], wf[r]);
+      #pragma unroll
+      for (int q = 0; q < NQ; ++q) {
         #pragma unroll
-        for (int r = 0; r < GV_R; ++r) Elem<T>::unpack(w[u][r], wf[r]);
-        #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
+        for (int m = 0; m < M; ++m) {
+          const float4 xv = xs4[((m * nC + c0 + u) * NQ + q) * 64 + lane];
           #pragma unroll
-          for (int m = 0; m < M; ++m) {
-            const float4 xv = xs4[((m * nC + c0 + u) * NQ + q) * 64 + lane];
-            #pragma unroll
-            for (int r = 0; r < GV_R; ++r) {
-              acc[r][m] = fmaf(wf[r][q * 4 + 0], xv.x, acc[r][m]);
-              acc[r][m] = fmaf(wf[r][q * 4 + 1], xv.y, acc[r][m]);
-              acc[r][m] = fmaf(wf[r][q * 4 + 2], xv.z, acc[r][m]);
-              acc[r][m] = fmaf(wf[r][q * 4 + 3], xv.w, acc[r][m]);
-            }
+          for (int r = 0; r < GV_R; ++r) {
+            acc[r][m] = fmaf(wf[r][q * 4 + 0], xv.x, acc[r][m]);
+            acc[r][m] = fmaf(wf[r][q * 4 + 1], xv.y, acc[r][m]);
+            acc[r][m] = fmaf(wf[r][q * 4 + 2], xv.z, acc[r][m]);
+            acc[r][m] = fmaf(wf[r][q * 4 + 3], xv.w, acc[r][m]);
           }
         }
       }
+    }
+  }
+}
+
+// one of three pointers by index, as selects on the address bits (written as a conditional chain it may be turned
+// into a table in scratch memory when it is evaluated in more than one place)
+template <typename P> __device__ __forceinline__ P *pick3(int i, P *a, P *b, P *c) {
+  const uintptr_t v = (i == 0 ? (uintptr_t)a : (uintptr_t)0) | (i == 1 ? (uintptr_t)b : (uintptr_t)0) | (i >= 2 ? (uintptr_t)c : (uintptr_t)0);
+  return (P *)v;
+}
+
+// With five or more activation rows a batch of fragments takes about as long to multiply as to fetch, and the rows
+// in LDS leave room for one workgroup per compute unit only, so nothing else would cover the fetch: those
+// instantiations keep two batches per wave and always have the next one on its way, across row groups as well
+// (measured with 5 rows at 7B shapes: gate/up 77.8 -> 62.7 us, the three SAL projections 45.2 -> 46.7, Wo / down
+// 17.5 -> 16.5).  With fewer rows several workgroups share a compute unit and a second batch per wave gains nothing
+// (1 row) or loses (4 rows: the LM head 52.9 -> 60.5 us).
+template <int M> struct GvPipe { static constexpr bool on = (M >= 5); };
+
+// The weight fragments a wave holds: one batch, or two when pipelined.  In the pipelined form w0 always holds (or
+// awaits) the first batch of the group that is multiplied next.
+template <typename T, int M> struct GvFrags {
+  uint4 w0[GV_U][GV_R];
+  uint4 w1[GvPipe<M>::on ? GV_U : 1][GV_R];
+};
+
+template <typename T, int M>
+__device__ __forceinline__ void gemv_begin(const T *const (&rows)[GV_R], int Kd, GvFrags<T, M> &f) {
+  if (GvPipe<M>::on) gemv_request<T>(rows, 0, Kd, f.w0);
+}
+
+// Accumulate acc[r][m] += sum_k W_r[k] * x[m][k] over the whole reduction axis for this lane's slots.
+// next: the rows of the group this wave multiplies after this one (any valid rows if there is none).
+template <typename T, int M>
+__device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const T *const (&next)[GV_R], const float *xs,
+                                          int Kd, int nC, float (&acc)[GV_R][M], GvFrags<T, M> &f) {
+  if constexpr (GvPipe<M>::on) {
+    // every request is unconditional (clamped inside the row), so the compiler can count the loads in flight: a
+    // batch is waited for with the one requested after it still outstanding
+    for (int c0 = 0; c0 < nC; c0 += 2 * GV_U) {
+      gemv_request<T>(rows, c0 + GV_U, Kd, f.w1);
+      gemv_consume<T, M>(xs, nC, c0, f.w0, acc);
+      const bool more = c0 + 2 * GV_U < nC;
+      const T *sel[GV_R];
+      #pragma unroll
+      for (int r = 0; r < GV_R; ++r) sel[r] = more ? rows[r] : next[r];
+      gemv_request<T>(sel, more ? c0 + 2 * GV_U : 0, Kd, f.w0);
+      gemv_consume<T, M>(xs, nC, c0 + GV_U, f.w1, acc);
+    }
+  } else {
+    for (int c0 = 0; c0 < nC; c0 += GV_U) {
+      gemv_request<T>(rows, c0, Kd, f.w0);
+      gemv_consume<T, M>(xs, nC, c0, f.w0, acc);
     }
   }
   #pragma unroll
@@ -212,13 +268,23 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int G = (d + GV_R - 1) / GV_R;
-  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
-    const T *rows[GV_R];
+  const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
     #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rows[r] = W + (size_t)min(g * GV_R + r, d - 1) * Kd;
+    for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, d - 1) * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g_first, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g_first; g < G; g += g_step) {
+    const T *next[GV_R];
+    set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int r = 0; r < GV_R; ++r) {
@@ -239,6 +305,24 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
 // n_valid is given) write nothing.  A wave step handles the two RoPE pairs (i, i + half),
 // (i + 1, i + 1 + half) of one head.  kv_stage points at [B, 2, n_heads, max_kv, d_h] of this stage.
 // =====================================================================================================
+// weight rows of group g of the stacked q, k, v matrices (Gseg groups each): two RoPE pairs (i0, i0 + 1 and their
+// partners half a head further on) of one head for q and k, four adjacent rows for v
+struct SalGroup { int seg, i0, n0, n1, n2, n3; };
+__device__ __forceinline__ SalGroup sal_group(int g, int Gseg, int d_h) {
+  SalGroup o;
+  o.seg = g / Gseg;
+  const int gl = g % Gseg, half = d_h / 2;
+  if (o.seg < 2) {
+    const int gph = half / 2;                // groups per head
+    o.i0 = (gl % gph) * 2;
+    o.n0 = (gl / gph) * d_h + o.i0; o.n1 = o.n0 + 1; o.n2 = o.n0 + half; o.n3 = o.n2 + 1;
+  } else {
+    o.i0 = 0;
+    o.n0 = gl * GV_R; o.n1 = o.n0 + 1; o.n2 = o.n0 + 2; o.n3 = o.n0 + 3;
+  }
+  return o;
+}
+
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk, const T *wv, const T *norm_w,
                                                         const float *x, int d, int n_heads, int d_h, int m_valid,
@@ -253,28 +337,29 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
   load_x_rmsnorm<T, M>(xs, smem, x, d, norm_w, m_valid, Kd, nC, eps, rs);
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int half = d_h / 2;
   const int Gseg = d / GV_R;                 // groups per matrix (d is a multiple of 4)
   const int G = 3 * Gseg;
-  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
-    const int seg = g / Gseg, gl = g % Gseg;
-    const T *Wm = (seg == 0) ? wq : (seg == 1) ? wk : wv;
-    int n[GV_R];
-    int head = 0, i0 = 0;
-    if (seg < 2) {
-      const int gph = half / 2;              // groups per head
-      head = gl / gph; i0 = (gl % gph) * 2;
-      n[0] = head * d_h + i0; n[1] = n[0] + 1; n[2] = n[0] + half; n[3] = n[2] + 1;
-    } else {
-      #pragma unroll
-      for (int r = 0; r < GV_R; ++r) n[r] = gl * GV_R + r;
-    }
-    const T *rows[GV_R];
-    #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)n[r] * Kd;
+  const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
+    const SalGroup sg = sal_group(g, Gseg, d_h);
+    const T *Wm = pick3(sg.seg, wq, wk, wv);
+    rw[0] = Wm + (size_t)sg.n0 * Kd; rw[1] = Wm + (size_t)sg.n1 * Kd; rw[2] = Wm + (size_t)sg.n2 * Kd; rw[3] = Wm + (size_t)sg.n3 * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g_first, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g_first; g < G; g += g_step) {
+    const SalGroup sg = sal_group(g, Gseg, d_h);
+    const int seg = sg.seg, i0 = sg.i0;
+    const int n[GV_R] = {sg.n0, sg.n1, sg.n2, sg.n3};
+    const T *next[GV_R];
+    set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int m = 0; m < M; ++m) {
@@ -334,16 +419,27 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int Gseg = (seg_rows + GV_R - 1) / GV_R;
   const int G = n_seg * Gseg;
-  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+  const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
     const int seg = g / Gseg, gl = g % Gseg;
-    const T *Wm = (seg == 0) ? w0 : (seg == 1) ? w1 : w2;
-    float *om = (seg == 0) ? o0 : (seg == 1) ? o1 : o2;
-    const T *rows[GV_R];
+    const T *Wm = pick3(seg, w0, w1, w2);
     #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * Kd;
+    for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g_first, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g_first; g < G; g += g_step) {
+    const int seg = g / Gseg, gl = g % Gseg;
+    float *om = (seg == 0) ? o0 : (seg == 1) ? o1 : o2;
+    const T *next[GV_R];
+    set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int r = 0; r < GV_R; ++r) {
@@ -379,13 +475,24 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int G = (f + 1) / 2;
-  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+  const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
     const int j0 = g * 2, j1 = min(j0 + 1, f - 1);
-    const T *rows[GV_R] = {w_gate + (size_t)j0 * Kd, w_gate + (size_t)j1 * Kd, w_up + (size_t)j0 * Kd,
-                           w_up + (size_t)j1 * Kd};
+    rw[0] = w_gate + (size_t)j0 * Kd; rw[1] = w_gate + (size_t)j1 * Kd; rw[2] = w_up + (size_t)j0 * Kd; rw[3] = w_up + (size_t)j1 * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g_first, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g_first; g < G; g += g_step) {
+    const int j0 = g * 2;
+    const T *next[GV_R];
+    set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int m = 0; m < M; ++m) {
@@ -416,18 +523,29 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int Gseg = (d + GV_R - 1) / GV_R;
   const int G = K * Gseg;
-  for (int g = blockIdx.x * 4 + wave; g < G; g += gridDim.x * 4) {
+  const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
+    const int k = g / Gseg, gl = g % Gseg;
+    const T *Wm = w_mlp + (size_t)k * d * d;
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, d - 1) * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g_first, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g_first; g < G; g += g_step) {
     const int k = g / Gseg, gl = g % Gseg;
     const bool first = (k < K / 2);
     const float *xs = first ? xs1 : xs2;
     const float *src = first ? h1 : h2;
-    const T *Wm = w_mlp + (size_t)k * d * d;
-    const T *rows[GV_R];
-    #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rows[r] = Wm + (size_t)min(gl * GV_R + r, d - 1) * Kd;
+    const T *next[GV_R];
+    set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int r = 0; r < GV_R; ++r) {
@@ -468,13 +586,22 @@ __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, i
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int G = (V + GV_R - 1) / GV_R;
   const int g0 = blockIdx.x * Gp, g1 = min(g0 + Gp, G);
-  for (int g = g0 + wave; g < g1; g += 4) {
-    const T *rows[GV_R];
+  auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
     #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rows[r] = W + (size_t)min(g * GV_R + r, V - 1) * Kd;
+    for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, V - 1) * Kd;
+  };
+  GvFrags<T, M> fr;
+  const T *rows[GV_R];
+  set_rows(min(g0 + wave, G - 1), rows);
+  gemv_begin<T, M>(rows, Kd, fr);
+  for (int g = g0 + wave; g < g1; g += 4) {
+    const T *next[GV_R];
+    set_rows(min(g + 4, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, xs, Kd, nC, acc);
+    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    #pragma unroll
+    for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (lane == 0) {
       #pragma unroll
       for (int r = 0; r < GV_R; ++r) {
