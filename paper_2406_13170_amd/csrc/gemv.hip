@@ -133,6 +133,18 @@ __device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const T 
     for (int m = 0; m < M; ++m) acc[r][m] = wave_sum(acc[r][m]);
 }
 
+// After gemv_rows every lane holds all R x M sums, so the epilogues spread their outputs over the lanes (lane ->
+// (row of the group, activation row)) instead of walking them on lane 0: the loads an epilogue needs (residual,
+// positions) and its transcendental functions then run side by side.  acc_at picks a lane's sum by selects.
+template <int M> __device__ __forceinline__ float acc_at(const float (&acc)[GV_R][M], int r, int m) {
+  float v = 0.f;
+  #pragma unroll
+  for (int mm = 0; mm < M; ++mm)
+    #pragma unroll
+    for (int rr = 0; rr < GV_R; ++rr) v = (mm == m && rr == r) ? acc[rr][mm] : v;
+  return v;
+}
+
 template <int M> __device__ __forceinline__ void zero_acc(float (&acc)[GV_R][M]) {
   #pragma unroll
   for (int r = 0; r < GV_R; ++r)
@@ -285,15 +297,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
-      #pragma unroll
-      for (int r = 0; r < GV_R; ++r) {
-        const int n = g * GV_R + r;
-        if (n < d) {
-          #pragma unroll
-          for (int m = 0; m < M; ++m) if (m < m_valid) out[(size_t)m * d + n] = acc[r][m];
-        }
-      }
+    {
+      const int r = lane & (GV_R - 1), m = lane / GV_R, n = g * GV_R + r;
+      const float v = acc_at<M>(acc, r, m);
+      if (m < m_valid && n < d) out[(size_t)m * d + n] = v;
     }
   }
 }
@@ -345,6 +352,23 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
     const T *Wm = pick3(sg.seg, wq, wk, wv);
     rw[0] = Wm + (size_t)sg.n0 * Kd; rw[1] = Wm + (size_t)sg.n1 * Kd; rw[2] = Wm + (size_t)sg.n2 * Kd; rw[3] = Wm + (size_t)sg.n3 * Kd;
   };
+  // epilogue role of this lane: activation row em, pair member ep (outputs ep and 2 + ep of a group); its position
+  // in the cache is read once, here
+  const int em = lane >> 1, ep = lane & 1;
+  bool e_live = false, e_bad = false;
+  int e_pos = 0, e_bb = 0;
+  float e_rs = 0.f;
+  if (em < M && em < m_valid) {
+    e_bb = (row0 + em) / R;
+    const int jn = (row0 + em) % R;
+    const bool valid = !(n_valid && jn >= n_valid[e_bb]);
+    const int sl = sal_len[e_bb];
+    e_pos = sl + jn;
+    e_bad = valid && (sl < 0 || e_pos + 1 > max_kv);
+    e_live = valid && !e_bad;
+    #pragma unroll
+    for (int m = 0; m < M; ++m) if (m == em) e_rs = rs[m];
+  }
   GvFrags<T, M> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
@@ -360,43 +384,26 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
-      #pragma unroll
-      for (int m = 0; m < M; ++m) {
-        if (m >= m_valid) continue;
-        const int bb = (row0 + m) / R, jn = (row0 + m) % R;
-        if (n_valid && jn >= n_valid[bb]) continue;
-        const int pos = sal_len[bb] + jn;
-        if (sal_len[bb] < 0 || pos + 1 > max_kv) {
-          if (g == 0) atomicOr(dev_status, 1u);
-          continue;
-        }
-        float y[GV_R];
-        #pragma unroll
-        for (int r = 0; r < GV_R; ++r) y[r] = acc[r][m] * rs[m];
-        if (seg < 2) {
-          #pragma unroll
-          for (int p = 0; p < 2; ++p) {
-            const float inv_freq = exp2f(-2.0f * (float)(i0 + p) / (float)d_h * log2f(theta));
-            float sn, cs;
-            sincosf((float)pos * inv_freq, &sn, &cs);
-            const float a = y[p], b = y[2 + p];
-            y[p] = a * cs - b * sn;
-            y[2 + p] = b * cs + a * sn;
-          }
-        }
-        if (seg == 0) {
-          #pragma unroll
-          for (int r = 0; r < GV_R; ++r) qbuf[(size_t)m * d + n[r]] = y[r];
-        } else {
-          // [B, 2, n_heads, max_kv, d_h]
-          #pragma unroll
-          for (int r = 0; r < GV_R; ++r) {
-            const int hh = n[r] / d_h, e = n[r] % d_h;
-            T *dst = kv_stage + ((((size_t)bb * 2 + (seg - 1)) * n_heads + hh) * max_kv + pos) * d_h + e;
-            *dst = Elem<T>::from_f32(y[r]);
-          }
-        }
+    if (g == 0 && e_bad && ep == 0) atomicOr(dev_status, 1u);
+    if (e_live) {
+      float ya = acc_at<M>(acc, ep, em) * e_rs, yb = acc_at<M>(acc, 2 + ep, em) * e_rs;
+      if (seg < 2) {
+        const float inv_freq = exp2f(-2.0f * (float)(i0 + ep) / (float)d_h * log2f(theta));
+        float sn, cs;
+        sincosf((float)e_pos * inv_freq, &sn, &cs);
+        const float a = ya, b = yb;
+        ya = a * cs - b * sn;
+        yb = b * cs + a * sn;
+      }
+      const int na = ep ? n[1] : n[0], nb = ep ? n[3] : n[2];
+      if (seg == 0) {
+        qbuf[(size_t)em * d + na] = ya;
+        qbuf[(size_t)em * d + nb] = yb;
+      } else {
+        // [B, 2, n_heads, max_kv, d_h]
+        T *base = kv_stage + (((size_t)e_bb * 2 + (seg - 1)) * n_heads) * (size_t)max_kv * d_h + (size_t)e_pos * d_h;
+        base[(size_t)(na / d_h) * max_kv * d_h + na % d_h] = Elem<T>::from_f32(ya);
+        base[(size_t)(nb / d_h) * max_kv * d_h + nb % d_h] = Elem<T>::from_f32(yb);
       }
     }
   }
@@ -440,20 +447,12 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
-      #pragma unroll
-      for (int r = 0; r < GV_R; ++r) {
-        const int n = gl * GV_R + r;
-        if (n < seg_rows) {
-          #pragma unroll
-          for (int m = 0; m < M; ++m) {
-            if (m < m_valid) {
-              float v = acc[r][m];
-              if (res) v += res[(size_t)m * ldo + n];
-              om[(size_t)m * ldo + n] = v;
-            }
-          }
-        }
+    {
+      const int r = lane & (GV_R - 1), m = lane / GV_R, n = gl * GV_R + r;
+      float v = acc_at<M>(acc, r, m);
+      if (m < m_valid && n < seg_rows) {
+        if (res) v += res[(size_t)m * ldo + n];
+        om[(size_t)m * ldo + n] = v;
       }
     }
   }
@@ -493,13 +492,13 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
+    {
+      const int jj = lane & 1, m = lane >> 1;
+      float rsm = 0.f;
       #pragma unroll
-      for (int m = 0; m < M; ++m) {
-        if (m >= m_valid) continue;
-        act[(size_t)m * f + j0] = silu_f(acc[0][m] * rs[m]) * (acc[2][m] * rs[m]);
-        if (j0 + 1 < f) act[(size_t)m * f + j0 + 1] = silu_f(acc[1][m] * rs[m]) * (acc[3][m] * rs[m]);
-      }
+      for (int mm = 0; mm < M; ++mm) if (mm == m) rsm = rs[mm];
+      const float gt = acc_at<M>(acc, jj, m) * rsm, up = acc_at<M>(acc, 2 + jj, m) * rsm;
+      if (m < M && m < m_valid && j0 + jj < f) act[(size_t)m * f + j0 + jj] = silu_f(gt) * up;
     }
   }
 }
@@ -546,16 +545,12 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
-      #pragma unroll
-      for (int r = 0; r < GV_R; ++r) {
-        const int n = gl * GV_R + r;
-        if (n < d) {
-          const float pek = pe ? Elem<T>::to_f32(pe[(size_t)k * d + n]) : 0.f;     // no position encoding: PE = 0
-          #pragma unroll
-          for (int m = 0; m < M; ++m)
-            if (m < m_valid) Hp[((size_t)m * K + k) * d + n] = src[(size_t)m * d + n] + silu_f(acc[r][m]) + pek;
-        }
+    {
+      const int r = lane & (GV_R - 1), m = lane / GV_R, n = gl * GV_R + r;
+      const float v = acc_at<M>(acc, r, m);
+      if (m < m_valid && n < d) {
+        const float pek = pe ? Elem<T>::to_f32(pe[(size_t)k * d + n]) : 0.f;     // no position encoding: PE = 0
+        Hp[((size_t)m * K + k) * d + n] = src[(size_t)m * d + n] + silu_f(v) + pek;
       }
     }
   }
@@ -602,15 +597,12 @@ __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, i
     gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
-    if (lane == 0) {
-      #pragma unroll
-      for (int r = 0; r < GV_R; ++r) {
-        const int n = g * GV_R + r;
-        #pragma unroll
-        for (int m = 0; m < M; ++m) {
-          lg[m * RP + (g - g0) * GV_R + r] = acc[r][m];
-          if (logits && n < V && m < m_valid) logits[(size_t)m * V + n] = acc[r][m];
-        }
+    {
+      const int r = lane & (GV_R - 1), m = lane / GV_R, n = g * GV_R + r;
+      const float v = acc_at<M>(acc, r, m);
+      if (m < M) {
+        lg[m * RP + (g - g0) * GV_R + r] = v;
+        if (logits && n < V && m < m_valid) logits[(size_t)m * V + n] = v;
       }
     }
   }
