@@ -224,14 +224,18 @@ __device__ __forceinline__ void load_x_rmsnorm(float *xs, float *red, const floa
 
 // =====================================================================================================
 // K1: x^s = fc^s([u ; e]) of Eq. 1, e = embed[tok] gathered on the fly.  out [M, d] float32.
+// half < 0: the whole product.  half = 0 / 1: only the columns that meet u / e (out = / out +=), for row counts whose
+// concatenated rows do not fit in LDS: two launches over half the columns each read the matrix once, where two
+// launches over fewer rows would read it twice.
 // =====================================================================================================
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const float *u, const T *embed,
                                                           const int32_t *tok, int vocab, int d, int m_valid,
-                                                          float *out, uint32_t *dev_status) {
+                                                          float *out, uint32_t *dev_status, int half) {
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
-  const int Kd = 2 * d, nC = (Kd + CH - 1) / CH, Kp = nC * CH;
+  const int ldw = 2 * d, k_lo = (half == 1) ? d : 0;       // weight row length; first column of this launch
+  const int Kd = (half < 0) ? 2 * d : d, nC = (Kd + CH - 1) / CH, Kp = nC * CH;
   float *xs = smem;
   {
     // [u ; e]: both halves are loaded for every piece (clamped addresses) and the right one is kept
@@ -251,8 +255,8 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
       float vu[2][M][4], ve[2][M][4];
       #pragma unroll
       for (int q2 = 0; q2 < 2; ++q2) {
-        const int k = (j0 + q2 * GV_THREADS) * 4;
-        const int ku = (k < d) ? k : 0, ke = (k >= d && k < Kd) ? k - d : 0;
+        const int k = (j0 + q2 * GV_THREADS) * 4, kg = k + k_lo;
+        const int ku = (kg < d) ? kg : 0, ke = (kg >= d && k < Kd) ? kg - d : 0;
         #pragma unroll
         for (int m = 0; m < M; ++m) {
           load4<float>(u + (size_t)(m < m_valid ? m : 0) * d + ku, vu[q2][m]);
@@ -265,7 +269,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
         if (q < nq) {
           #pragma unroll
           for (int m = 0; m < M; ++m) {
-            const bool in_u = k < d, ok = m < m_valid && k < Kd && (in_u || tok_ok[m]);
+            const bool in_u = k + k_lo < d, ok = m < m_valid && k < Kd && (in_u || tok_ok[m]);
             float4 o;
             o.x = ok ? (in_u ? vu[q2][m][0] : ve[q2][m][0]) : 0.f;
             o.y = ok ? (in_u ? vu[q2][m][1] : ve[q2][m][1]) : 0.f;
@@ -283,7 +287,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
   const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
   auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
     #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, d - 1) * Kd;
+    for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, d - 1) * ldw + k_lo;
   };
   GvFrags<T, M> fr;
   const T *rows[GV_R];
@@ -299,8 +303,11 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
       const int r = lane & (GV_R - 1), m = lane / GV_R, n = g * GV_R + r;
-      const float v = acc_at<M>(acc, r, m);
-      if (m < m_valid && n < d) out[(size_t)m * d + n] = v;
+      float v = acc_at<M>(acc, r, m);
+      if (m < m_valid && n < d) {
+        if (half == 1) v += out[(size_t)m * d + n];
+        out[(size_t)m * d + n] = v;
+      }
     }
   }
 }
@@ -660,18 +667,25 @@ template <typename T>
 hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const void *embed, const int32_t *tok,
                             int vocab, int d, int M, float *out, uint32_t *dev_status) {
   if (M < 1 || d % 8) return hipErrorInvalidValue;
-  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, 2 * d), 0);
+  int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, 2 * d), 0);
+  // rows that fit only without their other half: two launches over d columns each
+  const int mch = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 0);
+  const bool halves = mc < M && mch > mc;
+  if (halves) mc = mch;
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
     const int m = std::min(mc, M - m0);
-    hipError_t e = hipSuccess;
-    GV_DISPATCH_M(m, {
-      const size_t sm = gv_xs_bytes<T>(MM, 2 * d);
-      e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W,
-                         u + (size_t)m0 * d, (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status);
-    });
+    for (int half = halves ? 0 : -1; half < (halves ? 2 : 0); ++half) {
+      hipError_t e = hipSuccess;
+      GV_DISPATCH_M(m, {
+        const size_t sm = gv_xs_bytes<T>(MM, halves ? d : 2 * d);
+        e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W,
+                           u + (size_t)m0 * d, (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status,
+                           half);
+      });
+    }
   }
   return hipGetLastError();
 }
