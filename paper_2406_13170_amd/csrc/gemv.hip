@@ -93,22 +93,22 @@ template <int M> struct GvPipe { static constexpr bool on = (M >= 5); };
 
 // The weight fragments a wave holds: one batch, or two when pipelined.  In the pipelined form w0 always holds (or
 // awaits) the first batch of the group that is multiplied next.
-template <typename T, int M> struct GvFrags {
+template <typename T, bool PIPE> struct GvFrags {
   uint4 w0[GV_U][GV_R];
-  uint4 w1[GvPipe<M>::on ? GV_U : 1][GV_R];
+  uint4 w1[PIPE ? GV_U : 1][GV_R];
 };
 
-template <typename T, int M>
-__device__ __forceinline__ void gemv_begin(const T *const (&rows)[GV_R], int Kd, GvFrags<T, M> &f) {
-  if (GvPipe<M>::on) gemv_request<T>(rows, 0, Kd, f.w0);
+template <typename T, bool PIPE>
+__device__ __forceinline__ void gemv_begin(const T *const (&rows)[GV_R], int Kd, GvFrags<T, PIPE> &f) {
+  if (PIPE) gemv_request<T>(rows, 0, Kd, f.w0);
 }
 
 // Accumulate acc[r][m] += sum_k W_r[k] * x[m][k] over the whole reduction axis for this lane's slots.
 // next: the rows of the group this wave multiplies after this one (any valid rows if there is none).
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __device__ __forceinline__ void gemv_rows(const T *const (&rows)[GV_R], const T *const (&next)[GV_R], const float *xs,
-                                          int Kd, int nC, float (&acc)[GV_R][M], GvFrags<T, M> &f) {
-  if constexpr (GvPipe<M>::on) {
+                                          int Kd, int nC, float (&acc)[GV_R][M], GvFrags<T, PIPE> &f) {
+  if constexpr (PIPE) {
     // every request is unconditional (clamped inside the row), so the compiler can count the loads in flight: a
     // batch is waited for with the one requested after it still outstanding
     for (int c0 = 0; c0 < nC; c0 += 2 * GV_U) {
@@ -228,7 +228,7 @@ __device__ __forceinline__ void load_x_rmsnorm(float *xs, float *red, const floa
 // concatenated rows do not fit in LDS: two launches over half the columns each read the matrix once, where two
 // launches over fewer rows would read it twice.
 // =====================================================================================================
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const float *u, const T *embed,
                                                           const int32_t *tok, int vocab, int d, int m_valid,
                                                           float *out, uint32_t *dev_status, int half) {
@@ -289,16 +289,16 @@ __global__ __launch_bounds__(GV_THREADS) void k_fc_concat(const T *W, const floa
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, d - 1) * ldw + k_lo;
   };
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
     const T *next[GV_R];
     set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
@@ -343,6 +343,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
                                                         float eps, float theta, const int32_t *sal_len, int max_kv,
                                                         T *kv_stage, float *qbuf, uint32_t *dev_status, int row0, int R,
                                                         const int32_t *n_valid) {
+  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -376,10 +377,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
     #pragma unroll
     for (int m = 0; m < M; ++m) if (m == em) e_rs = rs[m];
   }
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
     const SalGroup sg = sal_group(g, Gseg, d_h);
     const int seg = sg.seg, i0 = sg.i0;
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
     set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     if (g == 0 && e_bad && ep == 0) atomicOr(dev_status, 1u);
@@ -420,7 +421,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
 // K3: generic linear with up to three stacked matrices of `seg_rows` rows each (AEB q/k/v, Wo, W_down,
 // LM head).  out_s[m][n] = (res ? res[m][n] : 0) + sum_k x[m][k] W_s[n][k].  x float32 [M, Kd].
 // =====================================================================================================
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1, const T *w2, int n_seg, int seg_rows,
                                                        int Kd, const float *x, int ldx, int m_valid, const float *res,
                                                        float *o0, float *o1, float *o2, int ldo) {
@@ -440,10 +441,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * Kd;
   };
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
     const int seg = g / Gseg, gl = g % Gseg;
     float *om = (seg == 0) ? o0 : (seg == 1) ? o1 : o2;
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
     set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
@@ -472,6 +473,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T *w_up, const T *norm_w, const float *x,
                                                         int d, int f, int m_valid, float eps, float *act) {
+  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -486,17 +488,17 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
     const int j0 = g * 2, j1 = min(j0 + 1, f - 1);
     rw[0] = w_gate + (size_t)j0 * Kd; rw[1] = w_gate + (size_t)j1 * Kd; rw[2] = w_up + (size_t)j0 * Kd; rw[3] = w_up + (size_t)j1 * Kd;
   };
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
     const int j0 = g * 2;
     const T *next[GV_R];
     set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
@@ -518,6 +520,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T *pe, const float *h1, const float *h2,
                                                          int d, int K, int m_valid, float *Hp) {
+  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -536,10 +539,10 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, d - 1) * Kd;
   };
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g_first, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
     const int k = g / Gseg, gl = g % Gseg;
     const bool first = (k < K / 2);
@@ -549,7 +552,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
     set_rows(min(g + g_step, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
@@ -577,6 +580,7 @@ constexpr int LMTK_NPT = 4;                      // logits per lane in the selec
 template <typename T, int M>
 __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, int Kd, const float *x, int m_valid, int Gp,
                                                             int k, float *logits, float *cand_v, int *cand_i) {
+  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int nC = (Kd + CH - 1) / CH;
@@ -592,16 +596,16 @@ __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, i
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rw[r] = W + (size_t)min(g * GV_R + r, V - 1) * Kd;
   };
-  GvFrags<T, M> fr;
+  GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
   set_rows(min(g0 + wave, G - 1), rows);
-  gemv_begin<T, M>(rows, Kd, fr);
+  gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g0 + wave; g < g1; g += 4) {
     const T *next[GV_R];
     set_rows(min(g + 4, G - 1), next);
     float acc[GV_R][M];
     zero_acc<M>(acc);
-    gemv_rows<T, M>(rows, next, xs, Kd, nC, acc, fr);
+    gemv_rows<T, M, PIPE>(rows, next, xs, Kd, nC, acc, fr);
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rows[r] = next[r];
     {
@@ -637,6 +641,11 @@ template <typename T> static inline size_t gv_xs_bytes(int M, int Kd) {
   constexpr int CH = XLayout<T>::CH;
   return (size_t)M * ((Kd + CH - 1) / CH) * CH * sizeof(float);
 }
+
+// Two batches of fragments per wave (see GvPipe): always from five rows on; for fewer rows where the matrix has so
+// few row groups that a compute unit gets one workgroup, whose four waves would otherwise each wait out every
+// round trip with nothing else to run.
+static inline bool gv_pipe(int mm, int grid) { return mm >= 5 || grid <= 256; }
 
 #define GV_DISPATCH_M(Mv, BODY)                                   \
   switch (Mv) {                                                    \
@@ -679,11 +688,18 @@ hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const
       hipError_t e = hipSuccess;
       GV_DISPATCH_M(m, {
         const size_t sm = gv_xs_bytes<T>(MM, halves ? d : 2 * d);
-        e = gv_set_smem<T>(k_fc_concat<T, MM>, sm);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((k_fc_concat<T, MM>), dim3(gv_grid((d + 3) / 4)), dim3(GV_THREADS), sm, st, (const T *)W,
-                           u + (size_t)m0 * d, (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status,
-                           half);
+        const int grid = gv_grid((d + 3) / 4);
+        if (gv_pipe(MM, grid)) {
+          e = gv_set_smem<T>(k_fc_concat<T, MM, true>, sm);
+          if (e != hipSuccess) return e;
+          hipLaunchKernelGGL((k_fc_concat<T, MM, true>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)W, u + (size_t)m0 * d,
+                             (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status, half);
+        } else {
+          e = gv_set_smem<T>(k_fc_concat<T, MM, false>, sm);
+          if (e != hipSuccess) return e;
+          hipLaunchKernelGGL((k_fc_concat<T, MM, false>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)W, u + (size_t)m0 * d,
+                             (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status, half);
+        }
       });
     }
   }
@@ -724,11 +740,20 @@ hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const v
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = gv_xs_bytes<T>(MM, Kd);
-      e = gv_set_smem<T>(k_linear<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_linear<T, MM>), dim3(gv_grid(n_seg * ((seg_rows + 3) / 4))), dim3(GV_THREADS), sm, st,
-                         (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m,
-                         res ? res + oo : nullptr, o0 + oo, o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
+      const int grid = gv_grid(n_seg * ((seg_rows + 3) / 4));
+      if (gv_pipe(MM, grid)) {
+        e = gv_set_smem<T>(k_linear<T, MM, true>, sm);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_linear<T, MM, true>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)w0, (const T *)w1,
+                           (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo,
+                           o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
+      } else {
+        e = gv_set_smem<T>(k_linear<T, MM, false>, sm);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_linear<T, MM, false>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)w0, (const T *)w1,
+                           (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo,
+                           o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
+      }
     });
   }
   return hipGetLastError();
