@@ -304,7 +304,8 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
     while (s > 1 && (size_t)s * slab > ctx->ws.slabs_floats) s /= 2;
     return s;
   };
-  if (n_layers > 0) HIP_TRY(ctx, launch_rope_table(st, tree_pos, M, d_h, c.rope_theta, rope_cs));
+  RopeTable rope_req;                     // written by the kernel that gathers the embeddings
+  rope_req.pos = tree_pos; rope_req.d_h = d_h; rope_req.theta = c.rope_theta; rope_req.cs = rope_cs;
   int pending = 0;                        // slabs of the previous GEMM still to be added to the residual stream
   for (int li = 0; li < n_layers; ++li) {
     const amph_layer_w &lw = layers[li];
@@ -318,7 +319,7 @@ amph_status target_impl(amph_ctx *ctx, const amph_tree *tree, const amph_layer_w
     const bool w_gu = gemm_is_wide(M, lt.gate_up != nullptr), w_down = gemm_is_wide(M, lt.down != nullptr);
     PROF_TRY(ctx, AMPH_K_T_RMSNORM, launch_norm_fold<T>(st, xres, embed, li == 0 ? tree_tok : nullptr, V, slabs, pending,
                                                         slab, lw.rms1, M, d, c.rms_eps, xn, nullptr, ctx->dev_status,
-                                                        w_qkv ? xt_tiles : 0));
+                                                        w_qkv ? xt_tiles : 0, li == 0 ? rope_req : RopeTable{}));
     GemmArgs a = g;
     a.w0 = lw.wq; a.w1 = lw.wk; a.w2 = lw.wv; a.wt = lt.qkv; a.n_seg = 3; a.seg_rows = d; a.Kd = d; a.x = xn;
     a.x_tiled = w_qkv;

@@ -694,24 +694,6 @@ __global__ __launch_bounds__(256) void k_sum_slabs(const float *slabs, int S, si
   }
 }
 
-// (cos, sin) of pos[m] * theta^(-2e/d_h) for e < d_h/2: the same table serves every layer of a pass
-__global__ void k_rope_table(const int32_t *pos, int M, int d_h, float theta, float2 *cs) {
-  const int half = d_h / 2;
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= M * half) return;
-  const int m = i / half, e = i % half;
-  const float inv_freq = exp2f(-2.0f * (float)e / (float)d_h * log2f(theta));
-  float sn, c;
-  sincosf((float)pos[m] * inv_freq, &sn, &c);
-  cs[i] = make_float2(c, sn);
-}
-
-hipError_t launch_rope_table(hipStream_t st, const int32_t *pos, int M, int d_h, float theta, float2 *cs) {
-  const int n = M * (d_h / 2);
-  hipLaunchKernelGGL(k_rope_table, dim3((n + 255) / 256), dim3(256), 0, st, pos, M, d_h, theta, cs);
-  return hipGetLastError();
-}
-
 hipError_t launch_sum_slabs(hipStream_t st, const float *slabs, int S, size_t n, float *out) {
   int blocks = (int)((n + 255) / 256);
   if (blocks > 2048) blocks = 2048;

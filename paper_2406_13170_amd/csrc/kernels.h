@@ -76,10 +76,12 @@ hipError_t launch_gather_rows(hipStream_t st, const float *rows, int B, int R, i
 // x[m] (+)= sum_s slabs[s][m] (or x[m] = embed[tok[m]] when tok != NULL); xn[m] = RMSNorm(x[m]) * g as T;
 // hidden_out (float32, optional) receives the same normalised rows.  xn_tiles != 0: xn is written in the tiled
 // activation layout of the wide GEMM (xn_tiles = number of 32-row tiles).
+// optional by-product of the embedding instance of k_norm_fold: cs[row][e] = (cos, sin)(pos[row] * theta^(-2e/d_h))
+struct RopeTable { const int32_t *pos = nullptr; int d_h = 0; float theta = 0.f; float2 *cs = nullptr; };
 template <typename T>
 hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
                             const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
-                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles = 0);
+                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles = 0, RopeTable rope = RopeTable{});
 
 // ---- gemm_skinny.hip (target path, rows on the matrix cores) ----
 enum GemmEpi { EPI_STORE = 0, EPI_QKV_ROPE = 2, EPI_SWIGLU = 3, EPI_ARGMAX = 4 };
@@ -124,7 +126,6 @@ template <typename T> hipError_t launch_gemm(hipStream_t st, int epi, const Gemm
 // bytes of the tiled copy of the matrices of one GEMM, and the kernel that writes it (w0..w2, seg_rows, Kd, n_heads, d_h of a)
 size_t gemm_tiled_bytes(int epi, int seg_rows, int Kd, int elem_bytes);
 template <typename T> hipError_t launch_pack_weights(hipStream_t st, int epi, const GemmArgs &a, void *dst);
-hipError_t launch_rope_table(hipStream_t st, const int32_t *pos, int M, int d_h, float theta, float2 *cs);
 hipError_t launch_sum_slabs(hipStream_t st, const float *slabs, int S, size_t n, float *out);
 hipError_t launch_argmax_fold(hipStream_t st, const float *amax_val, const int32_t *amax_idx, int tiles, int M,
                               int32_t *tgt);

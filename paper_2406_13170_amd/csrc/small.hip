@@ -806,7 +806,8 @@ template hipError_t launch_kv_layout<bf16_t>(hipStream_t, const void *, const vo
 template <typename T, int S, bool EMB, int NP>
 __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, const int32_t *tok, int vocab,
                                                     const float *slabs, size_t slab_stride, const T *g, int d,
-                                                    float eps, T *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles) {
+                                                    float eps, T *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles,
+                                                    RopeTable rope) {
   __shared__ float red[16];
   const int row = blockIdx.x, tid = threadIdx.x;
   float *xr = x + (size_t)row * d;
@@ -824,6 +825,17 @@ __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, co
     #pragma unroll
     for (int s = 0; s < S; ++s) load4<float>(slabs + (size_t)s * slab_stride + (size_t)row * d + kk, p[i][s]);
     load4<T>(g + kk, gk[i]);
+  }
+  if (EMB && rope.cs) {
+    // the pass's RoPE table rides on the kernel that starts the pass (one launch fewer): row `row` of
+    // (cos, sin) of pos * theta^(-2e/d_h), e < d_h/2, the same for every layer
+    const int half = rope.d_h / 2;
+    for (int e = tid; e < half; e += 1024) {
+      const float inv_freq = exp2f(-2.0f * (float)e / (float)rope.d_h * log2f(rope.theta));
+      float sn, c;
+      sincosf((float)rope.pos[row] * inv_freq, &sn, &c);
+      rope.cs[(size_t)row * half + e] = make_float2(c, sn);
+    }
   }
   float ss = 0.f;
   #pragma unroll
@@ -863,13 +875,14 @@ __global__ __launch_bounds__(1024) void k_norm_fold(float *x, const T *embed, co
 template <typename T>
 hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const int32_t *tok, int vocab,
                             const float *slabs, int S, size_t slab_stride, const void *g, int rows, int d, float eps,
-                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles) {
+                            void *xn, float *hidden_out, uint32_t *dev_status, int xn_tiles, RopeTable rope) {
   if (d % 4 || d > 8192) return hipErrorInvalidValue;
   if (tok && S != 0) return hipErrorInvalidValue;                  // the embedding gather starts a fresh residual stream
+  if (rope.cs && (!tok || !rope.pos || rope.d_h < 2)) return hipErrorInvalidValue;   // the table is written by the embedding instance
   const int np = d > 4096 ? 2 : 1;
   #define NF_LAUNCH(S_, EMB_, NP_)                                                                                  \
     hipLaunchKernelGGL((k_norm_fold<T, S_, EMB_, NP_>), dim3(rows), dim3(1024), 0, st, x, (const T *)embed, tok,    \
-                       vocab, slabs, slab_stride, (const T *)g, d, eps, (T *)xn, hidden_out, dev_status, xn_tiles)
+                       vocab, slabs, slab_stride, (const T *)g, d, eps, (T *)xn, hidden_out, dev_status, xn_tiles, rope)
   #define NF_CASE(S_)                                                                                               \
     case S_: if (np == 1) NF_LAUNCH(S_, false, 1); else NF_LAUNCH(S_, false, 2); break
   if (tok) {
@@ -885,8 +898,8 @@ hipError_t launch_norm_fold(hipStream_t st, float *x, const void *embed, const i
   return hipGetLastError();
 }
 template hipError_t launch_norm_fold<float>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
-                                            size_t, const void *, int, int, float, void *, float *, uint32_t *, int);
+                                            size_t, const void *, int, int, float, void *, float *, uint32_t *, int, RopeTable);
 template hipError_t launch_norm_fold<bf16_t>(hipStream_t, float *, const void *, const int32_t *, int, const float *, int,
-                                             size_t, const void *, int, int, float, void *, float *, uint32_t *, int);
+                                             size_t, const void *, int, int, float, void *, float *, uint32_t *, int, RopeTable);
 
 }  // namespace amph
