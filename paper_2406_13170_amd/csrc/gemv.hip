@@ -337,13 +337,12 @@ __device__ __forceinline__ SalGroup sal_group(int g, int Gseg, int d_h) {
   return o;
 }
 
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk, const T *wv, const T *norm_w,
                                                         const float *x, int d, int n_heads, int d_h, int m_valid,
                                                         float eps, float theta, const int32_t *sal_len, int max_kv,
                                                         T *kv_stage, float *qbuf, uint32_t *dev_status, int row0, int R,
                                                         const int32_t *n_valid) {
-  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -470,10 +469,9 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
 // K4: SwiGLU front half: act[m][j] = SiLU(W_gate[j] . n) * (W_up[j] . n), n = RMSNorm(x).
 // A wave step handles gate rows j, j+1 and up rows j, j+1.
 // =====================================================================================================
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T *w_up, const T *norm_w, const float *x,
                                                         int d, int f, int m_valid, float eps, float *act) {
-  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -517,10 +515,9 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
 // Hp[b, k, n] = src[b][n] + SiLU(W_k[n] . src[b]) + PE[k][n].  Rows m are batch elements.
 // Both sources sit in LDS; a workgroup handles groups of one head at a time.
 // =====================================================================================================
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T *pe, const float *h1, const float *h2,
                                                          int d, int K, int m_valid, float *Hp) {
-  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
@@ -577,10 +574,9 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
 // =====================================================================================================
 constexpr int LMTK_NPT = 4;                      // logits per lane in the selection: a workgroup owns at most 256 rows
 
-template <typename T, int M>
+template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, int Kd, const float *x, int m_valid, int Gp,
                                                             int k, float *logits, float *cand_v, int *cand_i) {
-  constexpr bool PIPE = GvPipe<M>::on;
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int nC = (Kd + CH - 1) / CH;
@@ -633,8 +629,14 @@ __global__ __launch_bounds__(GV_THREADS) void k_lmhead_topk(const T *W, int V, i
 }
 
 // ---- host launchers ---------------------------------------------------------------------------------
-static inline int gv_grid(int groups, int cap = 1024) {
-  int g = (groups + 3) / 4;
+// Workgroups of a launch over `groups` row groups: one wave per group until the chip is full, i.e. at most as many
+// workgroups as stay resident at once with `smem` bytes of LDS each (at most four per compute unit).  Beyond that
+// the waves walk several groups each: a second round of workgroups would stage the activation rows again (with 80 KB
+// of rows, four rounds read more activations than weights) and leave nothing to request ahead.
+static inline int gv_grid(int groups, size_t smem) {
+  int per_cu = (int)((160 * 1024) / (smem < 1 ? 1 : smem));
+  per_cu = per_cu < 1 ? 1 : (per_cu > 4 ? 4 : per_cu);
+  const int g = (groups + 3) / 4, cap = 256 * per_cu;
   return g < 1 ? 1 : (g > cap ? cap : g);
 }
 template <typename T> static inline size_t gv_xs_bytes(int M, int Kd) {
@@ -642,10 +644,28 @@ template <typename T> static inline size_t gv_xs_bytes(int M, int Kd) {
   return (size_t)M * ((Kd + CH - 1) / CH) * CH * sizeof(float);
 }
 
-// Two batches of fragments per wave (see GvPipe): always from five rows on; for fewer rows where the matrix has so
-// few row groups that a compute unit gets one workgroup, whose four waves would otherwise each wait out every
-// round trip with nothing else to run.
-static inline bool gv_pipe(int mm, int grid) { return mm >= 5 || grid <= 256; }
+// Two batches of fragments per wave (see GvPipe): always from five rows on; for fewer rows where a compute unit gets
+// a single workgroup, whose four waves would otherwise each wait out every round trip with nothing else to run:
+// because the matrix has so few row groups, or because the rows of a wide model fill more than half the LDS.
+static inline bool gv_pipe(int mm, int grid, size_t smem) {
+  return mm >= 5 || grid <= 256 || 2 * smem > 160 * 1024;
+}
+
+// launch KERN<T, MM, pipelined or not> (MM, e, st from the enclosing launcher)
+#define GV_LAUNCH(KERN, GRID, SM, ...)                                                                      \
+  do {                                                                                                      \
+    const int grid_ = (GRID);                                                                               \
+    const size_t sm_ = (SM);                                                                                \
+    if (gv_pipe(MM, grid_, sm_)) {                                                                          \
+      e = gv_set_smem<T>(KERN<T, MM, true>, sm_);                                                           \
+      if (e != hipSuccess) return e;                                                                        \
+      hipLaunchKernelGGL((KERN<T, MM, true>), dim3(grid_), dim3(GV_THREADS), sm_, st, __VA_ARGS__);         \
+    } else if constexpr (!GvPipe<MM>::on) {                                                                 \
+      e = gv_set_smem<T>(KERN<T, MM, false>, sm_);                                                          \
+      if (e != hipSuccess) return e;                                                                        \
+      hipLaunchKernelGGL((KERN<T, MM, false>), dim3(grid_), dim3(GV_THREADS), sm_, st, __VA_ARGS__);        \
+    }                                                                                                       \
+  } while (0)
 
 #define GV_DISPATCH_M(Mv, BODY)                                   \
   switch (Mv) {                                                    \
@@ -688,18 +708,8 @@ hipError_t launch_fc_concat(hipStream_t st, const void *W, const float *u, const
       hipError_t e = hipSuccess;
       GV_DISPATCH_M(m, {
         const size_t sm = gv_xs_bytes<T>(MM, halves ? d : 2 * d);
-        const int grid = gv_grid((d + 3) / 4);
-        if (gv_pipe(MM, grid)) {
-          e = gv_set_smem<T>(k_fc_concat<T, MM, true>, sm);
-          if (e != hipSuccess) return e;
-          hipLaunchKernelGGL((k_fc_concat<T, MM, true>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)W, u + (size_t)m0 * d,
-                             (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status, half);
-        } else {
-          e = gv_set_smem<T>(k_fc_concat<T, MM, false>, sm);
-          if (e != hipSuccess) return e;
-          hipLaunchKernelGGL((k_fc_concat<T, MM, false>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)W, u + (size_t)m0 * d,
-                             (const T *)embed, tok + m0, vocab, d, m, out + (size_t)m0 * d, dev_status, half);
-        }
+        GV_LAUNCH(k_fc_concat, gv_grid((d + 3) / 4, sm), sm, (const T *)W, u + (size_t)m0 * d, (const T *)embed, tok + m0, vocab, d, m,
+                  out + (size_t)m0 * d, dev_status, half);
       });
     }
   }
@@ -718,11 +728,9 @@ hipError_t launch_sal_qkv(hipStream_t st, const amph_layer_w &lw, const float *x
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
-      e = gv_set_smem<T>(k_sal_qkv<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_sal_qkv<T, MM>), dim3(gv_grid(3 * d / 4)), dim3(GV_THREADS), sm, st, (const T *)lw.wq,
-                         (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1, x + (size_t)m0 * d, d, n_heads, d_h, m, eps,
-                         theta, sal_len, max_kv, (T *)kv_stage, qbuf + (size_t)m0 * d, dev_status, m0, R, n_valid);
+      GV_LAUNCH(k_sal_qkv, gv_grid(3 * d / 4, sm), sm, (const T *)lw.wq, (const T *)lw.wk, (const T *)lw.wv, (const T *)lw.rms1,
+                x + (size_t)m0 * d, d, n_heads, d_h, m, eps, theta, sal_len, max_kv, (T *)kv_stage, qbuf + (size_t)m0 * d,
+                dev_status, m0, R, n_valid);
     });
   }
   return hipGetLastError();
@@ -740,20 +748,9 @@ hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const v
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = gv_xs_bytes<T>(MM, Kd);
-      const int grid = gv_grid(n_seg * ((seg_rows + 3) / 4));
-      if (gv_pipe(MM, grid)) {
-        e = gv_set_smem<T>(k_linear<T, MM, true>, sm);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((k_linear<T, MM, true>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)w0, (const T *)w1,
-                           (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo,
-                           o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
-      } else {
-        e = gv_set_smem<T>(k_linear<T, MM, false>, sm);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((k_linear<T, MM, false>), dim3(grid), dim3(GV_THREADS), sm, st, (const T *)w0, (const T *)w1,
-                           (const T *)w2, n_seg, seg_rows, Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo,
-                           o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo);
-      }
+      GV_LAUNCH(k_linear, gv_grid(n_seg * ((seg_rows + 3) / 4), sm), sm, (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows,
+                Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo, o1 ? o1 + oo : nullptr,
+                o2 ? o2 + oo : nullptr, ldo);
     });
   }
   return hipGetLastError();
@@ -770,10 +767,8 @@ hipError_t launch_gate_up(hipStream_t st, const amph_layer_w &lw, const float *x
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = gv_xs_bytes<T>(MM, d) + 16;
-      e = gv_set_smem<T>(k_gate_up<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_gate_up<T, MM>), dim3(gv_grid((f + 1) / 2)), dim3(GV_THREADS), sm, st, (const T *)lw.w_gate,
-                         (const T *)lw.w_up, (const T *)lw.rms2, x + (size_t)m0 * d, d, f, m, eps, act + (size_t)m0 * f);
+      GV_LAUNCH(k_gate_up, gv_grid((f + 1) / 2, sm), sm, (const T *)lw.w_gate, (const T *)lw.w_up, (const T *)lw.rms2,
+                x + (size_t)m0 * d, d, f, m, eps, act + (size_t)m0 * f);
     });
   }
   return hipGetLastError();
@@ -790,10 +785,8 @@ hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, co
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = 2 * gv_xs_bytes<T>(MM, d);
-      e = gv_set_smem<T>(k_head_mlp<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_head_mlp<T, MM>), dim3(gv_grid(K * ((d + 3) / 4))), dim3(GV_THREADS), sm, st, (const T *)w_mlp,
-                         (const T *)pe, h1 + (size_t)m0 * d, h2 + (size_t)m0 * d, d, K, m, Hp + (size_t)m0 * K * d);
+      GV_LAUNCH(k_head_mlp, gv_grid(K * ((d + 3) / 4), sm), sm, (const T *)w_mlp, (const T *)pe, h1 + (size_t)m0 * d,
+                h2 + (size_t)m0 * d, d, K, m, Hp + (size_t)m0 * K * d);
     });
   }
   return hipGetLastError();
@@ -829,10 +822,8 @@ hipError_t launch_lmhead_cands(hipStream_t st, const void *W, int V, int Kd, con
     hipError_t e = hipSuccess;
     GV_DISPATCH_M(m, {
       const size_t sm = gv_xs_bytes<T>(MM, Kd) + (size_t)MM * Gp * GV_R * sizeof(float);
-      e = gv_set_smem<T>(k_lmhead_topk<T, MM>, sm);
-      if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((k_lmhead_topk<T, MM>), dim3(n_wg), dim3(GV_THREADS), sm, st, (const T *)W, V, Kd, x + (size_t)m0 * Kd, m, Gp,
-                         k, logits ? logits + (size_t)m0 * V : nullptr, cand_v + (size_t)m0 * n_wg * k, cand_i + (size_t)m0 * n_wg * k);
+      GV_LAUNCH(k_lmhead_topk, n_wg, sm, (const T *)W, V, Kd, x + (size_t)m0 * Kd, m, Gp, k,
+                logits ? logits + (size_t)m0 * V : nullptr, cand_v + (size_t)m0 * n_wg * k, cand_i + (size_t)m0 * n_wg * k);
     });
   }
   *n_cand = n_wg * k;
