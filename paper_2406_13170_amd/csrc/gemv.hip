@@ -419,11 +419,14 @@ __global__ __launch_bounds__(GV_THREADS) void k_sal_qkv(const T *wq, const T *wk
 // =====================================================================================================
 // K3: generic linear with up to three stacked matrices of `seg_rows` rows each (AEB q/k/v, Wo, W_down,
 // LM head).  out_s[m][n] = (res ? res[m][n] : 0) + sum_k x[m][k] W_s[n][k].  x float32 [M, Kd].
+// A launch may cover a slice of the reduction axis only (Kd = its length, ldw = the length of a weight row, the
+// pointers already at the slice): with add_out it adds its sums to what out_s holds, so that consecutive launches
+// over consecutive slices build the product of rows too wide to sit in LDS whole while reading the matrix once.
 // =====================================================================================================
 template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1, const T *w2, int n_seg, int seg_rows,
                                                        int Kd, const float *x, int ldx, int m_valid, const float *res,
-                                                       float *o0, float *o1, float *o2, int ldo) {
+                                                       float *o0, float *o1, float *o2, int ldo, int ldw, int add_out) {
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int nC = (Kd + CH - 1) / CH;
@@ -438,7 +441,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
     const int seg = g / Gseg, gl = g % Gseg;
     const T *Wm = pick3(seg, w0, w1, w2);
     #pragma unroll
-    for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * Kd;
+    for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, seg_rows - 1) * ldw;
   };
   GvFrags<T, PIPE> fr;
   const T *rows[GV_R];
@@ -459,6 +462,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_linear(const T *w0, const T *w1,
       float v = acc_at<M>(acc, r, m);
       if (m < m_valid && n < seg_rows) {
         if (res) v += res[(size_t)m * ldo + n];
+        if (add_out) v += om[(size_t)m * ldo + n];
         om[(size_t)m * ldo + n] = v;
       }
     }
@@ -740,18 +744,32 @@ template <typename T>
 hipError_t launch_linear(hipStream_t st, const void *w0, const void *w1, const void *w2, int n_seg, int seg_rows, int Kd,
                          const float *x, int ldx, int M, const float *res, float *o0, float *o1, float *o2, int ldo) {
   if (M < 1 || Kd % 8) return hipErrorInvalidValue;
-  const int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd), 0);
+  int mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd), 0);
+  // Rows too wide for all of them (up to 8) to sit in LDS whole: cut the reduction axis into ks slices instead of
+  // the rows into more launches, each of which would read the matrix again.
+  const int want = std::min(M, 8);
+  int ks = 1;
+  if (mc < want) {
+    for (int c = 2; c <= 8; c *= 2)
+      if (Kd % (8 * c) == 0 && gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd / c), 0) >= want) { ks = c; break; }
+    if (ks > 1) mc = gv_rows_per_launch(M, gv_xs_bytes<T>(1, Kd / ks), 0);
+  }
   if (mc < 1) return hipErrorInvalidValue;
+  const int Kq = Kd / ks;
   for (int m0 = 0; m0 < M; m0 += mc) {
     const int m = std::min(mc, M - m0);
     const size_t oo = (size_t)m0 * ldo;
-    hipError_t e = hipSuccess;
-    GV_DISPATCH_M(m, {
-      const size_t sm = gv_xs_bytes<T>(MM, Kd);
-      GV_LAUNCH(k_linear, gv_grid(n_seg * ((seg_rows + 3) / 4), sm), sm, (const T *)w0, (const T *)w1, (const T *)w2, n_seg, seg_rows,
-                Kd, x + (size_t)m0 * ldx, ldx, m, res ? res + oo : nullptr, o0 + oo, o1 ? o1 + oo : nullptr,
-                o2 ? o2 + oo : nullptr, ldo);
-    });
+    for (int kq = 0; kq < ks; ++kq) {
+      const size_t ko = (size_t)kq * Kq;
+      hipError_t e = hipSuccess;
+      GV_DISPATCH_M(m, {
+        const size_t sm = gv_xs_bytes<T>(MM, Kq);
+        GV_LAUNCH(k_linear, gv_grid(n_seg * ((seg_rows + 3) / 4), sm), sm, (const T *)w0 + ko, w1 ? (const T *)w1 + ko : nullptr,
+                  w2 ? (const T *)w2 + ko : nullptr, n_seg, seg_rows, Kq, x + (size_t)m0 * ldx + ko, ldx, m,
+                  (res && kq == 0) ? res + oo : nullptr, o0 + oo, o1 ? o1 + oo : nullptr, o2 ? o2 + oo : nullptr, ldo, Kd,
+                  kq > 0 ? 1 : 0);
+      });
+    }
   }
   return hipGetLastError();
 }

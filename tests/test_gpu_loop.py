@@ -74,10 +74,12 @@ def test_commit_moves_the_accepted_rows_and_gathers_the_next_draft_inputs(cfg, T
 # five concatenated [h ; e] rows of this width do not fit in LDS as float32: Eq. 1's product then runs as two launches
 # over half the columns each
 WIDE_FC = si.with_(si.MINI, name="mini_wide_fc", d_model=3584, n_heads=28, d_ffn=512, vocab=512)
+# five rows of this FFN width do not fit in LDS either: W_down's product runs as launches over slices of its columns
+WIDE_FFN = si.with_(si.MINI, name="mini_wide_ffn", d_ffn=8192)
 
 
 @pytest.mark.parametrize("cfg,n_rows,n_live", [(si.TINY, 5, 5), (si.TINY, 5, 2), (si.MINI, 5, 3), (si.MINI, 3, 1),
-                                               (WIDE_FC, 5, 4)])
+                                               (WIDE_FC, 5, 4), (WIDE_FFN, 5, 5)])
 def test_draft_catches_up_over_new_positions(cfg, n_rows, n_live):
     """h_new carries n_rows positions of which the first n_live count (n_valid on the device)."""
     say(f"draft catch-up {cfg.name} rows={n_rows} live={n_live}")
