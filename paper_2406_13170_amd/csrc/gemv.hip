@@ -521,21 +521,24 @@ __global__ __launch_bounds__(GV_THREADS) void k_gate_up(const T *w_gate, const T
 // =====================================================================================================
 template <typename T, int M, bool PIPE>
 __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T *pe, const float *h1, const float *h2,
-                                                         int d, int K, int m_valid, float *Hp) {
+                                                         int d, int K, int m_valid, float *Hp, int k0, int nk) {
+  // this launch serves heads k0 .. k0 + nk - 1; only the sources they read are staged (a launch over the heads of one
+  // source needs half the LDS, which is what lets all rows of a wide model share one pass over the matrices)
   extern __shared__ __align__(16) float smem[];
   constexpr int CH = XLayout<T>::CH;
   const int Kd = d, nC = (Kd + CH - 1) / CH;
+  const bool use1 = k0 < K / 2, use2 = k0 + nk > K / 2;
   float *xs1 = smem;
-  float *xs2 = smem + (size_t)M * nC * CH;
-  load_x_plain<T, M>(xs1, h1, d, m_valid, Kd, nC);
-  load_x_plain<T, M>(xs2, h2, d, m_valid, Kd, nC);
+  float *xs2 = use1 ? smem + (size_t)M * nC * CH : smem;
+  if (use1) load_x_plain<T, M>(xs1, h1, d, m_valid, Kd, nC);
+  if (use2) load_x_plain<T, M>(xs2, h2, d, m_valid, Kd, nC);
   __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int Gseg = (d + GV_R - 1) / GV_R;
-  const int G = K * Gseg;
+  const int G = nk * Gseg;
   const int g_first = blockIdx.x * 4 + wave, g_step = gridDim.x * 4;
   auto set_rows = [&](int g, const T *(&rw)[GV_R]) {
-    const int k = g / Gseg, gl = g % Gseg;
+    const int k = k0 + g / Gseg, gl = g % Gseg;
     const T *Wm = w_mlp + (size_t)k * d * d;
     #pragma unroll
     for (int r = 0; r < GV_R; ++r) rw[r] = Wm + (size_t)min(gl * GV_R + r, d - 1) * Kd;
@@ -545,7 +548,7 @@ __global__ __launch_bounds__(GV_THREADS) void k_head_mlp(const T *w_mlp, const T
   set_rows(min(g_first, G - 1), rows);
   gemv_begin<T, PIPE>(rows, Kd, fr);
   for (int g = g_first; g < G; g += g_step) {
-    const int k = g / Gseg, gl = g % Gseg;
+    const int k = k0 + g / Gseg, gl = g % Gseg;
     const bool first = (k < K / 2);
     const float *xs = first ? xs1 : xs2;
     const float *src = first ? h1 : h2;
@@ -796,16 +799,24 @@ template <typename T>
 hipError_t launch_head_mlp(hipStream_t st, const void *w_mlp, const void *pe, const float *h1, const float *h2, int d,
                            int K, int M, float *Hp) {
   if (M < 1 || d % 8) return hipErrorInvalidValue;
-  const int mc = gv_rows_per_launch(M, 2 * gv_xs_bytes<T>(1, d), 0);
+  int mc = gv_rows_per_launch(M, 2 * gv_xs_bytes<T>(1, d), 0);
+  // rows that fit only with one of the two sources staged: one launch for the heads of each source
+  const int mch = gv_rows_per_launch(M, gv_xs_bytes<T>(1, d), 0);
+  const bool by_source = mc < M && mch > mc && K / 2 > 0;
+  if (by_source) mc = mch;
   if (mc < 1) return hipErrorInvalidValue;
   for (int m0 = 0; m0 < M; m0 += mc) {
     const int m = std::min(mc, M - m0);
-    hipError_t e = hipSuccess;
-    GV_DISPATCH_M(m, {
-      const size_t sm = 2 * gv_xs_bytes<T>(MM, d);
-      GV_LAUNCH(k_head_mlp, gv_grid(K * ((d + 3) / 4), sm), sm, (const T *)w_mlp, (const T *)pe, h1 + (size_t)m0 * d,
-                h2 + (size_t)m0 * d, d, K, m, Hp + (size_t)m0 * K * d);
-    });
+    for (int part = 0; part < (by_source ? 2 : 1); ++part) {
+      const int k0 = (by_source && part == 1) ? K / 2 : 0;
+      const int nk = !by_source ? K : (part == 0 ? K / 2 : K - K / 2);
+      hipError_t e = hipSuccess;
+      GV_DISPATCH_M(m, {
+        const size_t sm = (by_source ? 1 : 2) * gv_xs_bytes<T>(MM, d);
+        GV_LAUNCH(k_head_mlp, gv_grid(nk * ((d + 3) / 4), sm), sm, (const T *)w_mlp, (const T *)pe, h1 + (size_t)m0 * d,
+                  h2 + (size_t)m0 * d, d, K, m, Hp + (size_t)m0 * K * d, k0, nk);
+      });
+    }
   }
   return hipGetLastError();
 }
