@@ -130,8 +130,9 @@ amph_status amph_device_status(amph_ctx *ctx, uint32_t *host_bits);
  * adaptation layers first catch up over the a + 1 new positions, oldest first (each row attends to the
  * cache and to the new rows before it); the heads read the LAST live position.
  *   h_new    [B, n_new, d] float32     tok_new [B, n_new] int32 (the token that follows each position)
- *            1 <= n_new <= K + 1.  The adaptation layers' weight-streaming kernels take 8 rows at a time: a
- *            call with B * n_new > 8 streams their weights ceil(B * n_new / 8) times.
+ *            1 <= n_new <= K + 1.  The adaptation layers' weight-streaming kernels take 8 rows at a time (fewer
+ *            where 8 float32 rows of the model width do not fit in 128 KB of LDS and the kernel has a fused
+ *            epilogue): a call with B * n_new > 8 streams their weights ceil(B * n_new / 8) times or more.
  *   n_valid  [B] int32 on the device or NULL: positions j >= n_valid[b] of element b are ignored (no
  *            cache row, no effect on the heads); NULL = all n_new live.  amph_commit writes such a triple.
  *   sal_kv   [2 stages, B, 2 (K then V), n_heads, max_kv, head_dim] T; rows sal_len[b] + j of both stages
