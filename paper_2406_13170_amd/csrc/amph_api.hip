@@ -197,20 +197,32 @@ amph_status draft_impl(amph_ctx *ctx, const amph_draft_w *w, const float *h_new,
     PROF_TRY(ctx, AMPH_K_FC, launch_fc_concat<T>(st, w->fc[s], u, w->embed, tok_new, V, d, M, x, ctx->dev_status));
     PROF_TRY(ctx, AMPH_K_SAL_QKV, launch_sal_qkv<T>(st, w->sal[s], x, d, n_h, d_h, M, c.rms_eps, c.rope_theta, sal_len, c.max_kv, kv_stage,
                                    q, ctx->dev_status, R, n_valid));
-    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, att, R, n_valid));
-    PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, M, x, y, nullptr, nullptr, d));
-    PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, M, c.rms_eps, act));
-    PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, M, y, h[s], nullptr, nullptr, d));
+    // Nothing reads the LAST stage's output at any but the last live position of a sequence (the heads read that one;
+    // the earlier positions only have to leave their cache rows, which the projections above wrote): there the
+    // attention, Wo and the FFN run over one row per sequence instead of R.
+    const bool last_rows_only = (R > 1 && s == c.n_stages - 1);
+    const int Ms = last_rows_only ? B : M;
+    const float *res = x;
+    if (last_rows_only) {
+      float *x_last = att + (size_t)B * d;        // att holds B * (K + 1) rows and the attention now fills the first B only
+      HIP_TRY(ctx, launch_gather_rows(st, x, B, R, d, n_valid, x_last));
+      res = x_last;
+    }
+    PROF_TRY(ctx, AMPH_K_SAL_ATTN, launch_sal_attn<T>(st, q, kv_stage, sal_len, B, n_h, d_h, c.max_kv, att, R, n_valid,
+                                                      last_rows_only ? 1 : 0));
+    PROF_TRY(ctx, AMPH_K_SAL_WO, launch_linear<T>(st, w->sal[s].wo, nullptr, nullptr, 1, d, d, att, d, Ms, res, y, nullptr, nullptr, d));
+    PROF_TRY(ctx, AMPH_K_SAL_GATEUP, launch_gate_up<T>(st, w->sal[s], y, d, f, Ms, c.rms_eps, act));
+    PROF_TRY(ctx, AMPH_K_SAL_DOWN, launch_linear<T>(st, w->sal[s].w_down, nullptr, nullptr, 1, d, f, act, f, Ms, y, h[s], nullptr, nullptr, d));
   }
   // the heads (Eq. 2-6) read the last live position of every batch element; with one adaptation layer every
-  // head reads that layer's output
+  // head reads that layer's output.  After a catch-up the last stage's output already is one row per sequence.
   const float *h1 = h[0], *h2 = h[c.n_stages - 1];
   if (R > 1) {
-    HIP_TRY(ctx, launch_gather_rows(st, h[0], B, R, d, n_valid, x));
-    h1 = h2 = x;
     if (c.n_stages == 2) {
-      HIP_TRY(ctx, launch_gather_rows(st, h[1], B, R, d, n_valid, y));
-      h2 = y;
+      HIP_TRY(ctx, launch_gather_rows(st, h[0], B, R, d, n_valid, x));
+      h1 = x;
+    } else {
+      h1 = h2;
     }
   }
   float *Hp = F(ctx->ws.Hp), *Qa = F(ctx->ws.Qa), *Ka = F(ctx->ws.Ka), *Va = F(ctx->ws.Va), *ctxa = F(ctx->ws.ctxa);

@@ -37,7 +37,7 @@ hipError_t launch_lmhead_cands(hipStream_t st, const void *W, int V, int Kd, con
 // ---- small.hip (attention of the draft path, top-k, tree, accept, norms) ----
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid);
+                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid, int last_only = 0);
 hipError_t launch_aeb_attn(hipStream_t st, const float *Q, const float *Kk, const float *V, int B, int K, int n_heads,
                            int d_h, float *ctx);
 // ws: topk_ws_floats(rows, V, k) floats of scratch for the per-wave candidates

@@ -20,14 +20,25 @@ constexpr int SA_WAVES = 16;
 template <typename T, int DH>
 __global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, const T *kv_stage, const int32_t *sal_len,
                                                             int n_heads, int max_kv, float *out, int R,
-                                                            const int32_t *n_valid) {
+                                                            const int32_t *n_valid, int last_only) {
   constexpr int PER = Elem<T>::PER;
   constexpr int LPR = DH / PER;          // lanes per row
   constexpr int G = WAVE / LPR;          // rows per wave load
   constexpr int U = 4;
   __shared__ float sm_m[SA_WAVES], sm_l[SA_WAVES];
   __shared__ float sm_o[SA_WAVES][DH];
-  const int row = blockIdx.y, b = row / R, jn = row % R, h = blockIdx.x;
+  // last_only: one workgroup row per batch element, serving its last live position (query row b * R + jn of qbuf,
+  // output row b); otherwise one per (element, position)
+  const int h = blockIdx.x;
+  int row = blockIdx.y, b, jn, out_row;
+  if (last_only) {
+    b = row;
+    jn = min(max(n_valid ? n_valid[b] : R, 1), R) - 1;
+    out_row = b;
+    row = b * R + jn;
+  } else {
+    b = row / R; jn = row % R; out_row = row;
+  }
   const int d = n_heads * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int grp = lane / LPR, li = lane % LPR;
@@ -104,28 +115,28 @@ __global__ __launch_bounds__(SA_WAVES * 64) void k_sal_attn(const float *qbuf, c
       lw += sm_l[w] * f;
       ow += sm_o[w][threadIdx.x] * f;
     }
-    out[(size_t)row * d + h * DH + threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
+    out[(size_t)out_row * d + h * DH + threadIdx.x] = (lw > 0.f) ? ow / lw : 0.f;
   }
 }
 
 template <typename T>
 hipError_t launch_sal_attn(hipStream_t st, const float *qbuf, const void *kv_stage, const int32_t *sal_len, int B,
-                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid) {
-  const dim3 grid(n_heads, B * R), block(SA_WAVES * 64);
+                           int n_heads, int d_h, int max_kv, float *out, int R, const int32_t *n_valid, int last_only) {
+  const dim3 grid(n_heads, last_only ? B : B * R), block(SA_WAVES * 64);
   if (d_h == 64)
     hipLaunchKernelGGL((k_sal_attn<T, 64>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out, R,
-                       n_valid);
+                       n_valid, last_only);
   else if (d_h == 128)
     hipLaunchKernelGGL((k_sal_attn<T, 128>), grid, block, 0, st, qbuf, (const T *)kv_stage, sal_len, n_heads, max_kv, out, R,
-                       n_valid);
+                       n_valid, last_only);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
 }
 template hipError_t launch_sal_attn<float>(hipStream_t, const float *, const void *, const int32_t *, int, int, int, int,
-                                           float *, int, const int32_t *);
+                                           float *, int, const int32_t *, int);
 template hipError_t launch_sal_attn<bf16_t>(hipStream_t, const float *, const void *, const int32_t *, int, int, int,
-                                            int, float *, int, const int32_t *);
+                                            int, float *, int, const int32_t *, int);
 
 // =====================================================================================================
 // Eq. 5 core: for one (batch, head) the K x K score matrix of the K head positions, a row softmax
