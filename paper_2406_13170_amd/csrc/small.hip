@@ -365,8 +365,19 @@ hipError_t launch_topk_merge(hipStream_t st, const float *cand_v, const int *can
   if (rows < 1 || n_cand < 1 || k < 1 || k > AMPH_MAX_TOPK || n_cand > 16 * 1024) return hipErrorInvalidValue;
   #define TM_LAUNCH(N) hipLaunchKernelGGL((k_topk_merge<N>), dim3(rows), dim3(1024), 0, st, cand_v, cand_i, n_cand, V, k, idx, val, \
                                           advance, n_advance, advance_by, advance_each, advance_limit)
-  if (n_cand <= 1024) TM_LAUNCH(1); else if (n_cand <= 2048) TM_LAUNCH(2); else if (n_cand <= 4096) TM_LAUNCH(4);
-  else if (n_cand <= 8192) TM_LAUNCH(8); else TM_LAUNCH(16);
+  // as few candidates per lane as cover the row: a selection round rescans a lane's candidates, and with ten rounds
+  // that is most of the kernel (5000 candidates: 8 per lane 16.4 us, 5 per lane 14.9; half the waves with 10 per lane
+  // 15.6, a quarter with 20 per lane 26.6)
+  switch ((n_cand + 1023) / 1024) {
+    case 1: TM_LAUNCH(1); break;
+    case 2: TM_LAUNCH(2); break;
+    case 3: TM_LAUNCH(3); break;
+    case 4: TM_LAUNCH(4); break;
+    case 5: TM_LAUNCH(5); break;
+    case 6: TM_LAUNCH(6); break;
+    case 7: case 8: TM_LAUNCH(8); break;
+    default: TM_LAUNCH(16); break;
+  }
   #undef TM_LAUNCH
   return hipGetLastError();
 }
