@@ -166,6 +166,10 @@ def test_draft_vicuna7b_shape():
     say("draft vicuna7b")
     cfgx, ctx, outs, got = run_draft(si.V7B)
     check_draft(cfgx, outs, got)
+    # the same call again (fresh context and caches): the same bits
+    got2 = run_draft(si.V7B)[3]
+    assert np.array_equal(got["logits"], got2["logits"]) and np.array_equal(got["topk_idx"], got2["topk_idx"])
+    assert np.array_equal(got["topk_val"], got2["topk_val"])
 
 
 def test_draft_vicuna13b_shape():
@@ -361,6 +365,22 @@ def test_target_forward_batches_on_tiled_weights(cfg, n_layers, T, caps, L, Bsz)
     say("  row-major weights")
     cfgx, refs, got, _ = run_target(cfg, n_layers, T, caps, L, Bsz=Bsz, tiled=False)
     check_target(cfgx, refs, got)
+
+
+@pytest.mark.parametrize("cfg,n_layers,T,caps,L,Bsz", [(si.MINI, 2, 64, (10,) * 4, 200, 1), (si.V7B, 2, 64, (10,) * 4, 1024, 1),
+                                                       (si.MINI, 2, 64, (10,) * 4, 77, 4)], ids=["mini", "7b", "mini-batch4"])
+def test_target_forward_is_bit_reproducible(cfg, n_layers, T, caps, L, Bsz):
+    """Split reductions are folded in a fixed order and nothing is accumulated with atomics, so two passes over the same
+    inputs (fresh contexts, fresh caches) give the same bits: hidden states, logits, argmax and the tree's K/V rows."""
+    say(f"target_forward twice on {cfg.name}, {n_layers} layers, batch {Bsz}")
+    runs = [run_target(cfg, n_layers, T, caps, L, seed=5, Bsz=Bsz, tiled=True, oracle=False)[2] for _ in range(2)]
+    a, b = runs
+    for key in ("hidden", "logits", "tgt"):
+        assert np.array_equal(a[key], b[key]), key
+    bits = lambda t: t.view(torch.int16 if t.element_size() == 2 else torch.int32)      # compare bits (NaN-safe)
+    rows_a, rows_b = D.unpack_kv(a["ctx"], a["k_caches"], a["v_caches"]), D.unpack_kv(b["ctx"], b["k_caches"], b["v_caches"])
+    for ra, rb, name in zip(rows_a, rows_b, ("keys", "values")):
+        assert torch.equal(bits(ra[:, :, :, :L + T]), bits(rb[:, :, :, :L + T])), name
 
 
 @pytest.mark.parametrize("tiled_keys", [("qkv",), ("wo", "down"), ("gate_up",), ("qkv", "gate_up", "down")])
